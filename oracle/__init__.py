@@ -1,0 +1,30 @@
+"""CPU oracle for the draft-verify step (TEST INFRASTRUCTURE ONLY).
+
+A plain, slow, obviously-correct numpy implementation of what the GPU library
+computes: a decoder-only transformer forward pass over a KV cache (chunked
+prefill and k-draft verification) and the lossless acceptance rules.  It exists
+to check the HIP kernels and is never on the product path: only the tests, the
+smoke check and the CPU-baseline leg of the benchmark may import it.  It shares
+no code with the GPU library and imports nothing from it.
+
+Paper anchors (section / table):
+  * draft-then-verify, "only correct tokens are accepted and any tokens after
+    the first mismatch are discarded"  -- Sec. 3, "NPU-only decoding ..."
+  * x = [T, x_1..x_n], predictions y = [y_1..y_{n+1}], accepted prefix
+    x_1..x_{e-1}, y_e                       -- Sec. 4.3, empirical analysis
+  * fixed-size chunked prefill              -- Sec. 2 / Sec. 4.1
+  * "executing the short graph several times equals one long execution"
+                                            -- Sec. 4.1 (equivalence insight)
+
+Parity pins (tests/test_oracle_*.py): every public function here is pinned by
+invariants, closed forms, brute force on a tiny vocabulary and a library
+cross-check; none is "parity unpinned".
+"""
+from .numfmt import round_bf16
+from .transformer import ModelSpec, Weights, KVCache, forward, prefill, verify
+from .acceptance import greedy_accept, stochastic_accept, first_token
+
+__all__ = [
+    "round_bf16", "ModelSpec", "Weights", "KVCache", "forward", "prefill",
+    "verify", "greedy_accept", "stochastic_accept", "first_token",
+]
