@@ -1,0 +1,203 @@
+/*
+ * vf.h -- C ABI of the draft-verify library for AMD MI355X (gfx950).
+ *
+ * What it computes.  A small decoder-only language model (RMSNorm, rotary
+ * embedding, grouped-query attention, SwiGLU, tied output head) is run over a
+ * KV cache in the two regimes the paper's speculative decoding uses:
+ *
+ *   - chunked prefill: the prompt is fed in fixed-size chunks, each appended to
+ *     the KV cache (paper Sec. 2 "on-device inference", Sec. 4.1);
+ *   - verify: the pending token T and k draft tokens x_1..x_k are scored in ONE
+ *     forward pass, giving predictions y_1..y_{k+1} (paper Sec. 3
+ *     "draft-then-verify", Sec. 4.3 "x = [T, x_1..x_n], y = [y_1..y_{n+1}]");
+ *   - accept: the longest draft prefix that matches the predictions is kept and
+ *     one corrected (or bonus) token is emitted (paper Sec. 3: "any tokens after
+ *     the first mismatch are discarded"; Sec. 4.3: accepted prefix
+ *     x_1..x_{e-1}, y_e).  Greedy (strict) and lossless stochastic
+ *     (speculative sampling, the rule of the work the paper cites for
+ *     "lossless generation quality") are both provided.
+ *
+ * Conventions.
+ *   - Every function returns int: VF_OK or a negative VF_ERR_* code.  Nothing
+ *     throws or aborts.  vf_last_error() gives a thread-local message for the
+ *     last failing call on this thread.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary
+ *     host memory.  The library never allocates device memory: every device
+ *     buffer (raw weights, packed model, KV pool, sequence state, inputs,
+ *     outputs) is owned by the caller and must outlive its use.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *     work is enqueued asynchronously on it; no call synchronises except where
+ *     stated.  Calls that touch the same model or sequence must be issued on
+ *     one stream (or be ordered by the caller).
+ *   - Errors detected on the host (bad arguments, capacity) are reported
+ *     before anything is enqueued and leave all state unchanged.
+ */
+#ifndef VF_H
+#define VF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VF_OK               0
+#define VF_ERR_ARG         (-1)  /* NULL / out-of-range / inconsistent argument            */
+#define VF_ERR_CAP         (-2)  /* KV capacity or workspace rows exceeded; state unchanged */
+#define VF_ERR_HIP         (-3)  /* a HIP runtime call failed                               */
+#define VF_ERR_UNSUPPORTED (-4)  /* shape or dtype the kernels are not built for            */
+
+#define VF_F32   0   /* weights, activations and KV cache in float32                        */
+#define VF_BF16  1   /* bfloat16 weights / activations / KV cache, float32 accumulation     */
+
+#define VF_GREEDY      0
+#define VF_STOCHASTIC  1
+
+#define VF_PENDING   (-1)   /* token id meaning "the sequence's pending token on the device" */
+#define VF_MAX_BATCH   32   /* sequences per vf_verify / vf_accept call                      */
+#define VF_MAX_DRAFTS  32   /* draft tokens per sequence per verify (paper Sec. 5.1: cap 32) */
+
+typedef struct vf_model vf_model;   /* opaque; host struct describing a packed model */
+typedef struct vf_seq   vf_seq;     /* opaque; host struct describing one sequence   */
+
+/* Model shape.  head_dim must be a multiple of 32, at most 128 and even; d_model, d_ffn and
+ * n_q_heads*head_dim multiples of 32; vocab a multiple of 16; n_q_heads a multiple of
+ * n_kv_heads.  max_rows = largest number of token rows one call may process (a prefill
+ * chunk, or the sum over the batch of k_b+1 for a verify).  max_positions = largest position
+ * + 1 any sequence may reach (rotary table size). */
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t dtype;                 /* VF_F32 | VF_BF16 */
+    float   rope_theta, rms_eps;
+    int32_t tie_embeddings;        /* 1: output head = embedding matrix (lm_head ignored) */
+    int32_t qkv_bias;              /* 1: bq/bk/bv are added before the rotary embedding   */
+    int32_t max_rows;
+    int32_t max_positions;
+} vf_config;
+
+/* Raw weights, DEVICE pointers, caller-owned, read only during vf_model_create.
+ * Matrices are row-major [out_features, in_features] in the model dtype (bfloat16 bits or
+ * float32).  Vectors (norm gains, biases) are always float32. */
+typedef struct {
+    const void *attn_norm;                 /* f32 [d_model]                              */
+    const void *wq, *wk, *wv;              /* [Hq*hd, d], [Hkv*hd, d], [Hkv*hd, d]       */
+    const void *bq, *bk, *bv;              /* f32, NULL unless qkv_bias                  */
+    const void *wo;                        /* [d, Hq*hd]                                 */
+    const void *ffn_norm;                  /* f32 [d_model]                              */
+    const void *w_gate, *w_up, *w_down;    /* [F, d], [F, d], [d, F]                     */
+} vf_layer_w;
+
+typedef struct {
+    const void *embed;                     /* [vocab, d]                                 */
+    const void *lm_head;                   /* [vocab, d]; ignored when tie_embeddings    */
+    const void *final_norm;                /* f32 [d]                                    */
+    const vf_layer_w *layers;              /* HOST array of n_layers entries             */
+} vf_weights;
+
+const char *vf_last_error(void);
+
+/* ---- model --------------------------------------------------------------------------------- */
+
+/* Bytes of device memory vf_model_create needs for the re-packed weights, the rotary tables
+ * and the activation workspace.  0 on invalid config (see vf_last_error). */
+size_t vf_model_packed_bytes(const vf_config *cfg);
+
+/* Re-packs the weights into `packed_dev` (packed_bytes >= vf_model_packed_bytes, 256-byte
+ * aligned) on `stream`; the raw weights may be released once the stream has drained.  On
+ * success *out owns only host memory. */
+int vf_model_create(const vf_config *cfg, const vf_weights *w, void *packed_dev,
+                    size_t packed_bytes, void *stream, vf_model **out);
+int vf_model_destroy(vf_model *m);
+
+/* ---- sequences and the KV cache ------------------------------------------------------------ */
+
+/* Bytes of one sequence's device state (current length, pending token). */
+size_t vf_seq_state_bytes(const vf_model *m);
+
+/* Bytes of a KV pool.  page_tokens == 0: a private contiguous cache for `n` tokens (n is
+ * rounded up to a multiple of 64 internally).  page_tokens == 64: a pool of `n` pages shared
+ * by many sequences through their block tables.  Layout inside the pool is private to the
+ * library (K row-major, V transposed in 64-token tiles); use vf_kv_read to inspect it. */
+size_t vf_kv_bytes(const vf_model *m, int page_tokens, int n);
+
+/* Binds a sequence to its KV memory.
+ *   contiguous: page_tokens = 0, block_table_dev = NULL, kv_dev = private buffer of
+ *               vf_kv_bytes(m, 0, capacity_tokens) bytes;
+ *   paged:      page_tokens = 64, kv_dev = the shared pool of pool_pages pages,
+ *               block_table_dev = int32[ceil(capacity_tokens/64)] page ids (device), which
+ *               must stay valid and unchanged while the sequence is in use.
+ * state_dev: vf_seq_state_bytes bytes; initialised (length 0, no pending token) on `stream`. */
+int vf_seq_create(vf_model *m, void *kv_dev, size_t kv_bytes, int page_tokens, int pool_pages,
+                  int capacity_tokens, const int32_t *block_table_dev, void *state_dev,
+                  void *stream, vf_seq **out);
+int vf_seq_destroy(vf_seq *s);
+
+/* Sets the sequence length (positions >= len are dead and will be overwritten): roll-back,
+ * teacher forcing.  Also resets the host-side upper bound of the length. */
+int vf_seq_set_len(vf_seq *s, int len, void *stream);
+/* Sets the pending token T (the last emitted token, not yet in the KV cache). */
+int vf_seq_set_pending(vf_seq *s, int32_t token, void *stream);
+/* Reads length and pending token back (synchronises the stream) and tightens the host-side
+ * upper bound of the length to the true value.  Either output pointer may be NULL. */
+int vf_seq_get_state(vf_seq *s, int32_t *len_host, int32_t *pending_host, void *stream);
+
+/* Debug / test accessor: copies K and V of `layer` for positions [t0, t0+n) into row-major
+ * float32 arrays k_out_dev, v_out_dev of shape [n, n_kv_heads, head_dim]. */
+int vf_kv_read(vf_model *m, vf_seq *s, int layer, int t0, int n, float *k_out_dev,
+               float *v_out_dev, void *stream);
+
+/* ---- the three operations ------------------------------------------------------------------ */
+
+/* Chunked prefill (paper Sec. 2, Sec. 4.1): runs n_tokens ids (tokens_dev, int32) at
+ * positions len..len+n_tokens-1, appends their K/V, and advances the length.
+ *   logits_mode 0: no logits returned; 1: float32 logits of the last row to
+ *   logits_out_dev[vocab]; 2: of all rows to logits_out_dev[n_tokens, vocab] (the all-position
+ *   logits the paper's calibration step consumes, Sec. 4.2).
+ *   sample_first != 0: the last row also produces the pending token T: arg-max when
+ *   temperature == 0, else an inverse-CDF sample of softmax(z/temperature) with the uniform
+ *   u_dev[0] (float32 in [0,1), device).
+ * n_tokens <= cfg.max_rows; VF_ERR_CAP if the cache cannot take n_tokens more rows. */
+int vf_prefill_chunk(vf_model *m, vf_seq *s, const int32_t *tokens_dev, int n_tokens,
+                     int logits_mode, float *logits_out_dev, int sample_first,
+                     const float *u_dev, float temperature, void *stream);
+
+/* Verify forward (paper Sec. 3, Sec. 4.3) for a ragged batch.  row_off_host[0..n_seqs] are
+ * prefix sums of the per-sequence row counts m_b = k_b + 1 (1 <= m_b <= VF_MAX_DRAFTS+1).
+ * tokens_dev[row_off[b]] is sequence b's pending token (or VF_PENDING to take it from the
+ * device state), followed by its k_b drafts.  Rows sit at positions len_b .. len_b + k_b.
+ * Writes K/V for all rows (the length is NOT advanced: vf_accept commits it) and leaves the
+ * float32 logits of all rows for vf_accept: in logits_out_dev[total_rows, vocab] if that is
+ * not NULL, else in the model workspace.
+ * VF_ERR_CAP if a cache cannot take m_b more rows or total rows exceed cfg.max_rows. */
+int vf_verify(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+              const int32_t *row_off_host, float *logits_out_dev, void *stream);
+
+typedef struct {
+    int32_t mode;            /* VF_GREEDY | VF_STOCHASTIC                                    */
+    float   temperature;     /* stochastic: target logits are divided by it (> 0)             */
+    const float *q_dev;      /* stochastic: draft distributions [k_b, vocab] (rows sum to 1), */
+                             /* or NULL for a deterministic drafter (one-hot at each draft)   */
+    const float *u_dev;      /* stochastic: 2*(k_b+1) uniforms in [0,1): u[i] decides draft   */
+                             /* i+1, u[k_b+1+i] drives the replacement/bonus draw at row i    */
+} vf_accept_params;
+
+/* Acceptance (paper Sec. 3, Sec. 4.3) on logits_dev[total_rows, vocab], or, if that is NULL,
+ * on the logits the preceding vf_verify on this model left, for the same seqs / tokens_dev /
+ * row_off_host.  Per sequence b, with a_b = number of accepted drafts:
+ *   n_accept_dev[b]                         = a_b
+ *   out_tokens_dev[row_off[b] .. +a_b]      = x_1..x_{a_b} then the corrected/bonus token
+ *                                             (remaining entries of the slice are set to -1)
+ *   y_dev[row_off[b] + i]                   = arg-max of row i's logits, for ALL rows (what
+ *                                             the draft-reuse rule of Sec. 4.3 compares with)
+ * and on the device: len_b += 1 + a_b, pending_b = the emitted token.  Arg-max ties go to
+ * the lowest id.  Stochastic decisions use float64 probabilities from the float32 logits. */
+int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+              const int32_t *row_off_host, const vf_accept_params *params_host,
+              const float *logits_dev, int32_t *n_accept_dev, int32_t *out_tokens_dev,
+              int32_t *y_dev, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VF_H */

@@ -1,0 +1,194 @@
+// Weight-streaming GEMM  Y[rows, N] = X[rows, K] * W[N, K]^T  for few rows.
+//
+// Every linear layer of the verify forward has at most a few dozen activation rows (the
+// pending token plus the drafts; paper Sec. 3 and Sec. 4.3), so the step is bound by reading
+// each weight byte once from HBM.  The weights are the MFMA A operand, streamed from global
+// memory straight into registers as 1 KiB-per-wavefront contiguous fragments; the activations
+// are the B operand, staged in LDS once per workgroup and re-used by all its wavefronts.
+// Products are accumulated in float32 and written as split-K partial sums [ks][rows][N]; the
+// consumer kernels add the partials in a fixed order, which keeps results bit-reproducible.
+#include "vf_internal.h"
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int GEMM_WAVES = 4;
+constexpr int PREFETCH = 4;   // weight fragments in flight per stream and wavefront
+
+template <int NB> struct Chunk { static constexpr int KC = (NB <= 2) ? 16 : 8; };
+
+__device__ inline u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+
+// NB: 16-row activation blocks handled per pass; NBW: weight n-blocks per wavefront.
+template <int NB, int NBW>
+__global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_bf16_kernel(
+    const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp, float *__restrict__ part, int N,
+    int KB, int ncb, int row_lo, int row_hi, int ld_rows, int kb_per_split) {
+    constexpr int KC = Chunk<NB>::KC;
+    __shared__ u32x4 xs[KC * NB * 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int NBt = N >> 4;
+    const int cb0 = (row_lo >> 4) + blockIdx.z * NB;
+    const int nb0 = (blockIdx.x * GEMM_WAVES + wave) * NBW;
+    const int kb_begin = blockIdx.y * kb_per_split;
+    const int kb_end = min(KB, kb_begin + kb_per_split);
+    const bool active = nb0 < NBt;
+
+    floatx4 acc[NBW][NB];
+#pragma unroll
+    for (int i = 0; i < NBW; ++i)
+#pragma unroll
+        for (int c = 0; c < NB; ++c) acc[i][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const u32x4 *wp[NBW];
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) {
+        int nb = min(nb0 + i, NBt - 1);  // out-of-range streams re-read a valid block, never stored
+        wp[i] = Wp + (size_t)nb * KB * 64 + lane;
+    }
+    u32x4 w[PREFETCH][NBW];
+    if (active) {
+#pragma unroll
+        for (int d = 0; d < PREFETCH; ++d)
+            if (kb_begin + d < kb_end)
+#pragma unroll
+                for (int i = 0; i < NBW; ++i) w[d][i] = load_stream(wp[i] + (size_t)(kb_begin + d) * 64);
+    }
+
+    for (int kc = kb_begin; kc < kb_end; kc += KC) {
+        const int nk = min(KC, kb_end - kc);
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < nk * NB * 64; idx += GEMM_WAVES * 64) {
+            int l = idx & 63, f = idx >> 6;
+            int c = f % NB, kbl = f / NB;
+            int cb = cb0 + c;
+            u32x4 v = u32x4{0u, 0u, 0u, 0u};
+            if (cb < ncb) v = Xp[((size_t)(kc + kbl) * ncb + cb) * 64 + l];
+            xs[idx] = v;
+        }
+        __syncthreads();
+        if (!active) continue;
+#pragma unroll 1
+        for (int k0 = 0; k0 < nk; k0 += PREFETCH) {
+#pragma unroll
+            for (int d = 0; d < PREFETCH; ++d) {
+                const int kbl = k0 + d;
+                if (kbl < nk) {
+                    bf16x8 a[NBW];
+#pragma unroll
+                    for (int i = 0; i < NBW; ++i) a[i] = __builtin_bit_cast(bf16x8, w[d][i]);
+                    const int nxt = kc + kbl + PREFETCH;
+                    if (nxt < kb_end)
+#pragma unroll
+                        for (int i = 0; i < NBW; ++i) w[d][i] = load_stream(wp[i] + (size_t)nxt * 64);
+#pragma unroll
+                    for (int c = 0; c < NB; ++c) {
+                        bf16x8 b = __builtin_bit_cast(bf16x8, xs[(kbl * NB + c) * 64 + lane]);
+#pragma unroll
+                        for (int i = 0; i < NBW; ++i)
+                            acc[i][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b, acc[i][c], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    if (!active) return;
+    // lane holds Y[row = 16*cb + (lane & 15)][n = 16*nb + 4*(lane >> 4) + 0..3]
+    float *out = part + (size_t)blockIdx.y * ld_rows * N;
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) {
+        if (nb0 + i >= NBt) break;
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+            int row = (cb0 + c) * 16 + (lane & 15);
+            if (row >= row_lo && row < row_hi) {
+                float *p = out + (size_t)row * N + (nb0 + i) * 16 + (lane >> 4) * 4;
+                *reinterpret_cast<floatx4 *>(p) = acc[i][c];
+            }
+        }
+    }
+}
+
+// float32 model: plain fused-multiply-add GEMM, one wavefront per output column, 8 rows at a time.
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__ W,
+                                                        const float *__restrict__ X,
+                                                        float *__restrict__ out, int N, int K,
+                                                        int row_lo, int row_hi) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;
+    const float *wr = W + (size_t)n * K;
+    for (int r0 = row_lo; r0 < row_hi; r0 += 8) {
+        float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int k = lane; k < K; k += 64) {
+            float wv = wr[k];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (r0 + i < row_hi) acc[i] = fmaf(wv, X[(size_t)(r0 + i) * K + k], acc[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float v = acc[i];
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+            if (lane == 0 && r0 + i < row_hi) out[(size_t)(r0 + i) * N + n] = v;
+        }
+    }
+}
+
+template <int NB>
+int launch_bf16(const vf_model *m, const void *W, const void *X, float *part, int N, int K, int ncb,
+                int row_lo, int row_hi, int ld_rows, GemmPlan plan, hipStream_t st) {
+    const int KB = K >> 5, NBt = N >> 4;
+    const int kbps = (KB + plan.ks - 1) / plan.ks;
+    const int cbs = ((row_hi + 15) >> 4) - (row_lo >> 4);
+    dim3 grid((NBt + GEMM_WAVES * plan.nbw - 1) / (GEMM_WAVES * plan.nbw), plan.ks, (cbs + NB - 1) / NB);
+    dim3 block(GEMM_WAVES * 64);
+    auto args = [&](auto kern) {
+        hipLaunchKernelGGL(kern, grid, block, 0, st, (const u32x4 *)W, (const u32x4 *)X, part, N, KB, ncb,
+                           row_lo, row_hi, ld_rows, kbps);
+    };
+    switch (plan.nbw) {
+        case 1: args(gemm_bf16_kernel<NB, 1>); break;
+        case 2: args(gemm_bf16_kernel<NB, 2>); break;
+        default: args(gemm_bf16_kernel<NB, 4>); break;
+    }
+    VF_LAUNCH_CHECK("gemm_bf16");
+    return VF_OK;
+}
+
+}  // namespace
+
+GemmPlan vf_gemm_plan(const vf_model *m, int N, int K, int rows, int force_single) {
+    GemmPlan p{1, 1};
+    if (m->cfg.dtype == VF_F32) return p;
+    const int NBt = N >> 4, KB = K >> 5;
+    const int groups1 = (NBt + GEMM_WAVES - 1) / GEMM_WAVES;
+    if (groups1 >= 4096) p.nbw = 4;
+    else if (groups1 >= 2048) p.nbw = 2;
+    if (force_single) return p;
+    const int groups = (NBt + GEMM_WAVES * p.nbw - 1) / (GEMM_WAVES * p.nbw);
+    int ks = 1;
+    while (groups * ks < 256 && KB / (ks * 2) >= 4) ks *= 2;
+    // the partial buffer must hold ks * ld_rows * N floats
+    while (ks > 1 && (size_t)ks * m->cfg.max_rows * N > m->part_floats) ks /= 2;
+    p.ks = ks;
+    return p;
+}
+
+int vf_launch_gemm(const vf_model *m, const void *W, const void *X, float *part, int N, int K,
+                   int rows_total, int row_lo, int row_hi, int ld_rows, GemmPlan plan, hipStream_t st) {
+    if (row_hi <= row_lo) return VF_OK;
+    if (m->cfg.dtype == VF_F32) {
+        hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 3) / 4), dim3(256), 0, st, (const float *)W,
+                           (const float *)X, part, N, K, row_lo, row_hi);
+        VF_LAUNCH_CHECK("gemm_f32");
+        return VF_OK;
+    }
+    const int ncb = (rows_total + 15) >> 4;
+    const int cbs = ((row_hi + 15) >> 4) - (row_lo >> 4);
+    if (cbs <= 1) return launch_bf16<1>(m, W, X, part, N, K, ncb, row_lo, row_hi, ld_rows, plan, st);
+    if (cbs == 2) return launch_bf16<2>(m, W, X, part, N, K, ncb, row_lo, row_hi, ld_rows, plan, st);
+    if (cbs == 3) return launch_bf16<3>(m, W, X, part, N, K, ncb, row_lo, row_hi, ld_rows, plan, st);
+    return launch_bf16<4>(m, W, X, part, N, K, ncb, row_lo, row_hi, ld_rows, plan, st);
+}

@@ -1,0 +1,178 @@
+// Internal declarations shared by the translation units of libvf.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "vf.h"
+
+#define VF_TILE 64            // tokens per KV tile / page
+#define VF_ATTN_SPLIT_MAX 64  // most key splits one query row can have
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// ---- per-call description of the batch, passed to kernels by value --------------------------
+struct SeqDesc {
+    char *kv;                   // KV pool base
+    const int32_t *block_table; // NULL: page id = tile index
+    int32_t *state;             // [0] = length, [1] = pending token
+    int32_t n_pages;            // pages in the pool (contiguous: tiles of this sequence)
+    int32_t capacity;           // tokens this sequence may hold
+    int32_t row0, nrows;        // its rows inside the call
+    int32_t len_ub;             // host upper bound of the length before this call
+    int32_t pad;
+};
+struct Batch {
+    int32_t n_seqs, total_rows;
+    SeqDesc s[VF_MAX_BATCH];
+};
+
+struct AcceptDesc {
+    const float *q;             // [k, V] or NULL
+    const float *u;             // [2*(k+1)]
+    float temperature;
+    int32_t mode;
+};
+struct AcceptBatch {
+    AcceptDesc a[VF_MAX_BATCH];
+};
+
+// ---- model / sequence host structs ------------------------------------------------------------
+struct LayerPacked {
+    void *wqkv, *wo, *wgu, *wd; // packed matrices
+    float *attn_norm, *ffn_norm, *bqkv;
+};
+
+struct vf_model {
+    vf_config cfg;
+    int es;                     // bytes per element of the model dtype
+    char *base;
+    size_t bytes;
+    LayerPacked *layers;        // host array
+    void *embed, *lm_head;
+    float *final_norm, *rope_cos, *rope_sin;
+    // workspace
+    float *h;                   // residual stream [R, d]
+    void *x;                    // GEMM input (activation layout) [R, max(d, Hq*hd)]
+    void *q;                    // [R, Hq*hd] row-major
+    void *o;                    // attention output (activation layout) [R, Hq*hd]
+    void *a;                    // SwiGLU product (activation layout) [R, F]
+    float *part;                // split-K partial sums
+    size_t part_floats;
+    float *attn_part;           // [R*Hq, VF_ATTN_SPLIT_MAX, hd+2]
+    float *logits;              // [R, V]
+    float *stat_max;            // [R, n_chunks]
+    int32_t *stat_idx;          // [R, n_chunks]
+    double *stat_sum;           // [R, n_chunks]
+    int n_chunks;               // vocabulary chunks of the row-statistics pass
+    const float *last_logits;   // where the last verify left its logits
+    int last_rows;
+};
+
+struct vf_seq {
+    vf_model *m;
+    char *kv;
+    const int32_t *block_table;
+    int32_t *state;
+    int n_pages, capacity, paged;
+    int len_ub;                 // host upper bound of the device-side length
+};
+
+// ---- error handling ----------------------------------------------------------------------------
+int vf_fail(int code, const char *fmt, ...);
+#define VF_HIP(call)                                                                       \
+    do {                                                                                   \
+        hipError_t e_ = (call);                                                            \
+        if (e_ != hipSuccess) return vf_fail(VF_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+#define VF_LAUNCH_CHECK(name)                                                              \
+    do {                                                                                   \
+        hipError_t e_ = hipGetLastError();                                                 \
+        if (e_ != hipSuccess) return vf_fail(VF_ERR_HIP, "launch %s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- layouts ------------------------------------------------------------------------------------
+// Packed bf16 matrix W[N, K]: 16x32 fragments in MFMA A-operand order.  Fragment (nb, kb) holds
+// rows 16*nb.. and columns 32*kb..; lane l of a wavefront owns row (l & 15), columns
+// 8*(l >> 4) .. +8: eight consecutive bf16 = 16 bytes.  Fragments of one nb are contiguous in kb.
+__host__ __device__ inline size_t wfrag_index(int n, int k, int K) {
+    int nb = n >> 4, kb = k >> 5;
+    int lane = (((k >> 3) & 3) << 4) | (n & 15);
+    return (((size_t)nb * (K >> 5) + kb) * 64 + lane) * 8 + (k & 7);
+}
+// bf16 activations X[rows, K] in MFMA B-operand order: fragment (kb, cb) holds rows 16*cb.. and
+// columns 32*kb..; ncb = number of 16-row blocks.  float32 activations are plain row-major.
+__host__ __device__ inline size_t xfrag_index(int row, int k, int ncb) {
+    int cb = row >> 4, kb = k >> 5;
+    int lane = (((k >> 3) & 3) << 4) | (row & 15);
+    return (((size_t)kb * ncb + cb) * 64 + lane) * 8 + (k & 7);
+}
+template <typename T> __device__ inline size_t act_index(int row, int k, int K, int ncb);
+template <> __device__ inline size_t act_index<float>(int row, int k, int K, int) { return (size_t)row * K + k; }
+template <> __device__ inline size_t act_index<bf16_t>(int row, int k, int, int ncb) { return xfrag_index(row, k, ncb); }
+
+template <typename T> __device__ inline size_t w_index(int n, int k, int K);
+template <> __device__ inline size_t w_index<float>(int n, int k, int K) { return (size_t)n * K + k; }
+template <> __device__ inline size_t w_index<bf16_t>(int n, int k, int K) { return wfrag_index(n, k, K); }
+
+// KV pool: per layer and page, K as [Hkv][64][hd] then V transposed as [Hkv][hd][64].
+__host__ __device__ inline size_t kv_k_index(int layer, int n_pages, int page, int hkv, int head, int tin,
+                                              int d, int hd) {
+    return ((((size_t)layer * n_pages + page) * 2 * hkv + head) * VF_TILE + tin) * hd + d;
+}
+__host__ __device__ inline size_t kv_v_index(int layer, int n_pages, int page, int hkv, int head, int tin,
+                                              int d, int hd) {
+    return ((((size_t)layer * n_pages + page) * 2 * hkv + hkv + head) * hd + d) * VF_TILE + tin;
+}
+__device__ inline int kv_page(const SeqDesc &s, int t) {
+    int tile = t / VF_TILE;
+    return s.block_table ? s.block_table[tile] : tile;
+}
+
+__device__ inline float to_f32(float v) { return v; }
+__device__ inline float to_f32(bf16_t v) { return (float)v; }
+template <typename T> __device__ inline T from_f32(float v);
+template <> __device__ inline float from_f32<float>(float v) { return v; }
+template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // round-to-nearest-even
+
+__device__ inline int find_seq(const Batch &b, int row) {
+    int i = 0;
+    while (i + 1 < b.n_seqs && row >= b.s[i + 1].row0) ++i;
+    return i;
+}
+
+// ---- launchers (defined next to their kernels) --------------------------------------------------
+struct GemmPlan {
+    int ks;        // K splits (partials)
+    int nbw;       // n-blocks per wavefront
+};
+GemmPlan vf_gemm_plan(const vf_model *m, int N, int K, int rows, int force_single);
+// Y partials [ks][R][N] (R = ld_rows) for rows [row_lo, row_hi) of X.
+int vf_launch_gemm(const vf_model *m, const void *W, const void *X, float *part, int N, int K,
+                   int rows_total, int row_lo, int row_hi, int ld_rows, GemmPlan plan, hipStream_t st);
+
+int vf_launch_pack(const vf_model *m, const void *src, void *dst, int n_rows, int K, int dst_nb0,
+                   int dst_nb_stride, int dst_rows_total, hipStream_t st);
+int vf_launch_rope_table(const vf_model *m, hipStream_t st);
+int vf_launch_embed(const vf_model *m, const Batch &b, const int32_t *tokens, hipStream_t st);
+int vf_launch_norm(const vf_model *m, const float *gain, void *x_out, const float *part, int nparts,
+                   int rows, int ld_rows, hipStream_t st);
+int vf_launch_qkv_finish(const vf_model *m, const Batch &b, int layer, const float *part, int nparts,
+                         int ld_rows, hipStream_t st);
+int vf_launch_swiglu(const vf_model *m, const float *part, int nparts, int rows, int ld_rows, hipStream_t st);
+int vf_launch_reduce_rows(const vf_model *m, const float *part, int nparts, int N, int row_lo, int row_hi,
+                          int ld_rows, float *out, int out_ld, hipStream_t st);
+int vf_launch_attention(const vf_model *m, const Batch &b, int layer, hipStream_t st);
+int vf_launch_state_set(int32_t *state, int idx, int32_t value, hipStream_t st);
+int vf_launch_state_add(int32_t *state, int idx, int32_t delta, hipStream_t st);
+int vf_launch_kv_read(const vf_model *m, const SeqDesc &s, int layer, int t0, int n, float *k_out,
+                      float *v_out, hipStream_t st);
+int vf_launch_accept(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
+                     const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y,
+                     hipStream_t st);
+int vf_launch_first_token(const vf_model *m, const SeqDesc &s, const float *logits_row, const float *u,
+                          float temperature, hipStream_t st);
