@@ -197,6 +197,28 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
               const float *logits_dev, int32_t *n_accept_dev, int32_t *out_tokens_dev,
               int32_t *y_dev, void *stream);
 
+/* ---- measurement hook (not part of the method) ---------------------------------------------- */
+
+/* Kernel sites timed by vf_profile: the five GEMMs of the forward pass, attention (both
+ * kernels), the small norm / epilogue kernels together, and acceptance. */
+#define VF_SITE_QKV     0
+#define VF_SITE_O       1
+#define VF_SITE_GATEUP  2
+#define VF_SITE_DOWN    3
+#define VF_SITE_HEAD    4
+#define VF_SITE_ATTN    5
+#define VF_SITE_SMALL   6
+#define VF_SITE_ACCEPT  7
+#define VF_N_SITES      8
+
+/* enable != 0: from now on every launch group of the sites above is bracketed by a pair of
+ * HIP events on the call's stream (costs about a microsecond per event; leave it off when
+ * timing whole steps).  enable == 0: stop recording. */
+int vf_profile(vf_model *m, int enable);
+/* Synchronises with the recorded events, adds up elapsed milliseconds and launch counts per
+ * site into ms_host[VF_N_SITES] / count_host[VF_N_SITES], and clears the record. */
+int vf_profile_read(vf_model *m, float *ms_host, int32_t *count_host);
+
 #ifdef __cplusplus
 }
 #endif

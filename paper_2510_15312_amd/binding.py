@@ -23,8 +23,9 @@ EXPORTS = [
     "vf_last_error", "vf_model_packed_bytes", "vf_model_create", "vf_model_destroy",
     "vf_seq_state_bytes", "vf_kv_bytes", "vf_seq_create", "vf_seq_destroy", "vf_seq_set_len",
     "vf_seq_set_pending", "vf_seq_get_state", "vf_kv_read", "vf_prefill_chunk", "vf_verify",
-    "vf_accept",
+    "vf_accept", "vf_profile", "vf_profile_read",
 ]
+SITES = ["qkv", "o", "gateup", "down", "head", "attn", "small", "accept"]
 
 
 class VfError(RuntimeError):
@@ -77,6 +78,8 @@ def _load():
         "vf_verify": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), vp, vp]),
         "vf_accept": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(vf_accept_params),
                                 vp, vp, vp, vp, vp]),
+        "vf_profile": (C.c_int, [vp, C.c_int]),
+        "vf_profile_read": (C.c_int, [vp, C.POINTER(C.c_float), C.POINTER(i32)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -233,3 +236,15 @@ def vf_accept(model, seqs, tokens, row_off, params, n_accept, out_tokens, y, log
                                  u.data_ptr() if u is not None else None)
     _check(lib.vf_accept(model.handle, hs, len(seqs), _ptr(tokens), ro, ps, _ptr(logits), _ptr(n_accept),
                          _ptr(out_tokens), _ptr(y), _stream()))
+
+
+def vf_profile(model, enable):
+    _check(lib.vf_profile(model.handle, int(enable)))
+
+
+def vf_profile_read(model):
+    """{site: (total ms, launch groups)} since the last read."""
+    ms = (C.c_float * len(SITES))()
+    cnt = (C.c_int32 * len(SITES))()
+    _check(lib.vf_profile_read(model.handle, ms, cnt))
+    return {s: (ms[i], cnt[i]) for i, s in enumerate(SITES)}

@@ -107,6 +107,25 @@ SeqDesc describe(const vf_seq *s, int row0, int nrows) {
     return d;
 }
 
+// Brackets a launch group with two events when profiling is on.
+struct ProfScope {
+    vf_model *m;
+    hipStream_t st;
+    hipEvent_t b = nullptr;
+    ProfScope(vf_model *m_, int site, hipStream_t st_) : m(m_), st(st_) {
+        if (!m->prof_on) return;
+        hipEvent_t ev[2];
+        for (int i = 0; i < 2; ++i) {
+            if (!m->prof_pool->empty()) { ev[i] = m->prof_pool->back(); m->prof_pool->pop_back(); }
+            else if (hipEventCreate(&ev[i]) != hipSuccess) { if (i) m->prof_pool->push_back(ev[0]); return; }
+        }
+        (void)hipEventRecord(ev[0], st);
+        m->prof->push_back({site, ev[0], ev[1]});
+        b = ev[1];
+    }
+    ~ProfScope() { if (b) (void)hipEventRecord(b, st); }
+};
+
 // One pass of the decoder stack over the rows of `b`; leaves the residual stream in m->h with
 // the last down-projection still in (part, nparts) form: *tail_parts tells the caller how many
 // partial sums the final norm must add.
@@ -119,19 +138,28 @@ int run_layers(vf_model *m, const Batch &b, const int32_t *tokens, int *tail_par
     int nparts = 0;
     for (int l = 0; l < c.n_layers; ++l) {
         const LayerPacked &lp = m->layers[l];
-        if ((rc = vf_launch_norm(m, lp.attn_norm, m->x, m->part, nparts, rows, R, st))) return rc;
+        { ProfScope ps(m, VF_SITE_SMALL, st);
+          if ((rc = vf_launch_norm(m, lp.attn_norm, m->x, m->part, nparts, rows, R, st))) return rc; }
         GemmPlan p = vf_gemm_plan(m, nq + 2 * nkv, d, rows, 0);
-        if ((rc = vf_launch_gemm(m, lp.wqkv, m->x, m->part, nq + 2 * nkv, d, rows, 0, rows, R, p, st))) return rc;
-        if ((rc = vf_launch_qkv_finish(m, b, l, m->part, p.ks, R, st))) return rc;
-        if ((rc = vf_launch_attention(m, b, l, st))) return rc;
+        { ProfScope ps(m, VF_SITE_QKV, st);
+          if ((rc = vf_launch_gemm(m, lp.wqkv, m->x, m->part, nq + 2 * nkv, d, rows, 0, rows, R, p, st))) return rc; }
+        { ProfScope ps(m, VF_SITE_SMALL, st);
+          if ((rc = vf_launch_qkv_finish(m, b, l, m->part, p.ks, R, st))) return rc; }
+        { ProfScope ps(m, VF_SITE_ATTN, st);
+          if ((rc = vf_launch_attention(m, b, l, st))) return rc; }
         p = vf_gemm_plan(m, d, nq, rows, 0);
-        if ((rc = vf_launch_gemm(m, lp.wo, m->o, m->part, d, nq, rows, 0, rows, R, p, st))) return rc;
-        if ((rc = vf_launch_norm(m, lp.ffn_norm, m->x, m->part, p.ks, rows, R, st))) return rc;
+        { ProfScope ps(m, VF_SITE_O, st);
+          if ((rc = vf_launch_gemm(m, lp.wo, m->o, m->part, d, nq, rows, 0, rows, R, p, st))) return rc; }
+        { ProfScope ps(m, VF_SITE_SMALL, st);
+          if ((rc = vf_launch_norm(m, lp.ffn_norm, m->x, m->part, p.ks, rows, R, st))) return rc; }
         p = vf_gemm_plan(m, 2 * F, d, rows, 0);
-        if ((rc = vf_launch_gemm(m, lp.wgu, m->x, m->part, 2 * F, d, rows, 0, rows, R, p, st))) return rc;
-        if ((rc = vf_launch_swiglu(m, m->part, p.ks, rows, R, st))) return rc;
+        { ProfScope ps(m, VF_SITE_GATEUP, st);
+          if ((rc = vf_launch_gemm(m, lp.wgu, m->x, m->part, 2 * F, d, rows, 0, rows, R, p, st))) return rc; }
+        { ProfScope ps(m, VF_SITE_SMALL, st);
+          if ((rc = vf_launch_swiglu(m, m->part, p.ks, rows, R, st))) return rc; }
         p = vf_gemm_plan(m, d, F, rows, 0);
-        if ((rc = vf_launch_gemm(m, lp.wd, m->a, m->part, d, F, rows, 0, rows, R, p, st))) return rc;
+        { ProfScope ps(m, VF_SITE_DOWN, st);
+          if ((rc = vf_launch_gemm(m, lp.wd, m->a, m->part, d, F, rows, 0, rows, R, p, st))) return rc; }
         nparts = p.ks;
     }
     *tail_parts = nparts;
@@ -142,8 +170,10 @@ int run_layers(vf_model *m, const Batch &b, const int32_t *tokens, int *tail_par
 int run_head(vf_model *m, int rows, int tail_parts, int row_lo, int row_hi, float *out, hipStream_t st) {
     const vf_config &c = m->cfg;
     int rc;
-    if ((rc = vf_launch_norm(m, m->final_norm, m->x, m->part, tail_parts, rows, rows, st))) return rc;
+    { ProfScope ps(m, VF_SITE_SMALL, st);
+      if ((rc = vf_launch_norm(m, m->final_norm, m->x, m->part, tail_parts, rows, rows, st))) return rc; }
     GemmPlan p = vf_gemm_plan(m, c.vocab, c.d_model, rows, 1);
+    ProfScope ps(m, VF_SITE_HEAD, st);
     // with ks == 1 the "partial" [ld_rows][V] is the logits matrix itself: shift the base so
     // that row_lo lands on out[0]
     float *base = out - (size_t)row_lo * c.vocab;
@@ -183,11 +213,13 @@ int vf_model_create(const vf_config *cfg, const vf_weights *w, void *packed_dev,
     memset(m, 0, sizeof *m);
     m->cfg = *cfg;
     m->es = cfg->dtype == VF_BF16 ? 2 : 4;
+    m->prof = new std::vector<vf_model::ProfRec>();
+    m->prof_pool = new std::vector<hipEvent_t>();
     m->layers = new (std::nothrow) LayerPacked[cfg->n_layers];
-    if (!m->layers) { delete m; return vf_fail(VF_ERR_ARG, "out of host memory"); }
+    if (!m->layers) { delete m->prof; delete m->prof_pool; delete m; return vf_fail(VF_ERR_ARG, "out of host memory"); }
     const size_t need = carve_model(m, (char *)packed_dev);
     if (packed_bytes < need) {
-        delete[] m->layers; delete m;
+        delete[] m->layers; delete m->prof; delete m->prof_pool; delete m;
         return vf_fail(VF_ERR_ARG, "packed buffer too small: %zu < %zu", packed_bytes, need);
     }
     m->base = (char *)packed_dev;
@@ -195,7 +227,7 @@ int vf_model_create(const vf_config *cfg, const vf_weights *w, void *packed_dev,
     hipStream_t st = (hipStream_t)stream;
     const vf_config &c = m->cfg;
     const int d = c.d_model, F = c.d_ffn, hd = c.head_dim, nq = c.n_q_heads * hd, nkv = c.n_kv_heads * hd;
-    auto fail = [&](int code) { delete[] m->layers; delete m; return code; };
+    auto fail = [&](int code) { delete[] m->layers; delete m->prof; delete m->prof_pool; delete m; return code; };
 #define TRY(x) do { int rc_ = (x); if (rc_) return fail(rc_); } while (0)
 #define TRYHIP(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return fail(vf_fail(VF_ERR_HIP, "%s: %s", #x, hipGetErrorString(e_))); } while (0)
     TRY(vf_launch_pack(m, w->embed, m->embed, c.vocab, d, 0, 1, c.vocab, st));
@@ -230,6 +262,12 @@ int vf_model_create(const vf_config *cfg, const vf_weights *w, void *packed_dev,
 
 int vf_model_destroy(vf_model *m) {
     if (!m) return vf_fail(VF_ERR_ARG, "vf_model_destroy: NULL");
+    if (m->prof) {
+        for (auto &r : *m->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+        for (auto e : *m->prof_pool) (void)hipEventDestroy(e);
+        delete m->prof;
+        delete m->prof_pool;
+    }
     delete[] m->layers;
     delete m;
     return VF_OK;
@@ -431,10 +469,35 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
         ab.a[i].temperature = p.mode == VF_STOCHASTIC ? p.temperature : 1.f;
         ab.a[i].mode = p.mode;
     }
-    if ((rc = vf_launch_accept(m, b, ab, tokens_dev, logits, n_accept_dev, out_tokens_dev, y_dev,
-                               (hipStream_t)stream)))
-        return rc;
+    {
+        ProfScope ps(m, VF_SITE_ACCEPT, (hipStream_t)stream);
+        if ((rc = vf_launch_accept(m, b, ab, tokens_dev, logits, n_accept_dev, out_tokens_dev, y_dev,
+                                   (hipStream_t)stream)))
+            return rc;
+    }
     for (int i = 0; i < n_seqs; ++i) seqs[i]->len_ub += b.s[i].nrows;
+    return VF_OK;
+}
+
+int vf_profile(vf_model *m, int enable) {
+    if (!m) return vf_fail(VF_ERR_ARG, "vf_profile: NULL");
+    m->prof_on = enable != 0;
+    return VF_OK;
+}
+
+int vf_profile_read(vf_model *m, float *ms_host, int32_t *count_host) {
+    if (!m || !ms_host || !count_host) return vf_fail(VF_ERR_ARG, "vf_profile_read: NULL argument");
+    for (int i = 0; i < VF_N_SITES; ++i) { ms_host[i] = 0.f; count_host[i] = 0; }
+    for (auto &r : *m->prof) {
+        VF_HIP(hipEventSynchronize(r.b));
+        float ms = 0.f;
+        VF_HIP(hipEventElapsedTime(&ms, r.a, r.b));
+        ms_host[r.site] += ms;
+        count_host[r.site] += 1;
+        m->prof_pool->push_back(r.a);
+        m->prof_pool->push_back(r.b);
+    }
+    m->prof->clear();
     return VF_OK;
 }
 

@@ -7,6 +7,8 @@
 
 #include "vf.h"
 
+#include <vector>
+
 #define VF_TILE 64            // tokens per KV tile / page
 #define VF_ATTN_SPLIT_MAX 64  // most key splits one query row can have
 
@@ -71,6 +73,11 @@ struct vf_model {
     int n_chunks;               // vocabulary chunks of the row-statistics pass
     const float *last_logits;   // where the last verify left its logits
     int last_rows;
+    // measurement hook
+    struct ProfRec { int site; hipEvent_t a, b; };
+    bool prof_on;
+    std::vector<ProfRec> *prof;       // recorded, not yet read
+    std::vector<hipEvent_t> *prof_pool;  // events free for reuse
 };
 
 struct vf_seq {
