@@ -230,25 +230,25 @@ int vf_model_create(const vf_config *cfg, const vf_weights *w, void *packed_dev,
     auto fail = [&](int code) { delete[] m->layers; delete m->prof; delete m->prof_pool; delete m; return code; };
 #define TRY(x) do { int rc_ = (x); if (rc_) return fail(rc_); } while (0)
 #define TRYHIP(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return fail(vf_fail(VF_ERR_HIP, "%s: %s", #x, hipGetErrorString(e_))); } while (0)
-    TRY(vf_launch_pack(m, w->embed, m->embed, c.vocab, d, 0, 1, c.vocab, st));
-    if (!c.tie_embeddings) TRY(vf_launch_pack(m, w->lm_head, m->lm_head, c.vocab, d, 0, 1, c.vocab, st));
+    TRY(vf_launch_pack(m, w->embed, m->embed, c.vocab, d, 0, 1, 0, st));
+    if (!c.tie_embeddings) TRY(vf_launch_pack(m, w->lm_head, m->lm_head, c.vocab, d, 0, 1, 0, st));
     TRYHIP(hipMemcpyAsync(m->final_norm, w->final_norm, (size_t)d * 4, hipMemcpyDeviceToDevice, st));
     for (int l = 0; l < c.n_layers; ++l) {
         const vf_layer_w &lw = w->layers[l];
         LayerPacked &lp = m->layers[l];
-        TRY(vf_launch_pack(m, lw.wq, lp.wqkv, nq, d, 0, 1, nq + 2 * nkv, st));
-        TRY(vf_launch_pack(m, lw.wk, lp.wqkv, nkv, d, nq / 16, 1, nq + 2 * nkv, st));
-        TRY(vf_launch_pack(m, lw.wv, lp.wqkv, nkv, d, (nq + nkv) / 16, 1, nq + 2 * nkv, st));
-        TRY(vf_launch_pack(m, lw.wo, lp.wo, d, nq, 0, 1, d, st));
-        TRY(vf_launch_pack(m, lw.w_gate, lp.wgu, F, d, 0, 2, 2 * F, st));
-        TRY(vf_launch_pack(m, lw.w_up, lp.wgu, F, d, 1, 2, 2 * F, st));
-        TRY(vf_launch_pack(m, lw.w_down, lp.wd, d, F, 0, 1, d, st));
+        TRY(vf_launch_pack(m, lw.wq, lp.wqkv, nq, d, 0, 1, hd, st));
+        TRY(vf_launch_pack(m, lw.wk, lp.wqkv, nkv, d, nq / 16, 1, hd, st));
+        TRY(vf_launch_pack(m, lw.wv, lp.wqkv, nkv, d, (nq + nkv) / 16, 1, 0, st));
+        TRY(vf_launch_pack(m, lw.wo, lp.wo, d, nq, 0, 1, 0, st));
+        TRY(vf_launch_pack(m, lw.w_gate, lp.wgu, F, d, 0, 2, 0, st));
+        TRY(vf_launch_pack(m, lw.w_up, lp.wgu, F, d, 1, 2, 0, st));
+        TRY(vf_launch_pack(m, lw.w_down, lp.wd, d, F, 0, 1, 0, st));
         TRYHIP(hipMemcpyAsync(lp.attn_norm, lw.attn_norm, (size_t)d * 4, hipMemcpyDeviceToDevice, st));
         TRYHIP(hipMemcpyAsync(lp.ffn_norm, lw.ffn_norm, (size_t)d * 4, hipMemcpyDeviceToDevice, st));
         if (c.qkv_bias) {
-            TRYHIP(hipMemcpyAsync(lp.bqkv, lw.bq, (size_t)nq * 4, hipMemcpyDeviceToDevice, st));
-            TRYHIP(hipMemcpyAsync(lp.bqkv + nq, lw.bk, (size_t)nkv * 4, hipMemcpyDeviceToDevice, st));
-            TRYHIP(hipMemcpyAsync(lp.bqkv + nq + nkv, lw.bv, (size_t)nkv * 4, hipMemcpyDeviceToDevice, st));
+            TRY(vf_launch_pack_vec((const float *)lw.bq, lp.bqkv, nq, hd, st));
+            TRY(vf_launch_pack_vec((const float *)lw.bk, lp.bqkv + nq, nkv, hd, st));
+            TRY(vf_launch_pack_vec((const float *)lw.bv, lp.bqkv + nq + nkv, nkv, 0, st));
         }
     }
     TRY(vf_launch_rope_table(m, st));

@@ -10,8 +10,16 @@ namespace {
 
 // Row-major bf16 [n_rows, K] -> 16x32 fragments; source n-block nb lands at dst block
 // dst_nb0 + nb * dst_nb_stride (interleaving gate and up, concatenating q, k, v).
+// perm_hd > 0: within every head of perm_hd rows, packed row 2i is source row i and packed row 2i+1
+// is source row i + perm_hd/2, so that the two elements of a rotary pair are neighbours.
+__device__ inline int pack_src_row(int n, int perm_hd) {
+    if (perm_hd <= 0) return n;
+    const int head = n / perm_hd, p = n % perm_hd;
+    return head * perm_hd + (p >> 1) + (p & 1) * (perm_hd >> 1);
+}
+
 __global__ void pack_bf16_kernel(const uint16_t *__restrict__ src, uint4 *__restrict__ dst, int n_rows,
-                                 int K, int dst_nb0, int dst_nb_stride) {
+                                 int K, int dst_nb0, int dst_nb_stride, int perm_hd) {
     const int KB = K >> 5;
     size_t total = (size_t)(n_rows >> 4) * KB * 64;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total;
@@ -19,7 +27,7 @@ __global__ void pack_bf16_kernel(const uint16_t *__restrict__ src, uint4 *__rest
         int lane = (int)(i & 63);
         size_t f = i >> 6;
         int kb = (int)(f % KB), nb = (int)(f / KB);
-        int n = nb * 16 + (lane & 15), k = kb * 32 + (lane >> 4) * 8;
+        int n = pack_src_row(nb * 16 + (lane & 15), perm_hd), k = kb * 32 + (lane >> 4) * 8;
         uint4 v = *reinterpret_cast<const uint4 *>(src + (size_t)n * K + k);
         int dnb = dst_nb0 + nb * dst_nb_stride;
         dst[((size_t)dnb * KB + kb) * 64 + lane] = v;
@@ -28,13 +36,13 @@ __global__ void pack_bf16_kernel(const uint16_t *__restrict__ src, uint4 *__rest
 
 // float32 model: same block re-ordering on plain row-major rows.
 __global__ void pack_f32_kernel(const float *__restrict__ src, float *__restrict__ dst, int n_rows, int K,
-                                int dst_nb0, int dst_nb_stride) {
+                                int dst_nb0, int dst_nb_stride, int perm_hd) {
     size_t total = (size_t)n_rows * K;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total;
          i += (size_t)gridDim.x * blockDim.x) {
         int n = (int)(i / K), k = (int)(i % K);
         int dn = (dst_nb0 + (n >> 4) * dst_nb_stride) * 16 + (n & 15);
-        dst[(size_t)dn * K + k] = src[i];
+        dst[(size_t)dn * K + k] = src[(size_t)pack_src_row(n, perm_hd) * K + k];
     }
 }
 
@@ -94,7 +102,8 @@ __global__ __launch_bounds__(256) void norm_kernel(float *__restrict__ h, const 
 }
 
 // QKV epilogue: one thread per (row, head, rotary pair).  Heads 0..Hq-1 are q, then Hkv k heads,
-// then Hkv v heads (v is not rotated).  Pair = elements (i, i + hd/2) of a head.
+// then Hkv v heads (v is not rotated).  Pair = elements (i, i + hd/2) of a head; the packed
+// q and k weight rows (and biases) hold a pair in neighbouring columns 2i, 2i+1.
 template <typename T>
 __global__ void qkv_finish_kernel(const float *__restrict__ part, int nparts, int ld_rows, Batch b, int layer,
                                   const float *__restrict__ bias, const float *__restrict__ cosv,
@@ -107,7 +116,8 @@ __global__ void qkv_finish_kernel(const float *__restrict__ part, int nparts, in
     const int row = idx / per_row, rem = idx % per_row;
     const int head = rem / half, i = rem % half;
     const int N = heads * hd;
-    const int n0 = head * hd + i, n1 = n0 + half;
+    const bool rot = head < hq + hkv;
+    const int n0 = rot ? head * hd + 2 * i : head * hd + i, n1 = rot ? n0 + 1 : n0 + half;
     float v0 = 0.f, v1 = 0.f;
     for (int p = 0; p < nparts; ++p) {
         const float *pr = part + ((size_t)p * ld_rows + row) * N;
@@ -118,7 +128,7 @@ __global__ void qkv_finish_kernel(const float *__restrict__ part, int nparts, in
     const SeqDesc &s = b.s[find_seq(b, row)];
     const int pos = s.state[0] + (row - s.row0);
     if (pos < 0 || pos >= s.capacity) return;
-    if (head < hq + hkv) {
+    if (rot) {
         const float c = cosv[(size_t)pos * half + i], sn = sinv[(size_t)pos * half + i];
         const float r0 = v0 * c - v1 * sn, r1 = v1 * c + v0 * sn;
         v0 = r0; v1 = r1;
@@ -189,20 +199,35 @@ __global__ void kv_read_kernel(SeqDesc s, int layer, int t0, int n, int hkv, int
 
 inline int nblocks(size_t n, int bs) { return (int)((n + bs - 1) / bs); }
 
+__global__ void pack_vec_kernel(const float *__restrict__ src, float *__restrict__ dst, int n, int perm_hd) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[pack_src_row(i, perm_hd)];
+}
+
 }  // namespace
 
+int vf_launch_pack_vec(const float *src, float *dst, int n, int perm_hd, hipStream_t st) {
+    hipLaunchKernelGGL(pack_vec_kernel, dim3((n + 255) / 256), dim3(256), 0, st, src, dst, n, perm_hd);
+    VF_LAUNCH_CHECK("pack_vec");
+    return VF_OK;
+}
+
+namespace {
+inline int nblocks2(size_t n, int bs) { return (int)((n + bs - 1) / bs); }
+}
+
 int vf_launch_pack(const vf_model *m, const void *src, void *dst, int n_rows, int K, int dst_nb0,
-                   int dst_nb_stride, int, hipStream_t st) {
+                   int dst_nb_stride, int perm_hd, hipStream_t st) {
     if (m->cfg.dtype == VF_BF16) {
         size_t total = (size_t)(n_rows >> 4) * (K >> 5) * 64;
         int grid = (int)((total + 255) / 256 < 65535 ? (total + 255) / 256 : 65535);
         hipLaunchKernelGGL(pack_bf16_kernel, dim3(grid), dim3(256), 0, st, (const uint16_t *)src, (uint4 *)dst,
-                           n_rows, K, dst_nb0, dst_nb_stride);
+                           n_rows, K, dst_nb0, dst_nb_stride, perm_hd);
     } else {
         size_t total = (size_t)n_rows * K;
         int grid = (int)((total + 255) / 256 < 65535 ? (total + 255) / 256 : 65535);
         hipLaunchKernelGGL(pack_f32_kernel, dim3(grid), dim3(256), 0, st, (const float *)src, (float *)dst,
-                           n_rows, K, dst_nb0, dst_nb_stride);
+                           n_rows, K, dst_nb0, dst_nb_stride, perm_hd);
     }
     VF_LAUNCH_CHECK("pack");
     return VF_OK;

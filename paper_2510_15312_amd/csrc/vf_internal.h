@@ -163,7 +163,8 @@ int vf_launch_gemm(const vf_model *m, const void *W, const void *X, float *part,
                    int rows_total, int row_lo, int row_hi, int ld_rows, GemmPlan plan, hipStream_t st);
 
 int vf_launch_pack(const vf_model *m, const void *src, void *dst, int n_rows, int K, int dst_nb0,
-                   int dst_nb_stride, int dst_rows_total, hipStream_t st);
+                   int dst_nb_stride, int perm_hd, hipStream_t st);
+int vf_launch_pack_vec(const float *src, float *dst, int n, int perm_hd, hipStream_t st);
 int vf_launch_rope_table(const vf_model *m, hipStream_t st);
 int vf_launch_embed(const vf_model *m, const Batch &b, const int32_t *tokens, hipStream_t st);
 int vf_launch_norm(const vf_model *m, const float *gain, void *x_out, const float *part, int nparts,
