@@ -197,6 +197,14 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
               const float *logits_dev, int32_t *n_accept_dev, int32_t *out_tokens_dev,
               int32_t *y_dev, void *stream);
 
+/* ---- options ---------------------------------------------------------------------------------- */
+
+/* VF_OPT_FAST_PATH (default 1): vf_verify on a bfloat16 model with at most 48 rows in total runs
+ * the fused few-row kernels; 0 forces the general kernels (any row count), which compute the
+ * same function. */
+#define VF_OPT_FAST_PATH 1
+int vf_set_option(vf_model *m, int option, int value);
+
 /* ---- measurement hook (not part of the method) ---------------------------------------------- */
 
 /* Kernel sites timed by vf_profile: the five GEMMs of the forward pass, attention (both

@@ -18,12 +18,13 @@ VF_F32, VF_BF16 = 0, 1
 VF_GREEDY, VF_STOCHASTIC = 0, 1
 VF_PENDING = -1
 VF_MAX_BATCH, VF_MAX_DRAFTS = 32, 32
+VF_OPT_FAST_PATH = 1
 
 EXPORTS = [
     "vf_last_error", "vf_model_packed_bytes", "vf_model_create", "vf_model_destroy",
     "vf_seq_state_bytes", "vf_kv_bytes", "vf_seq_create", "vf_seq_destroy", "vf_seq_set_len",
     "vf_seq_set_pending", "vf_seq_get_state", "vf_kv_read", "vf_prefill_chunk", "vf_verify",
-    "vf_accept", "vf_profile", "vf_profile_read",
+    "vf_accept", "vf_profile", "vf_profile_read", "vf_set_option",
 ]
 SITES = ["qkv", "o", "gateup", "down", "head", "attn", "small", "accept"]
 
@@ -78,6 +79,7 @@ def _load():
         "vf_verify": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), vp, vp]),
         "vf_accept": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(vf_accept_params),
                                 vp, vp, vp, vp, vp]),
+        "vf_set_option": (C.c_int, [vp, C.c_int, C.c_int]),
         "vf_profile": (C.c_int, [vp, C.c_int]),
         "vf_profile_read": (C.c_int, [vp, C.POINTER(C.c_float), C.POINTER(i32)]),
     }
@@ -248,3 +250,7 @@ def vf_profile_read(model):
     cnt = (C.c_int32 * len(SITES))()
     _check(lib.vf_profile_read(model.handle, ms, cnt))
     return {s: (ms[i], cnt[i]) for i, s in enumerate(SITES)}
+
+
+def vf_set_option(model, option, value):
+    _check(lib.vf_set_option(model.handle, option, int(value)))

@@ -2,16 +2,17 @@
 // Sec. 4.3 "accepted prefix x_1..x_{e-1}, y_e"), greedy and stochastic, and the commit of the
 // sequence state (length, pending token) without a host round trip.
 //
-// Pass 1 (row_stats): per (row, vocabulary chunk) the maximum logit, its lowest index and, for
-// stochastic rows, sum exp((z - chunk max)/T) in float64.
-// Pass 2 (finalize): one workgroup per sequence merges the chunks in a fixed order, walks the
-// drafts, and if needed draws the replacement / bonus token by inverse CDF over the
-// vocabulary in id order, all in float64.
+//   row_stats : per (row, vocabulary chunk): maximum logit, its lowest index and, for stochastic
+//               rows, sum exp((z - chunk max)/T) in float64.
+//   decide    : one workgroup per sequence merges the chunks in a fixed order (arg-max y of every
+//               row, softmax normaliser), walks the drafts and fixes the accepted count a.  Greedy
+//               sequences are finished here.
+//   draw_sums : stochastic only: per vocabulary chunk the float64 sum of the weights the
+//               replacement (or bonus) token is drawn from at row a.
+//   emit      : inverse CDF in id order: finds the chunk, then the id inside it; commits the state.
 #include "vf_internal.h"
 
 namespace {
-
-constexpr int FIN_THREADS = 1024;
 
 struct MaxIdx {
     float v;
@@ -21,22 +22,30 @@ __device__ inline MaxIdx better(MaxIdx a, MaxIdx b) {
     if (b.v > a.v || (b.v == a.v && b.i < a.i)) return b;
     return a;
 }
-
-__global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict__ logits, int V, int n_chunks,
-                                                        Batch b, AcceptBatch ab, float *__restrict__ smax,
-                                                        int32_t *__restrict__ sidx, double *__restrict__ ssum) {
-    __shared__ MaxIdx rm[4];
-    __shared__ double rs[4];
-    const int row = blockIdx.y, chunk = blockIdx.x;
-    const int per = (V + n_chunks - 1) / n_chunks;
-    const int v0 = chunk * per, v1 = min(V, v0 + per);
-    const float *z = logits + (size_t)row * V;
-    MaxIdx best{-INFINITY, 0x7fffffff};
-    for (int v = v0 + threadIdx.x; v < v1; v += 256) best = better(best, MaxIdx{z[v], v});
+__device__ inline MaxIdx wave_best(MaxIdx best) {
     for (int off = 32; off > 0; off >>= 1) {
         MaxIdx o{__shfl_xor(best.v, off, 64), __shfl_xor(best.i, off, 64)};
         best = better(best, o);
     }
+    return best;
+}
+__device__ inline double wave_sum(double s) {
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    return s;
+}
+
+__global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict__ logits, int V, Batch b,
+                                                        AcceptBatch ab, float *__restrict__ smax,
+                                                        int32_t *__restrict__ sidx, double *__restrict__ ssum) {
+    __shared__ MaxIdx rm[4];
+    __shared__ double rs[4];
+    const int row = blockIdx.y, chunk = blockIdx.x;
+    const int per = (V + VF_STAT_CHUNKS - 1) / VF_STAT_CHUNKS;
+    const int v0 = min(V, chunk * per), v1 = min(V, v0 + per);
+    const float *z = logits + (size_t)row * V;
+    MaxIdx best{-INFINITY, 0x7fffffff};
+    for (int v = v0 + threadIdx.x; v < v1; v += 256) best = better(best, MaxIdx{z[v], v});
+    best = wave_best(best);
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) rm[wave] = best;
     __syncthreads();
@@ -46,191 +55,244 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict_
     if (a.mode == VF_STOCHASTIC && v0 < v1) {
         const double t = (double)a.temperature, cm = (double)best.v;
         for (int v = v0 + threadIdx.x; v < v1; v += 256) sum += exp(((double)z[v] - cm) / t);
-        for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        sum = wave_sum(sum);
         if ((threadIdx.x & 63) == 0) rs[wave] = sum;
         __syncthreads();
         sum = ((rs[0] + rs[1]) + rs[2]) + rs[3];
     }
     if (threadIdx.x == 0) {
-        const size_t o = (size_t)row * n_chunks + chunk;
+        const size_t o = (size_t)row * VF_STAT_CHUNKS + chunk;
         smax[o] = best.v;
         sidx[o] = best.i;
         ssum[o] = sum;
     }
 }
 
-// Inverse-CDF draw over the vocabulary in id order, by the whole workgroup.
-//   weight(v) = max(0, p_v - q_v)   (q given)          p_v = exp((z_v - zmax)/t) / S
-//             = p_v with p_x = 0    (one-hot drafter, x = excluded id)
-//             = p_v                 (bonus / first token: q == NULL and x < 0)
-// If every weight is zero the draw is from p.  Returns the smallest id whose running sum
-// exceeds u * total (same value in every thread).
-__device__ int draw_token(const float *__restrict__ z, int V, double zmax, double t, double S,
-                          const float *__restrict__ q, int x, double u, double *seg, int *result) {
-    const int per = (V + FIN_THREADS - 1) / FIN_THREADS;
-    const int v0 = min(V, (int)threadIdx.x * per), v1 = min(V, v0 + per);
-    for (int pass = 0; pass < 2; ++pass) {
-        const bool plain = pass == 1;
-        auto weight = [&](int v) -> double {
-            double p = exp(((double)z[v] - zmax) / t) / S;
-            if (plain) return p;
-            if (q) return fmax(p - (double)q[v], 0.0);
-            return v == x ? 0.0 : p;
-        };
-        double local = 0.0;
-        for (int v = v0; v < v1; ++v) local += weight(v);
-        __syncthreads();
-        seg[threadIdx.x] = local;
-        if (threadIdx.x == 0) *result = 0x7fffffff;
-        __syncthreads();
-        // exclusive prefix of the segment sums, in segment order (every thread the same way)
-        double before = 0.0, total = 0.0;
-        for (int j = 0; j < FIN_THREADS; ++j) {
-            if (j == (int)threadIdx.x) before = total;
-            total += seg[j];
-        }
-        if (total == 0.0 && !plain) continue;
-        const double target = u * total;
-        if (before <= target) {
-            double run = before;
-            for (int v = v0; v < v1; ++v) {
-                run += weight(v);
-                if (run > target) {
-                    atomicMin(result, v);
-                    break;
-                }
-            }
-        }
-        __syncthreads();
-        int w = *result;
-        if (w == 0x7fffffff) w = V - 1;  // rounding left the running sum at or below the target
-        __syncthreads();
-        return w;
-    }
-    return V - 1;
-}
-
-__global__ __launch_bounds__(FIN_THREADS) void accept_finalize_kernel(
-    const float *__restrict__ logits, int V, int n_chunks, Batch b, AcceptBatch ab,
-    const int32_t *__restrict__ tokens, const float *__restrict__ smax, const int32_t *__restrict__ sidx,
-    const double *__restrict__ ssum, int32_t *__restrict__ n_accept, int32_t *__restrict__ out_tokens,
-    int32_t *__restrict__ y) {
-    __shared__ double seg[FIN_THREADS];
+// commit_len == 0: only the pending token is written (first token after prefill).
+__global__ __launch_bounds__(256) void accept_decide_kernel(
+    const float *__restrict__ logits, int V, Batch b, AcceptBatch ab, const int32_t *__restrict__ tokens,
+    const float *__restrict__ smax, const int32_t *__restrict__ sidx, const double *__restrict__ ssum,
+    int32_t *__restrict__ n_accept, int32_t *__restrict__ out_tokens, int32_t *__restrict__ y,
+    DrawDesc *__restrict__ draw, int commit_len) {
     __shared__ double row_S[VF_MAX_DRAFTS + 1];
     __shared__ float row_max[VF_MAX_DRAFTS + 1];
     __shared__ int row_arg[VF_MAX_DRAFTS + 1];
-    __shared__ int sh_a, sh_result;
+    __shared__ int ok[VF_MAX_DRAFTS + 1];
     const SeqDesc &s = b.s[blockIdx.x];
     const AcceptDesc &a = ab.a[blockIdx.x];
     const int m = s.nrows, k = m - 1;
     const double t = (double)a.temperature;
-    if ((int)threadIdx.x < m) {
-        const size_t o = (size_t)(s.row0 + threadIdx.x) * n_chunks;
-        MaxIdx best{-INFINITY, 0x7fffffff};
-        for (int c = 0; c < n_chunks; ++c) best = better(best, MaxIdx{smax[o + c], sidx[o + c]});
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int r = wave; r < m; r += 4) {
+        const size_t o = (size_t)(s.row0 + r) * VF_STAT_CHUNKS + lane;  // one chunk per lane
+        const MaxIdx mine{smax[o], sidx[o]};
+        const MaxIdx best = wave_best(mine);
         double S = 0.0;
-        if (a.mode == VF_STOCHASTIC)
-            for (int c = 0; c < n_chunks; ++c)
-                if (ssum[o + c] != 0.0) S += ssum[o + c] * exp(((double)smax[o + c] - (double)best.v) / t);
-        row_S[threadIdx.x] = S;
-        row_max[threadIdx.x] = best.v;
-        row_arg[threadIdx.x] = best.i;
-        y[s.row0 + threadIdx.x] = best.i;
+        if (a.mode == VF_STOCHASTIC) {
+            const double sm = ssum[o];
+            S = wave_sum(sm != 0.0 ? sm * exp(((double)mine.v - (double)best.v) / t) : 0.0);
+        }
+        if (lane == 0) {
+            row_S[r] = S;
+            row_max[r] = best.v;
+            row_arg[r] = best.i;
+            y[s.row0 + r] = best.i;
+        }
     }
     __syncthreads();
     const int32_t *drafts = tokens + s.row0 + 1;
-    if (threadIdx.x == 0) {
-        int acc = 0;
+    if ((int)threadIdx.x < k) {
+        const int i = threadIdx.x, x = drafts[i];
+        int good;
         if (a.mode == VF_GREEDY) {
-            while (acc < k && drafts[acc] == row_arg[acc]) ++acc;
+            good = x == row_arg[i];
+        } else if (x < 0 || x >= V) {
+            good = 0;
         } else {
-            for (; acc < k; ++acc) {
-                const int x = drafts[acc];
-                if (x < 0 || x >= V) break;
-                const float *z = logits + (size_t)(s.row0 + acc) * V;
-                const double px = exp(((double)z[x] - (double)row_max[acc]) / t) / row_S[acc];
-                const double qx = a.q ? (double)a.q[(size_t)acc * V + x] : 1.0;
-                if (!((double)a.u[acc] * qx < px)) break;
-            }
+            const float *z = logits + (size_t)(s.row0 + i) * V;
+            const double px = exp(((double)z[x] - (double)row_max[i]) / t) / row_S[i];
+            const double qx = a.q ? (double)a.q[(size_t)i * V + x] : 1.0;
+            good = (double)a.u[i] * qx < px;
         }
-        sh_a = acc;
+        ok[i] = good;
     }
     __syncthreads();
-    const int acc = sh_a;
-    int emitted;
-    if (a.mode == VF_GREEDY) {
-        emitted = row_arg[acc];
-    } else {
-        const float *z = logits + (size_t)(s.row0 + acc) * V;
-        const float *q = (acc < k && a.q) ? a.q + (size_t)acc * V : nullptr;
-        const int x = (acc < k && !a.q) ? drafts[acc] : -1;
-        emitted = draw_token(z, V, (double)row_max[acc], t, row_S[acc], q, x, (double)a.u[m + acc], seg,
-                             &sh_result);
-    }
+    int acc = 0;
+    while (acc < k && ok[acc]) ++acc;
     if ((int)threadIdx.x < m) {
         int v = -1;
         if ((int)threadIdx.x < acc) v = drafts[threadIdx.x];
-        else if ((int)threadIdx.x == acc) v = emitted;
+        else if ((int)threadIdx.x == acc && a.mode == VF_GREEDY) v = row_arg[acc];
         out_tokens[s.row0 + threadIdx.x] = v;
     }
     if (threadIdx.x == 0) {
         n_accept[blockIdx.x] = acc;
-        s.state[0] += 1 + acc;
-        s.state[1] = emitted;
+        DrawDesc d;
+        d.zmax = (double)row_max[acc];
+        d.S = row_S[acc];
+        d.active = a.mode == VF_STOCHASTIC;
+        d.acc = acc;
+        d.row = s.row0 + acc;
+        d.q = (acc < k && a.q) ? a.q + (size_t)acc * V : nullptr;
+        d.x_excl = (acc < k && !a.q) ? drafts[acc] : -1;
+        d.u = d.active ? (double)a.u[m + acc] : 0.0;
+        d.t = t;
+        draw[blockIdx.x] = d;
+        if (a.mode == VF_GREEDY) {
+            if (commit_len) s.state[0] += 1 + acc;
+            s.state[1] = row_arg[acc];
+        }
     }
 }
 
-// First generated token from one row of logits: arg-max (temperature 0) or a draw from
-// softmax(z / temperature); written to the sequence's pending token.
-__global__ __launch_bounds__(FIN_THREADS) void first_token_kernel(const float *__restrict__ z, int V,
-                                                                  const float *__restrict__ u, float temperature,
-                                                                  int32_t *__restrict__ state) {
-    __shared__ double seg[FIN_THREADS];
-    __shared__ MaxIdx rm[FIN_THREADS / 64];
-    __shared__ int sh_result;
-    MaxIdx best{-INFINITY, 0x7fffffff};
-    for (int v = threadIdx.x; v < V; v += FIN_THREADS) best = better(best, MaxIdx{z[v], v});
-    for (int off = 32; off > 0; off >>= 1) {
-        MaxIdx o{__shfl_xor(best.v, off, 64), __shfl_xor(best.i, off, 64)};
-        best = better(best, o);
-    }
-    if ((threadIdx.x & 63) == 0) rm[threadIdx.x >> 6] = best;
+// weight of id v in the draw at the deciding row:
+//   max(0, p_v - q_v)  (dense draft distribution),  p_v with p_x = 0  (one-hot drafter),
+//   p_v  (bonus token / first token / every residual weight zero),  p_v = exp((z_v - zmax)/T) / S.
+__device__ inline double draw_weight(const float *__restrict__ z, const DrawDesc &d, int v, bool plain) {
+    const double p = exp(((double)z[v] - d.zmax) / d.t) / d.S;
+    if (plain) return p;
+    if (d.q) return fmax(p - (double)d.q[v], 0.0);
+    return v == d.x_excl ? 0.0 : p;
+}
+
+__device__ inline double chunk_weight_sum(const float *__restrict__ z, const DrawDesc &d, int v0, int v1,
+                                          bool plain, double *rs) {
+    double sum = 0.0;
+    for (int v = v0 + threadIdx.x; v < v1; v += 256) sum += draw_weight(z, d, v, plain);
+    sum = wave_sum(sum);
     __syncthreads();
-    best = rm[0];
-    for (int i = 1; i < FIN_THREADS / 64; ++i) best = better(best, rm[i]);
-    int tok = best.i;
-    if (temperature > 0.f) {
-        const double t = (double)temperature;
-        double local = 0.0;
-        for (int v = threadIdx.x; v < V; v += FIN_THREADS) local += exp(((double)z[v] - (double)best.v) / t);
+    if ((threadIdx.x & 63) == 0) rs[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    return ((rs[0] + rs[1]) + rs[2]) + rs[3];
+}
+
+__global__ __launch_bounds__(256) void draw_sums_kernel(const float *__restrict__ logits, int V,
+                                                        const DrawDesc *__restrict__ draw,
+                                                        double *__restrict__ wsum) {
+    __shared__ double rs[4];
+    const DrawDesc d = draw[blockIdx.y];
+    if (!d.active) return;
+    const int per = (V + VF_STAT_CHUNKS - 1) / VF_STAT_CHUNKS;
+    const int v0 = min(V, (int)blockIdx.x * per), v1 = min(V, v0 + per);
+    const double sum = chunk_weight_sum(logits + (size_t)d.row * V, d, v0, v1, false, rs);
+    if (threadIdx.x == 0) wsum[blockIdx.y * VF_STAT_CHUNKS + blockIdx.x] = sum;
+}
+
+__global__ __launch_bounds__(256) void accept_emit_kernel(const float *__restrict__ logits, int V, Batch b,
+                                                          const DrawDesc *__restrict__ draw,
+                                                          const double *__restrict__ wsum,
+                                                          int32_t *__restrict__ out_tokens, int commit_len) {
+    __shared__ double cs[VF_STAT_CHUNKS];
+    __shared__ double seg[256];
+    __shared__ double rs[4];
+    __shared__ int result;
+    const DrawDesc d = draw[blockIdx.x];
+    if (!d.active) return;
+    const SeqDesc &s = b.s[blockIdx.x];
+    const float *z = logits + (size_t)d.row * V;
+    const int per = (V + VF_STAT_CHUNKS - 1) / VF_STAT_CHUNKS;
+    if (threadIdx.x < VF_STAT_CHUNKS) cs[threadIdx.x] = wsum[blockIdx.x * VF_STAT_CHUNKS + threadIdx.x];
+    __syncthreads();
+    double total = 0.0;
+    for (int c = 0; c < VF_STAT_CHUNKS; ++c) total += cs[c];
+    bool plain = false;
+    if (total == 0.0) {
+        // every residual weight is zero: draw from p itself (sums recomputed here; rare)
+        plain = true;
+        for (int c = 0; c < VF_STAT_CHUNKS; ++c) {
+            const int v0 = min(V, c * per), v1 = min(V, v0 + per);
+            const double sum = chunk_weight_sum(z, d, v0, v1, true, rs);
+            if (threadIdx.x == 0) cs[c] = sum;
+        }
         __syncthreads();
-        seg[threadIdx.x] = local;
-        __syncthreads();
-        double S = 0.0;
-        for (int j = 0; j < FIN_THREADS; ++j) S += seg[j];
-        tok = draw_token(z, V, (double)best.v, t, S, nullptr, -1, (double)u[0], seg, &sh_result);
+        total = 0.0;
+        for (int c = 0; c < VF_STAT_CHUNKS; ++c) total += cs[c];
     }
-    if (threadIdx.x == 0) state[1] = tok;
+    const double target = d.u * total;
+    // first chunk whose inclusive prefix exceeds the target
+    int cstar = VF_STAT_CHUNKS - 1;
+    double before_chunk = 0.0;
+    {
+        double run = 0.0;
+        for (int c = 0; c < VF_STAT_CHUNKS; ++c) {
+            if (run + cs[c] > target) { cstar = c; before_chunk = run; break; }
+            run += cs[c];
+            if (c == VF_STAT_CHUNKS - 1) before_chunk = run - cs[c];
+        }
+    }
+    const int v0 = min(V, cstar * per), v1 = min(V, v0 + per);
+    const int per_t = (v1 - v0 + 255) / 256;
+    const int a0 = min(v1, v0 + (int)threadIdx.x * per_t), a1 = min(v1, a0 + per_t);
+    double local = 0.0;
+    for (int v = a0; v < a1; ++v) local += draw_weight(z, d, v, plain);
+    seg[threadIdx.x] = local;
+    if (threadIdx.x == 0) result = 0x7fffffff;
+    __syncthreads();
+    double before = before_chunk;
+    for (int j = 0; j < (int)threadIdx.x; ++j) before += seg[j];
+    if (before <= target) {
+        double run = before;
+        for (int v = a0; v < a1; ++v) {
+            run += draw_weight(z, d, v, plain);
+            if (run > target) { atomicMin(&result, v); break; }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int w = result;
+        if (w == 0x7fffffff) w = max(v0, v1 - 1);  // rounding left the running sum at the target
+        out_tokens[s.row0 + d.acc] = w;
+        if (commit_len) s.state[0] += 1 + d.acc;
+        s.state[1] = w;
+    }
+}
+
+int launch_all(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
+               const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y, int commit_len,
+               hipStream_t st) {
+    const int V = m->cfg.vocab;
+    hipLaunchKernelGGL(row_stats_kernel, dim3(VF_STAT_CHUNKS, b.total_rows), dim3(256), 0, st, logits, V, b, ab,
+                       m->stat_max, m->stat_idx, m->stat_sum);
+    VF_LAUNCH_CHECK("row_stats");
+    hipLaunchKernelGGL(accept_decide_kernel, dim3(b.n_seqs), dim3(256), 0, st, logits, V, b, ab, tokens,
+                       m->stat_max, m->stat_idx, m->stat_sum, n_accept, out_tokens, y, m->draw, commit_len);
+    VF_LAUNCH_CHECK("accept_decide");
+    bool any = false;
+    for (int i = 0; i < b.n_seqs; ++i) any = any || ab.a[i].mode == VF_STOCHASTIC;
+    if (!any) return VF_OK;
+    hipLaunchKernelGGL(draw_sums_kernel, dim3(VF_STAT_CHUNKS, b.n_seqs), dim3(256), 0, st, logits, V, m->draw,
+                       m->draw_sums);
+    VF_LAUNCH_CHECK("draw_sums");
+    hipLaunchKernelGGL(accept_emit_kernel, dim3(b.n_seqs), dim3(256), 0, st, logits, V, b, m->draw,
+                       m->draw_sums, out_tokens, commit_len);
+    VF_LAUNCH_CHECK("accept_emit");
+    return VF_OK;
 }
 
 }  // namespace
 
 int vf_launch_accept(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
                      const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y, hipStream_t st) {
-    const int V = m->cfg.vocab;
-    hipLaunchKernelGGL(row_stats_kernel, dim3(m->n_chunks, b.total_rows), dim3(256), 0, st, logits, V,
-                       m->n_chunks, b, ab, m->stat_max, m->stat_idx, m->stat_sum);
-    VF_LAUNCH_CHECK("row_stats");
-    hipLaunchKernelGGL(accept_finalize_kernel, dim3(b.n_seqs), dim3(FIN_THREADS), 0, st, logits, V, m->n_chunks,
-                       b, ab, tokens, m->stat_max, m->stat_idx, m->stat_sum, n_accept, out_tokens, y);
-    VF_LAUNCH_CHECK("accept_finalize");
-    return VF_OK;
+    return launch_all(m, b, ab, tokens, logits, n_accept, out_tokens, y, 1, st);
 }
 
+// First generated token from one row of logits: arg-max (temperature 0) or a draw from
+// softmax(z / temperature): acceptance with no drafts whose "bonus" token becomes the pending
+// token; the length is left alone.
 int vf_launch_first_token(const vf_model *m, const SeqDesc &s, const float *logits_row, const float *u,
                           float temperature, hipStream_t st) {
-    hipLaunchKernelGGL(first_token_kernel, dim3(1), dim3(FIN_THREADS), 0, st, logits_row, m->cfg.vocab, u,
-                       temperature, s.state);
-    VF_LAUNCH_CHECK("first_token");
-    return VF_OK;
+    Batch b;
+    b.n_seqs = 1;
+    b.total_rows = 1;
+    b.s[0] = s;
+    b.s[0].row0 = 0;
+    b.s[0].nrows = 1;
+    AcceptBatch ab;
+    ab.a[0].q = nullptr;
+    ab.a[0].u = u;  // u[m + acc] with m = 1, acc = 0 is u[1]: see the shift below
+    ab.a[0].temperature = temperature > 0.f ? temperature : 1.f;
+    ab.a[0].mode = temperature > 0.f ? VF_STOCHASTIC : VF_GREEDY;
+    if (u) ab.a[0].u = u - 1;  // the draw reads u[1]; the caller's single uniform sits at u[0]
+    int32_t *scratch = m->scratch_i32;
+    return launch_all(m, b, ab, scratch + 8, logits_row, scratch, scratch + 16, scratch + 24, 0, st);
 }

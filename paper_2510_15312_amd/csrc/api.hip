@@ -84,12 +84,16 @@ size_t carve_model(vf_model *m, char *base) {
     if (nq + 2 * nkv > widest) widest = nq + 2 * nkv;
     m->part_floats = R * widest * 2;  // room for two partials of the widest layer GEMM
     m->part = (float *)cv.take(m->part_floats * 4);
-    m->attn_part = (float *)cv.take(R * c.n_q_heads * 16 * (hd + 2) * 4);
+    m->attn_part = (float *)cv.take(R * c.n_q_heads * 16 * (hd + 4) * 4);
     m->logits = (float *)cv.take(R * V * 4);
-    m->n_chunks = 64;
-    m->stat_max = (float *)cv.take(R * m->n_chunks * 4);
-    m->stat_idx = (int32_t *)cv.take(R * m->n_chunks * 4);
-    m->stat_sum = (double *)cv.take(R * m->n_chunks * 8);
+    m->stat_max = (float *)cv.take(R * VF_STAT_CHUNKS * 4);
+    m->stat_idx = (int32_t *)cv.take(R * VF_STAT_CHUNKS * 4);
+    m->stat_sum = (double *)cv.take(R * VF_STAT_CHUNKS * 8);
+    m->draw = (DrawDesc *)cv.take(sizeof(DrawDesc) * VF_MAX_BATCH);
+    m->draw_sums = (double *)cv.take((size_t)VF_MAX_BATCH * VF_STAT_CHUNKS * 8);
+    m->scratch_i32 = (int32_t *)cv.take(64 * 4);
+    m->ss = (float *)cv.take((d / 16) * 64 * 4);
+    m->counters = (int32_t *)cv.take(VF_N_COUNTERS * 4);
     return (cv.off + 255) & ~(size_t)255;
 }
 
@@ -106,25 +110,6 @@ SeqDesc describe(const vf_seq *s, int row0, int nrows) {
     d.pad = 0;
     return d;
 }
-
-// Brackets a launch group with two events when profiling is on.
-struct ProfScope {
-    vf_model *m;
-    hipStream_t st;
-    hipEvent_t b = nullptr;
-    ProfScope(vf_model *m_, int site, hipStream_t st_) : m(m_), st(st_) {
-        if (!m->prof_on) return;
-        hipEvent_t ev[2];
-        for (int i = 0; i < 2; ++i) {
-            if (!m->prof_pool->empty()) { ev[i] = m->prof_pool->back(); m->prof_pool->pop_back(); }
-            else if (hipEventCreate(&ev[i]) != hipSuccess) { if (i) m->prof_pool->push_back(ev[0]); return; }
-        }
-        (void)hipEventRecord(ev[0], st);
-        m->prof->push_back({site, ev[0], ev[1]});
-        b = ev[1];
-    }
-    ~ProfScope() { if (b) (void)hipEventRecord(b, st); }
-};
 
 // One pass of the decoder stack over the rows of `b`; leaves the residual stream in m->h with
 // the last down-projection still in (part, nparts) form: *tail_parts tells the caller how many
@@ -213,6 +198,7 @@ int vf_model_create(const vf_config *cfg, const vf_weights *w, void *packed_dev,
     memset(m, 0, sizeof *m);
     m->cfg = *cfg;
     m->es = cfg->dtype == VF_BF16 ? 2 : 4;
+    m->fast_path = 1;
     m->prof = new std::vector<vf_model::ProfRec>();
     m->prof_pool = new std::vector<hipEvent_t>();
     m->layers = new (std::nothrow) LayerPacked[cfg->n_layers];
@@ -433,10 +419,14 @@ int vf_verify(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
             return vf_fail(VF_ERR_CAP, "vf_verify: sequence %d: %d + %d > capacity %d", i, seqs[i]->len_ub,
                            b.s[i].nrows, seqs[i]->capacity);
     hipStream_t st = (hipStream_t)stream;
-    int tail = 0;
-    if ((rc = run_layers(m, b, tokens_dev, &tail, st))) return rc;
     float *dst = logits_out_dev ? logits_out_dev : m->logits;
-    if ((rc = run_head(m, b.total_rows, tail, 0, b.total_rows, dst, st))) return rc;
+    if (m->fast_path && vf_fast_path_ok(m, b.total_rows)) {
+        if ((rc = vf_run_fast(m, b, tokens_dev, dst, st))) return rc;
+    } else {
+        int tail = 0;
+        if ((rc = run_layers(m, b, tokens_dev, &tail, st))) return rc;
+        if ((rc = run_head(m, b.total_rows, tail, 0, b.total_rows, dst, st))) return rc;
+    }
     m->last_logits = dst;
     m->last_rows = b.total_rows;
     return VF_OK;
@@ -477,6 +467,12 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
     }
     for (int i = 0; i < n_seqs; ++i) seqs[i]->len_ub += b.s[i].nrows;
     return VF_OK;
+}
+
+int vf_set_option(vf_model *m, int option, int value) {
+    if (!m) return vf_fail(VF_ERR_ARG, "vf_set_option: NULL");
+    if (option == VF_OPT_FAST_PATH) { m->fast_path = value != 0; return VF_OK; }
+    return vf_fail(VF_ERR_ARG, "vf_set_option: unknown option %d", option);
 }
 
 int vf_profile(vf_model *m, int enable) {

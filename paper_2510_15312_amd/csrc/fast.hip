@@ -1,0 +1,595 @@
+// The verify hot path for few rows (pending token + drafts, paper Sec. 3 / Sec. 4.3), bfloat16.
+//
+// Per decoder layer four fused GEMM kernels, attention and its merge:
+//   QKV     : x * Wqkv^T          -> row scale, bias, rotary embedding, q and KV-cache append
+//   attn    : split-KV causal attention of all rows over the cache (MFMA), then the merge
+//   O       : o * Wo^T            -> residual add, next norm's input and sums of squares
+//   gate/up : x * [Wg|Wu]^T       -> row scale, SwiGLU
+//   down    : a * Wd^T            -> residual add, next norm's input and sums of squares
+// and the output head  x * E^T -> row scale -> float32 logits.
+//
+// RMSNorm is split around the GEMM that consumes it: the producer of the residual stream h
+// writes x = bf16(h * gain) and per-16-column sums of h^2; the consumer multiplies its
+// accumulators by rsqrt(mean(h^2) + eps) of the row.  This is the same product
+// (h * gain * rstd) * W with the row factor moved outside the dot product.
+//
+// GEMM kernel: one workgroup per unit of UB weight blocks (16 rows each); its wavefronts split
+// the K range, stream their weight fragments from HBM straight into registers (1 KiB per
+// wavefront load, read once, non-temporal) and take the activations from LDS.  Wavefront
+// partial sums are added in LDS in a fixed order.  With a K split across workgroups (ks > 1)
+// each workgroup leaves its partial tile in memory and the last one to arrive adds them in split
+// order, so results do not depend on timing.
+#include "vf_internal.h"
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int FAST_THREADS = 512;
+constexpr int FAST_WAVES = FAST_THREADS / 64;
+
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+
+struct FastGemm {
+    const u32x4 *W;   // packed fragments
+    int N, KB;        // output features, K / 32
+    const bf16_t *X;  // [m, K] row-major
+    int m;
+    int ks, kbps;     // K split across workgroups, k-blocks per split
+    int kch;          // k-blocks staged in LDS at a time
+    float *part;      // ks > 1: partial tiles
+    int *counters;    // ks > 1: arrivals per unit
+    const float *ss_in;  // per-16-column sums of squares of the rows of h, [n_ss][64]
+    int n_ss;
+    float inv_d, eps;
+    // EPI_RESID
+    float *h;
+    const float *gain_next;
+    bf16_t *xg_out;
+    float *ss_out;
+    // EPI_SWIGLU
+    bf16_t *a_out;
+    int F;
+    // EPI_LOGITS
+    float *logits;
+    // EPI_QKV
+    const float *bias, *cosv, *sinv;
+    bf16_t *q;
+    int layer, hq, hkv, hd;
+};
+
+__device__ inline u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+
+__device__ inline void store_coherent(float *p, floatx4 v) {
+    __hip_atomic_store(p + 0, v[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 1, v[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 2, v[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 3, v[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline floatx4 load_coherent(const float *p) {
+    floatx4 v;
+    v[0] = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v[1] = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v[2] = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v[3] = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return v;
+}
+
+__device__ inline u32x2 pack4_bf16(float a, float b, float c, float d) {
+    bf16x4 v = {(bf16_t)a, (bf16_t)b, (bf16_t)c, (bf16_t)d};
+    return __builtin_bit_cast(u32x2, v);
+}
+
+// ---- epilogues: thread holds Y[row][n0 .. n0+3] ------------------------------------------------
+
+__device__ inline void epi_resid(const FastGemm &g, int row, bool live, int nb, int lane, floatx4 v) {
+    const int n0 = nb * 16 + (lane >> 4) * 4;
+    floatx4 hv = {0.f, 0.f, 0.f, 0.f};
+    if (live) {
+        float *hp = g.h + (size_t)row * g.N + n0;
+        hv = *reinterpret_cast<floatx4 *>(hp) + v;
+        *reinterpret_cast<floatx4 *>(hp) = hv;
+        const floatx4 gn = *reinterpret_cast<const floatx4 *>(g.gain_next + n0);
+        *reinterpret_cast<u32x2 *>(g.xg_out + (size_t)row * g.N + n0) =
+            pack4_bf16(hv[0] * gn[0], hv[1] * gn[1], hv[2] * gn[2], hv[3] * gn[3]);
+    }
+    float ssq = hv[0] * hv[0] + hv[1] * hv[1] + hv[2] * hv[2] + hv[3] * hv[3];
+    ssq += __shfl_xor(ssq, 16, 64);
+    ssq += __shfl_xor(ssq, 32, 64);
+    if (live && (lane >> 4) == 0) g.ss_out[nb * 64 + row] = ssq;
+}
+
+__device__ inline void epi_qkv(const FastGemm &g, const Batch &b, int row, int nb, int lane, floatx4 v, float rs) {
+    const int n0 = nb * 16 + (lane >> 4) * 4;
+    const int hd = g.hd, half = hd >> 1;
+    for (int i = 0; i < 4; ++i) v[i] *= rs;
+    if (g.bias)
+        for (int i = 0; i < 4; ++i) v[i] += g.bias[n0 + i];
+    const SeqDesc &s = b.s[find_seq(b, row)];
+    const int pos = s.state[0] + (row - s.row0);
+    if (pos < 0 || pos >= s.capacity) return;
+    const int head = n0 / hd, p0 = n0 % hd;
+    bf16_t *kv = reinterpret_cast<bf16_t *>(s.kv);
+    if (head < g.hq + g.hkv) {
+        const int i0 = p0 >> 1;  // packed columns 2i, 2i+1 are elements i and i + hd/2
+        const float c0 = g.cosv[(size_t)pos * half + i0], s0 = g.sinv[(size_t)pos * half + i0];
+        const float c1 = g.cosv[(size_t)pos * half + i0 + 1], s1 = g.sinv[(size_t)pos * half + i0 + 1];
+        const float a0 = v[0] * c0 - v[1] * s0, b0 = v[1] * c0 + v[0] * s0;
+        const float a1 = v[2] * c1 - v[3] * s1, b1 = v[3] * c1 + v[2] * s1;
+        bf16_t *dst;
+        if (head < g.hq) {
+            dst = g.q + ((size_t)row * g.hq + head) * hd;
+        } else {
+            const int page = kv_page(s, pos), tin = pos % VF_TILE;
+            dst = kv + kv_k_index(g.layer, s.n_pages, page, g.hkv, head - g.hq, tin, 0, hd);
+        }
+        dst[i0] = (bf16_t)a0;
+        dst[i0 + 1] = (bf16_t)a1;
+        dst[i0 + half] = (bf16_t)b0;
+        dst[i0 + half + 1] = (bf16_t)b1;
+    } else {
+        const int vh = head - g.hq - g.hkv;
+        const int page = kv_page(s, pos), tin = pos % VF_TILE;
+        for (int i = 0; i < 4; ++i)
+            kv[kv_v_index(g.layer, s.n_pages, page, g.hkv, vh, tin, p0 + i, hd)] = (bf16_t)v[i];
+    }
+}
+
+__device__ inline void epi_swiglu(const FastGemm &g, int row, int nb_gate, int lane, floatx4 vg, floatx4 vu, float rs) {
+    const int f0 = (nb_gate >> 1) * 16 + (lane >> 4) * 4;
+    float o[4];
+    for (int i = 0; i < 4; ++i) {
+        const float gt = vg[i] * rs, up = vu[i] * rs;
+        o[i] = gt / (1.0f + __expf(-gt)) * up;
+    }
+    *reinterpret_cast<u32x2 *>(g.a_out + (size_t)row * g.F + f0) = pack4_bf16(o[0], o[1], o[2], o[3]);
+}
+
+// NB: 16-row activation blocks (rows <= 16*NB); UB: weight blocks per unit; PD: fragments in flight
+// per weight stream and wavefront.
+template <int NB, int UB, int PD, int EPI>
+__global__ __launch_bounds__(FAST_THREADS) void gemm_fast_kernel(FastGemm g, Batch b) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    u32x4 *xs = reinterpret_cast<u32x4 *>(smem_raw);
+    floatx4 *red = reinterpret_cast<floatx4 *>(smem_raw);
+    __shared__ float rs_s[64];
+    __shared__ float rs_tmp[FAST_WAVES][64];
+    __shared__ int s_last;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m = g.m, KB = g.KB, NBt = g.N >> 4;
+    const int unit = blockIdx.x, split = blockIdx.y;
+    const int nb0 = unit * UB;
+    const int kb0 = split * g.kbps, kb1 = min(KB, kb0 + g.kbps);
+
+    floatx4 acc[UB][NB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u)
+#pragma unroll
+        for (int c = 0; c < NB; ++c) acc[u][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const u32x4 *wp[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) wp[u] = g.W + (size_t)min(nb0 + u, NBt - 1) * KB * 64 + lane;
+    int rowc[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) rowc[c] = min(c * 16 + (lane & 15), m - 1);
+
+    // row scale rstd[row] from the per-block sums of squares
+    if (EPI != EPI_RESID) {
+        float sum = 0.f;  // lane = row, wavefront = every 8th block of 16 columns
+        if (lane < m)
+            for (int j = wave; j < g.n_ss; j += FAST_WAVES) sum += g.ss_in[j * 64 + lane];
+        rs_tmp[wave][lane] = sum;
+    }
+
+    for (int kc0 = kb0; kc0 < kb1; kc0 += g.kch) {
+        const int kc1 = min(kb1, kc0 + g.kch), nk = kc1 - kc0;
+        const int wk0 = kc0 + nk * wave / FAST_WAVES, wk1 = kc0 + nk * (wave + 1) / FAST_WAVES, nw = wk1 - wk0;
+        u32x4 w[PD][UB];
+#pragma unroll
+        for (int d = 0; d < PD; ++d)
+            if (d < nw)
+#pragma unroll
+                for (int u = 0; u < UB; ++u) w[d][u] = load_stream(wp[u] + (size_t)(wk0 + d) * 64);
+        __syncthreads();  // previous chunk consumed
+        const int chunks = nk * 4;
+        for (int idx = tid; idx < m * chunks; idx += FAST_THREADS) {
+            const int row = idx / chunks, c = idx % chunks;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(g.X + (size_t)row * KB * 32 + (size_t)kc0 * 32 + c * 8);
+            xs[((c >> 2) * m + row) * 4 + (c & 3)] = v;
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int k0 = 0; k0 < nw; k0 += PD) {
+#pragma unroll
+            for (int d = 0; d < PD; ++d) {
+                const int kbl = k0 + d;
+                if (kbl < nw) {
+                    bf16x8 a[UB];
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) a[u] = __builtin_bit_cast(bf16x8, w[d][u]);
+                    if (kbl + PD < nw)
+#pragma unroll
+                        for (int u = 0; u < UB; ++u) w[d][u] = load_stream(wp[u] + (size_t)(wk0 + kbl + PD) * 64);
+                    const int kx = wk0 + kbl - kc0;
+#pragma unroll
+                    for (int c = 0; c < NB; ++c) {
+                        const bf16x8 bb = __builtin_bit_cast(bf16x8, xs[(kx * m + rowc[c]) * 4 + (lane >> 4)]);
+#pragma unroll
+                        for (int u = 0; u < UB; ++u)
+                            acc[u][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], bb, acc[u][c], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();  // activations no longer needed: the same LDS now takes the wavefront partials
+#pragma unroll
+    for (int u = 0; u < UB; ++u)
+#pragma unroll
+        for (int c = 0; c < NB; ++c) red[((wave * UB + u) * NB + c) * 64 + lane] = acc[u][c];
+    if (EPI != EPI_RESID && tid < 64) {
+        float sum = 0.f;
+        for (int j = 0; j < FAST_WAVES; ++j) sum += rs_tmp[j][tid];
+        rs_s[tid] = 1.0f / sqrtf(sum * g.inv_d + g.eps);
+    }
+    __syncthreads();
+
+    constexpr int NT = UB * NB * 64;   // tiles of 4 outputs per unit
+    constexpr int NTH = EPI == EPI_SWIGLU ? NB * 64 : NT;  // threads that run the epilogue
+    floatx4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
+    int u = 0, c = 0;
+    if (tid < NTH) {
+        if (EPI == EPI_SWIGLU) {
+            c = tid >> 6;
+            for (int w = 0; w < FAST_WAVES; ++w) {
+                v0 += red[((w * UB + 0) * NB + c) * 64 + lane];
+                v1 += red[((w * UB + 1) * NB + c) * 64 + lane];
+            }
+        } else {
+            u = tid / (NB * 64);
+            c = (tid >> 6) % NB;
+            for (int w = 0; w < FAST_WAVES; ++w) v0 += red[((w * UB + u) * NB + c) * 64 + lane];
+        }
+    }
+    if (g.ks > 1) {
+        float *mine = g.part + ((size_t)(unit * g.ks + split) * NT) * 4;
+        if (tid < NTH) {
+            if (EPI == EPI_SWIGLU) {
+                store_coherent(mine + (size_t)(c * 64 + lane) * 4, v0);
+                store_coherent(mine + (size_t)((NB + c) * 64 + lane) * 4, v1);
+            } else {
+                store_coherent(mine + (size_t)tid * 4, v0);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (tid == 0) {
+            const int old = __hip_atomic_fetch_add(g.counters + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = old == g.ks - 1;
+            if (s_last) __hip_atomic_store(g.counters + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (!s_last) return;
+        v0 = floatx4{0.f, 0.f, 0.f, 0.f};
+        v1 = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (tid < NTH) {
+            for (int sp = 0; sp < g.ks; ++sp) {
+                const float *p = g.part + ((size_t)(unit * g.ks + sp) * NT) * 4;
+                if (EPI == EPI_SWIGLU) {
+                    v0 += load_coherent(p + (size_t)(c * 64 + lane) * 4);
+                    v1 += load_coherent(p + (size_t)((NB + c) * 64 + lane) * 4);
+                } else {
+                    v0 += load_coherent(p + (size_t)tid * 4);
+                }
+            }
+        }
+    }
+    if (tid >= NTH) return;
+    const int nb = nb0 + u;
+    const int row = c * 16 + (lane & 15);
+    const bool live = row < m && nb < NBt;
+    if (EPI == EPI_RESID) {
+        epi_resid(g, row, live, nb, lane, v0);
+    } else if (live) {
+        const float rs = rs_s[row];
+        if (EPI == EPI_QKV) epi_qkv(g, b, row, nb, lane, v0, rs);
+        else if (EPI == EPI_SWIGLU) epi_swiglu(g, row, nb, lane, v0, v1, rs);
+        else *reinterpret_cast<floatx4 *>(g.logits + (size_t)row * g.N + nb * 16 + (lane >> 4) * 4) = v0 * rs;
+    }
+}
+
+// ---- embedding ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void embed_fast_kernel(const bf16_t *__restrict__ E, const int32_t *__restrict__ tokens,
+                                                         Batch b, float *__restrict__ h, bf16_t *__restrict__ xg,
+                                                         const float *__restrict__ gain, float *__restrict__ ss,
+                                                         int d, int vocab) {
+    const int row = blockIdx.x;
+    int tok = tokens[row];
+    if (tok == VF_PENDING) tok = b.s[find_seq(b, row)].state[1];
+    if (tok < 0 || tok >= vocab) tok = 0;
+    for (int k0 = 0; k0 < d; k0 += 256) {
+        const int k = k0 + threadIdx.x;
+        float v = 0.f;
+        if (k < d) {
+            v = (float)E[wfrag_index(tok, k, d)];
+            h[(size_t)row * d + k] = v;
+            xg[(size_t)row * d + k] = (bf16_t)(v * gain[k]);
+        }
+        float sq = v * v;
+        sq += __shfl_xor(sq, 8, 64);
+        sq += __shfl_xor(sq, 4, 64);
+        sq += __shfl_xor(sq, 2, 64);
+        sq += __shfl_xor(sq, 1, 64);
+        if (k < d && (threadIdx.x & 15) == 0) ss[(k >> 4) * 64 + row] = sq;
+    }
+}
+
+// ---- attention ----------------------------------------------------------------------------------
+constexpr int ATTF_STRIDE_PAD = 4;  // partial record: [max, sum, -, -, O[hd]]
+
+// One workgroup: one kv head of one sequence, one slice of the keys.  Query items (row, head in
+// group) are tiled 16 per MFMA column block; wavefront w takes blocks w, w+4, ...  Scores
+// S^T[key, item] = K * Q^T leave the MFMA with four consecutive keys per lane and one item per
+// lane column, which is already the B-operand layout of O^T[d, item] += V^T[d, key] * P[key, item]
+// when the V^T fragment is loaded with the same key order; the softmax statistics of an item
+// live in the four lanes l, l+16, l+32, l+48 and are merged with two shuffles.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
+                                                        float *__restrict__ part, int hq, int hkv, int n_splits,
+                                                        int chunk, float scale_log2e) {
+    constexpr int KD = HD / 32, DB = HD / 16, REC = HD + ATTF_STRIDE_PAD;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g4 = lane >> 4, l15 = lane & 15;
+    const int split = blockIdx.x, kvh = blockIdx.y;
+    const SeqDesc &s = b.s[blockIdx.z];
+    const int group = hq / hkv, n_items = s.nrows * group;
+    const int len = s.state[0];
+    const int kmax = min(len + s.nrows, s.capacity);  // keys 0..kmax-1 exist
+    const int k_begin = split * chunk, k_end = min(k_begin + chunk, kmax);
+    if (k_begin >= k_end) return;
+    const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);
+    const int nqb = (n_items + 15) >> 4;
+    for (int qb = wave; qb < nqb; qb += 4) {
+        const int item = qb * 16 + l15;
+        const bool valid = item < n_items;
+        const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
+        const int row = s.row0 + r;
+        const int last_key = valid ? len + r : -1;
+        bf16x8 qf[KD];
+#pragma unroll
+        for (int kd = 0; kd < KD; ++kd)
+            qf[kd] = *reinterpret_cast<const bf16x8 *>(q + ((size_t)row * hq + head) * HD + kd * 32 + g4 * 8);
+        floatx4 o[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
+        float m_run = -1e30f, l_run = 0.f;
+        for (int t0 = k_begin; t0 < k_end; t0 += 32) {
+            const int page = kv_page(s, t0), tin0 = t0 % VF_TILE;
+            const bf16_t *kbase = kv + kv_k_index(layer, s.n_pages, page, hkv, kvh, tin0, 0, HD);
+            const bf16_t *vbase = kv + kv_v_index(layer, s.n_pages, page, hkv, kvh, tin0, 0, HD);
+            floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kd = 0; kd < KD; ++kd) {
+                const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(kbase + (size_t)l15 * HD + kd * 32 + g4 * 8);
+                const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(kbase + (size_t)(16 + l15) * HD + kd * 32 + g4 * 8);
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[kd], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[kd], s1, 0, 0, 0);
+            }
+            // lane holds keys t0 + 4*g4 + j (s0) and t0 + 16 + 4*g4 + j (s1) of item l15
+            float tmax = -1e30f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                s0[j] = (t0 + g4 * 4 + j <= last_key) ? s0[j] * scale_log2e : -1e30f;
+                s1[j] = (t0 + 16 + g4 * 4 + j <= last_key) ? s1[j] * scale_log2e : -1e30f;
+                tmax = fmaxf(tmax, fmaxf(s0[j], s1[j]));
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float m_new = fmaxf(m_run, tmax);
+            const float corr = exp2f(m_run - m_new);
+            float p[8], psum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                p[j] = (t0 + g4 * 4 + j <= last_key) ? exp2f(s0[j] - m_new) : 0.f;
+                p[4 + j] = (t0 + 16 + g4 * 4 + j <= last_key) ? exp2f(s1[j] - m_new) : 0.f;
+                psum += p[j] + p[4 + j];
+            }
+            psum += __shfl_xor(psum, 16, 64);
+            psum += __shfl_xor(psum, 32, 64);
+            l_run = l_run * corr + psum;
+            m_run = m_new;
+            const bf16x8 pf = {(bf16_t)p[0], (bf16_t)p[1], (bf16_t)p[2], (bf16_t)p[3],
+                               (bf16_t)p[4], (bf16_t)p[5], (bf16_t)p[6], (bf16_t)p[7]};
+            const bool tail = t0 + 32 > kmax;  // rows past the last key may hold anything: zero them
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const bf16_t *vr = vbase + (size_t)(db * 16 + l15) * VF_TILE + g4 * 4;
+                u32x2 lo = *reinterpret_cast<const u32x2 *>(vr);
+                u32x2 hi = *reinterpret_cast<const u32x2 *>(vr + 16);
+                u32x4 raw = {lo[0], lo[1], hi[0], hi[1]};
+                bf16x8 vf = __builtin_bit_cast(bf16x8, raw);
+                if (tail) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (t0 + g4 * 4 + j >= kmax) vf[j] = (bf16_t)0.f;
+                        if (t0 + 16 + g4 * 4 + j >= kmax) vf[4 + j] = (bf16_t)0.f;
+                    }
+                }
+                o[db] = o[db] * corr;
+                o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o[db], 0, 0, 0);
+            }
+        }
+        if (valid) {
+            float *out = part + (((size_t)row * hq + head) * n_splits + split) * REC;
+            if (g4 == 0) { out[0] = m_run; out[1] = l_run; }
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+                *reinterpret_cast<floatx4 *>(out + ATTF_STRIDE_PAD + db * 16 + g4 * 4) = o[db];
+        }
+    }
+}
+
+template <int HD>
+__global__ __launch_bounds__(HD) void attn_fast_combine_kernel(Batch b, const float *__restrict__ part,
+                                                               bf16_t *__restrict__ o, int hq, int n_splits, int chunk) {
+    constexpr int REC = HD + ATTF_STRIDE_PAD;
+    const int row = blockIdx.x / hq, head = blockIdx.x % hq, d = threadIdx.x;
+    const SeqDesc &s = b.s[find_seq(b, row)];
+    const int kmax = min(s.state[0] + s.nrows, s.capacity);
+    const int used = min(n_splits, (kmax + chunk - 1) / chunk);  // slices that had keys
+    const float *p = part + ((size_t)row * hq + head) * n_splits * REC;
+    float M = -1e30f;
+    for (int i = 0; i < used; ++i) M = fmaxf(M, p[i * REC]);
+    float L = 0.f, acc = 0.f;
+    for (int i = 0; i < used; ++i) {
+        const float w = exp2f(p[i * REC] - M);
+        L += p[i * REC + 1] * w;
+        acc += p[i * REC + ATTF_STRIDE_PAD + d] * w;
+    }
+    o[(size_t)row * hq * HD + head * HD + d] = (bf16_t)(acc / L);
+}
+
+// ---- host side -------------------------------------------------------------------------------------
+
+constexpr size_t LDS_X_BUDGET = 96 * 1024;
+
+template <int NB, int UB, int PD, int EPI>
+int launch_gemm(FastGemm g, const Batch &b, int units, hipStream_t st) {
+    const int m = g.m;
+    // K split across workgroups so that roughly 2 workgroups per CU are in flight
+    int ks = 1;
+    while (units * ks < 384 && g.KB / (ks * 2) >= FAST_WAVES) ks *= 2;
+    if (EPI == EPI_LOGITS) ks = 1;
+    int kbps = (g.KB + ks - 1) / ks;
+    ks = (g.KB + kbps - 1) / kbps;
+    int kch = kbps;
+    while ((size_t)kch * m * 64 > LDS_X_BUDGET) kch = (kch + 1) / 2;
+    g.ks = ks;
+    g.kbps = kbps;
+    g.kch = kch;
+    size_t lds = (size_t)kch * m * 64;
+    const size_t red = (size_t)FAST_WAVES * UB * NB * 1024;
+    if (red > lds) lds = red;
+    auto kern = gemm_fast_kernel<NB, UB, PD, EPI>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)(LDS_X_BUDGET > red ? LDS_X_BUDGET : red)));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(units, ks), dim3(FAST_THREADS), lds, st, g, b);
+    VF_LAUNCH_CHECK("gemm_fast");
+    return VF_OK;
+}
+
+template <int NB>
+int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, hipStream_t st) {
+    const vf_config &c = m->cfg;
+    const int rows = b.total_rows;
+    const int d = c.d_model, F = c.d_ffn, hd = c.head_dim, nq = c.n_q_heads * hd, nkv = c.n_kv_heads * hd;
+    bf16_t *xg = (bf16_t *)m->x, *o = (bf16_t *)m->o, *a = (bf16_t *)m->a, *q = (bf16_t *)m->q;
+    int rc;
+    hipLaunchKernelGGL(embed_fast_kernel, dim3(rows), dim3(256), 0, st, (const bf16_t *)m->embed, tokens, b, m->h, xg,
+                       m->layers[0].attn_norm, m->ss, d, c.vocab);
+    VF_LAUNCH_CHECK("embed_fast");
+
+    FastGemm base;
+    memset(&base, 0, sizeof base);
+    base.m = rows;
+    base.part = m->part;
+    base.counters = m->counters;
+    base.ss_in = m->ss;
+    base.n_ss = d / 16;
+    base.inv_d = 1.0f / (float)d;
+    base.eps = c.rms_eps;
+    base.h = m->h;
+    base.xg_out = xg;
+    base.ss_out = m->ss;
+    base.a_out = a;
+    base.F = F;
+    base.cosv = m->rope_cos;
+    base.sinv = m->rope_sin;
+    base.q = q;
+    base.hq = c.n_q_heads;
+    base.hkv = c.n_kv_heads;
+    base.hd = hd;
+
+    // attention split
+    int max_keys = 0;
+    for (int i = 0; i < b.n_seqs; ++i) max_keys = max(max_keys, b.s[i].len_ub + b.s[i].nrows);
+    const int chunk = 128;
+    int n_splits = (max_keys + chunk - 1) / chunk;
+    const int room = ((c.max_rows + 15) / 16 * 16) * 16 / rows;
+    int achunk = chunk;
+    while (n_splits > room || n_splits > VF_ATTN_SPLIT_MAX) {
+        achunk *= 2;
+        n_splits = (max_keys + achunk - 1) / achunk;
+    }
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)hd);
+
+    for (int l = 0; l < c.n_layers; ++l) {
+        const LayerPacked &lp = m->layers[l];
+        {
+            ProfScope ps(m, VF_SITE_QKV, st);
+            FastGemm g = base;
+            g.W = (const u32x4 *)lp.wqkv; g.N = nq + 2 * nkv; g.KB = d / 32; g.X = xg;
+            g.bias = c.qkv_bias ? lp.bqkv : nullptr; g.layer = l;
+            if ((rc = launch_gemm<NB, 1, 8, EPI_QKV>(g, b, g.N / 16, st))) return rc;
+        }
+        {
+            ProfScope ps(m, VF_SITE_ATTN, st);
+            if (hd == 128) {
+                hipLaunchKernelGGL(attn_fast_kernel<128>, dim3(n_splits, c.n_kv_heads, b.n_seqs), dim3(256), 0, st, b, l,
+                                   q, m->attn_part, c.n_q_heads, c.n_kv_heads, n_splits, achunk, scale_log2e);
+                hipLaunchKernelGGL(attn_fast_combine_kernel<128>, dim3(rows * c.n_q_heads), dim3(128), 0, st, b,
+                                   m->attn_part, o, c.n_q_heads, n_splits, achunk);
+            } else {
+                hipLaunchKernelGGL(attn_fast_kernel<64>, dim3(n_splits, c.n_kv_heads, b.n_seqs), dim3(256), 0, st, b, l,
+                                   q, m->attn_part, c.n_q_heads, c.n_kv_heads, n_splits, achunk, scale_log2e);
+                hipLaunchKernelGGL(attn_fast_combine_kernel<64>, dim3(rows * c.n_q_heads), dim3(64), 0, st, b,
+                                   m->attn_part, o, c.n_q_heads, n_splits, achunk);
+            }
+            VF_LAUNCH_CHECK("attn_fast");
+        }
+        {
+            ProfScope ps(m, VF_SITE_O, st);
+            FastGemm g = base;
+            g.W = (const u32x4 *)lp.wo; g.N = d; g.KB = nq / 32; g.X = o; g.gain_next = lp.ffn_norm;
+            if ((rc = launch_gemm<NB, 1, 8, EPI_RESID>(g, b, d / 16, st))) return rc;
+        }
+        {
+            ProfScope ps(m, VF_SITE_GATEUP, st);
+            FastGemm g = base;
+            g.W = (const u32x4 *)lp.wgu; g.N = 2 * F; g.KB = d / 32; g.X = xg;
+            if ((rc = launch_gemm<NB, 2, 8, EPI_SWIGLU>(g, b, F / 16, st))) return rc;
+        }
+        {
+            ProfScope ps(m, VF_SITE_DOWN, st);
+            FastGemm g = base;
+            g.W = (const u32x4 *)lp.wd; g.N = d; g.KB = F / 32; g.X = a;
+            g.gain_next = l + 1 < c.n_layers ? m->layers[l + 1].attn_norm : m->final_norm;
+            if ((rc = launch_gemm<NB, 1, 8, EPI_RESID>(g, b, d / 16, st))) return rc;
+        }
+    }
+    {
+        ProfScope ps(m, VF_SITE_HEAD, st);
+        FastGemm g = base;
+        g.W = (const u32x4 *)m->lm_head; g.N = c.vocab; g.KB = d / 32; g.X = xg; g.logits = logits_out;
+        const int units = (c.vocab / 16 + 1) / 2;
+        if ((rc = launch_gemm<NB, 2, 8, EPI_LOGITS>(g, b, units, st))) return rc;
+    }
+    return VF_OK;
+}
+
+}  // namespace
+
+bool vf_fast_path_ok(const vf_model *m, int total_rows) {
+    return m->cfg.dtype == VF_BF16 && total_rows <= 48 && m->cfg.d_model % 64 == 0;
+}
+
+int vf_run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, hipStream_t st) {
+    const int rows = b.total_rows;
+    if (rows <= 16) return run_fast<1>(m, b, tokens, logits_out, st);
+    if (rows <= 32) return run_fast<2>(m, b, tokens, logits_out, st);
+    return run_fast<3>(m, b, tokens, logits_out, st);
+}

@@ -7,10 +7,12 @@
 
 #include "vf.h"
 
+#include <string.h>
 #include <vector>
 
 #define VF_TILE 64            // tokens per KV tile / page
 #define VF_ATTN_SPLIT_MAX 64  // most key splits one query row can have
+#define VF_STAT_CHUNKS 64     // vocabulary chunks of the row-statistics pass (one per lane)
 
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -42,6 +44,12 @@ struct AcceptDesc {
 struct AcceptBatch {
     AcceptDesc a[VF_MAX_BATCH];
 };
+// what the decide kernel leaves for the replacement / bonus draw of one sequence
+struct DrawDesc {
+    double zmax, S, u, t;       // row maximum, softmax normaliser, uniform, temperature
+    const float *q;             // draft distribution row or NULL
+    int32_t row, x_excl, active, acc;
+};
 
 // ---- model / sequence host structs ------------------------------------------------------------
 struct LayerPacked {
@@ -65,12 +73,17 @@ struct vf_model {
     void *a;                    // SwiGLU product (activation layout) [R, F]
     float *part;                // split-K partial sums
     size_t part_floats;
-    float *attn_part;           // [R*Hq, VF_ATTN_SPLIT_MAX, hd+2]
+    float *attn_part;           // [R*Hq, 16, hd+4]
     float *logits;              // [R, V]
-    float *stat_max;            // [R, n_chunks]
-    int32_t *stat_idx;          // [R, n_chunks]
-    double *stat_sum;           // [R, n_chunks]
-    int n_chunks;               // vocabulary chunks of the row-statistics pass
+    float *stat_max;            // [R, VF_STAT_CHUNKS]
+    int32_t *stat_idx;          // [R, VF_STAT_CHUNKS]
+    double *stat_sum;           // [R, VF_STAT_CHUNKS]
+    DrawDesc *draw;             // [VF_MAX_BATCH]
+    double *draw_sums;          // [VF_MAX_BATCH, VF_STAT_CHUNKS]
+    int32_t *scratch_i32;       // [64]
+    float *ss;                  // per-16-column sums of squares of h rows, [d/16][64]
+    int32_t *counters;          // split-K arrival counters, [VF_N_COUNTERS], zero between kernels
+    int fast_path;              // option: use the few-row kernels when they apply
     const float *last_logits;   // where the last verify left its logits
     int last_rows;
     // measurement hook
@@ -89,6 +102,8 @@ struct vf_seq {
     int len_ub;                 // host upper bound of the device-side length
 };
 
+#define VF_N_COUNTERS 8192
+
 // ---- error handling ----------------------------------------------------------------------------
 int vf_fail(int code, const char *fmt, ...);
 #define VF_HIP(call)                                                                       \
@@ -101,6 +116,25 @@ int vf_fail(int code, const char *fmt, ...);
         hipError_t e_ = hipGetLastError();                                                 \
         if (e_ != hipSuccess) return vf_fail(VF_ERR_HIP, "launch %s: %s", name, hipGetErrorString(e_)); \
     } while (0)
+
+// Brackets a launch group with two events when profiling is on.
+struct ProfScope {
+    vf_model *m;
+    hipStream_t st;
+    hipEvent_t b = nullptr;
+    ProfScope(vf_model *m_, int site, hipStream_t st_) : m(m_), st(st_) {
+        if (!m->prof_on) return;
+        hipEvent_t ev[2];
+        for (int i = 0; i < 2; ++i) {
+            if (!m->prof_pool->empty()) { ev[i] = m->prof_pool->back(); m->prof_pool->pop_back(); }
+            else if (hipEventCreate(&ev[i]) != hipSuccess) { if (i) m->prof_pool->push_back(ev[0]); return; }
+        }
+        (void)hipEventRecord(ev[0], st);
+        m->prof->push_back({site, ev[0], ev[1]});
+        b = ev[1];
+    }
+    ~ProfScope() { if (b) (void)hipEventRecord(b, st); }
+};
 
 // ---- layouts ------------------------------------------------------------------------------------
 // Packed bf16 matrix W[N, K]: 16x32 fragments in MFMA A-operand order.  Fragment (nb, kb) holds
@@ -182,5 +216,7 @@ int vf_launch_kv_read(const vf_model *m, const SeqDesc &s, int layer, int t0, in
 int vf_launch_accept(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
                      const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y,
                      hipStream_t st);
+bool vf_fast_path_ok(const vf_model *m, int total_rows);
+int vf_run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, hipStream_t st);
 int vf_launch_first_token(const vf_model *m, const SeqDesc &s, const float *logits_row, const float *u,
                           float temperature, hipStream_t st);

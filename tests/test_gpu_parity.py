@@ -81,6 +81,17 @@ def test_prefill_verify_accept_against_oracle(name):
     torch.cuda.synchronize()
     zg = logits.cpu().numpy()
     err = _check_logits(zg, z, tol, "verify rows")
+    if cfg.dtype == "bf16":
+        # the same rows through the general (any row count) kernels
+        vf.vf_set_option(pair.model, vf.VF_OPT_FAST_PATH, 0)
+        logits_gen = torch.empty_like(logits)
+        vf.vf_verify(pair.model, [seq], tokens, row_off, logits_gen)
+        torch.cuda.synchronize()
+        vf.vf_set_option(pair.model, vf.VF_OPT_FAST_PATH, 1)
+        _check_logits(logits_gen.cpu().numpy(), z, tol, "verify rows, general kernels")
+        vf.vf_verify(pair.model, [seq], tokens, row_off, logits)
+        torch.cuda.synchronize()
+        assert np.array_equal(logits.cpu().numpy(), zg), "verify is not bit-reproducible run to run"
     (kg, vg), (ko, vo) = pair.kv_both(seq, cache, cfg.n_layers - 1, n_ctx, k + 1)
     kv_tol = 2e-2 if cfg.dtype == "bf16" else 1e-5
     assert np.abs(kg - ko).max() <= kv_tol * np.abs(ko).max()
