@@ -84,7 +84,13 @@ size_t carve_model(vf_model *m, char *base) {
     if (nq + 2 * nkv > widest) widest = nq + 2 * nkv;
     m->part_floats = R * widest * 2;  // room for two partials of the widest layer GEMM
     m->part = (float *)cv.take(m->part_floats * 4);
-    m->attn_part = (float *)cv.take(R * c.n_q_heads * 16 * (hd + 4) * 4);
+    {
+        // general path: 16 slices per row of max_rows; few-row path: up to 48 rows, one slice per 128 keys
+        size_t recs = R * c.n_q_heads * 16;
+        const size_t few = (size_t)48 * c.n_q_heads * (((size_t)c.max_positions + 127) / 128);
+        if (few > recs) recs = few;
+        m->attn_part = (float *)cv.take(recs * (hd + 4) * 4);
+    }
     m->logits = (float *)cv.take(R * V * 4);
     m->stat_max = (float *)cv.take(R * VF_STAT_CHUNKS * 4);
     m->stat_idx = (int32_t *)cv.take(R * VF_STAT_CHUNKS * 4);

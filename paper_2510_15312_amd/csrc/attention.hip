@@ -114,7 +114,7 @@ int launch(const vf_model *m, const Batch &b, int layer, hipStream_t st) {
     int n_splits = (512 + wgs - 1) / wgs;
     n_splits = min(n_splits, (max_keys + VF_TILE - 1) / VF_TILE);
     const int room = ((c.max_rows + 15) / 16 * 16) * 16 / b.total_rows;  // partial buffer: 16 per row of max_rows
-    n_splits = max(1, min(n_splits, min(room, VF_ATTN_SPLIT_MAX)));
+    n_splits = max(1, min(n_splits, min(room, 64)));
     int chunk = (max_keys + n_splits - 1) / n_splits;
     chunk = (chunk + VF_TILE - 1) / VF_TILE * VF_TILE;
     const float scale = 1.0f / sqrtf((float)HD);

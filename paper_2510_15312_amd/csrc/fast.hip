@@ -26,8 +26,6 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int FAST_THREADS = 512;
-constexpr int FAST_WAVES = FAST_THREADS / 64;
 
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
 
@@ -147,9 +145,10 @@ __device__ inline void epi_swiglu(const FastGemm &g, int row, int nb_gate, int l
 }
 
 // NB: 16-row activation blocks (rows <= 16*NB); UB: weight blocks per unit; PD: fragments in flight
-// per weight stream and wavefront.
-template <int NB, int UB, int PD, int EPI>
-__global__ __launch_bounds__(FAST_THREADS) void gemm_fast_kernel(FastGemm g, Batch b) {
+// per weight stream and wavefront; NW: wavefronts per workgroup.
+template <int NB, int UB, int PD, int EPI, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_fast_kernel(FastGemm g, Batch b) {
+    constexpr int FAST_THREADS = NW * 64, FAST_WAVES = NW;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     u32x4 *xs = reinterpret_cast<u32x4 *>(smem_raw);
     floatx4 *red = reinterpret_cast<floatx4 *>(smem_raw);
@@ -174,11 +173,22 @@ __global__ __launch_bounds__(FAST_THREADS) void gemm_fast_kernel(FastGemm g, Bat
 #pragma unroll
     for (int c = 0; c < NB; ++c) rowc[c] = min(c * 16 + (lane & 15), m - 1);
 
-    // row scale rstd[row] from the per-block sums of squares
+    // row scale rstd[row] from the per-block sums of squares: lane = row, wavefront = every
+    // NW-th block of 16 columns
     if (EPI != EPI_RESID) {
-        float sum = 0.f;  // lane = row, wavefront = every 8th block of 16 columns
-        if (lane < m)
-            for (int j = wave; j < g.n_ss; j += FAST_WAVES) sum += g.ss_in[j * 64 + lane];
+        float sum = 0.f;
+        if (lane < m) {
+            for (int j0 = wave; j0 < g.n_ss; j0 += FAST_WAVES * 16) {
+                float t[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int j = j0 + i * FAST_WAVES;
+                    t[i] = j < g.n_ss ? g.ss_in[j * 64 + lane] : 0.f;
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum += t[i];
+            }
+        }
         rs_tmp[wave][lane] = sum;
     }
 
@@ -193,10 +203,24 @@ __global__ __launch_bounds__(FAST_THREADS) void gemm_fast_kernel(FastGemm g, Bat
                 for (int u = 0; u < UB; ++u) w[d][u] = load_stream(wp[u] + (size_t)(wk0 + d) * 64);
         __syncthreads();  // previous chunk consumed
         const int chunks = nk * 4;
-        for (int idx = tid; idx < m * chunks; idx += FAST_THREADS) {
-            const int row = idx / chunks, c = idx % chunks;
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(g.X + (size_t)row * KB * 32 + (size_t)kc0 * 32 + c * 8);
-            xs[((c >> 2) * m + row) * 4 + (c & 3)] = v;
+        for (int base = tid; base < m * chunks; base += FAST_THREADS * 4) {
+            u32x4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = base + i * FAST_THREADS;
+                if (idx < m * chunks) {
+                    const int row = idx / chunks, c = idx % chunks;
+                    v[i] = *reinterpret_cast<const u32x4 *>(g.X + (size_t)row * KB * 32 + (size_t)kc0 * 32 + c * 8);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = base + i * FAST_THREADS;
+                if (idx < m * chunks) {
+                    const int row = idx / chunks, c = idx % chunks;
+                    xs[((c >> 2) * m + row) * 4 + (c & 3)] = v[i];
+                }
+            }
         }
         __syncthreads();
 #pragma unroll 1
@@ -235,31 +259,36 @@ __global__ __launch_bounds__(FAST_THREADS) void gemm_fast_kernel(FastGemm g, Bat
     }
     __syncthreads();
 
-    constexpr int NT = UB * NB * 64;   // tiles of 4 outputs per unit
-    constexpr int NTH = EPI == EPI_SWIGLU ? NB * 64 : NT;  // threads that run the epilogue
-    floatx4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
-    int u = 0, c = 0;
-    if (tid < NTH) {
-        if (EPI == EPI_SWIGLU) {
-            c = tid >> 6;
-            for (int w = 0; w < FAST_WAVES; ++w) {
-                v0 += red[((w * UB + 0) * NB + c) * 64 + lane];
-                v1 += red[((w * UB + 1) * NB + c) * 64 + lane];
+    constexpr int NT = UB * NB * 64;                           // tiles of 4 outputs per unit
+    constexpr int NTH = EPI == EPI_SWIGLU ? NB * 64 : NT;      // tiles with an epilogue of their own
+    constexpr int TPT = (NTH + FAST_THREADS - 1) / FAST_THREADS;  // tiles per thread
+    floatx4 v0[TPT], v1[TPT];
+#pragma unroll
+    for (int it = 0; it < TPT; ++it) {
+        const int t = tid + it * FAST_THREADS;
+        v0[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+        v1[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (t < NTH) {
+            if (EPI == EPI_SWIGLU) {
+                const int c = t >> 6;
+                for (int w = 0; w < FAST_WAVES; ++w) {
+                    v0[it] += red[((w * UB + 0) * NB + c) * 64 + lane];
+                    v1[it] += red[((w * UB + 1) * NB + c) * 64 + lane];
+                }
+            } else {
+                const int u = t / (NB * 64), c = (t >> 6) % NB;
+                for (int w = 0; w < FAST_WAVES; ++w) v0[it] += red[((w * UB + u) * NB + c) * 64 + lane];
             }
-        } else {
-            u = tid / (NB * 64);
-            c = (tid >> 6) % NB;
-            for (int w = 0; w < FAST_WAVES; ++w) v0 += red[((w * UB + u) * NB + c) * 64 + lane];
         }
     }
     if (g.ks > 1) {
         float *mine = g.part + ((size_t)(unit * g.ks + split) * NT) * 4;
-        if (tid < NTH) {
-            if (EPI == EPI_SWIGLU) {
-                store_coherent(mine + (size_t)(c * 64 + lane) * 4, v0);
-                store_coherent(mine + (size_t)((NB + c) * 64 + lane) * 4, v1);
-            } else {
-                store_coherent(mine + (size_t)tid * 4, v0);
+#pragma unroll
+        for (int it = 0; it < TPT; ++it) {
+            const int t = tid + it * FAST_THREADS;
+            if (t < NTH) {
+                store_coherent(mine + (size_t)t * 4, v0[it]);
+                if (EPI == EPI_SWIGLU) store_coherent(mine + (size_t)(NTH + t) * 4, v1[it]);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -271,31 +300,49 @@ __global__ __launch_bounds__(FAST_THREADS) void gemm_fast_kernel(FastGemm g, Bat
         }
         __syncthreads();
         if (!s_last) return;
-        v0 = floatx4{0.f, 0.f, 0.f, 0.f};
-        v1 = floatx4{0.f, 0.f, 0.f, 0.f};
-        if (tid < NTH) {
-            for (int sp = 0; sp < g.ks; ++sp) {
-                const float *p = g.part + ((size_t)(unit * g.ks + sp) * NT) * 4;
-                if (EPI == EPI_SWIGLU) {
-                    v0 += load_coherent(p + (size_t)(c * 64 + lane) * 4);
-                    v1 += load_coherent(p + (size_t)((NB + c) * 64 + lane) * 4);
-                } else {
-                    v0 += load_coherent(p + (size_t)tid * 4);
+#pragma unroll
+        for (int it = 0; it < TPT; ++it) {
+            const int t = tid + it * FAST_THREADS;
+            v0[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+            v1[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (t < NTH) {
+                for (int sp0 = 0; sp0 < g.ks; sp0 += 8) {
+                    floatx4 t0[8], t1[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        t0[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+                        t1[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+                        if (sp0 + i < g.ks) {
+                            const float *p = g.part + ((size_t)(unit * g.ks + sp0 + i) * NT) * 4;
+                            t0[i] = load_coherent(p + (size_t)t * 4);
+                            if (EPI == EPI_SWIGLU) t1[i] = load_coherent(p + (size_t)(NTH + t) * 4);
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        v0[it] += t0[i];
+                        v1[it] += t1[i];
+                    }
                 }
             }
         }
     }
-    if (tid >= NTH) return;
-    const int nb = nb0 + u;
-    const int row = c * 16 + (lane & 15);
-    const bool live = row < m && nb < NBt;
-    if (EPI == EPI_RESID) {
-        epi_resid(g, row, live, nb, lane, v0);
-    } else if (live) {
-        const float rs = rs_s[row];
-        if (EPI == EPI_QKV) epi_qkv(g, b, row, nb, lane, v0, rs);
-        else if (EPI == EPI_SWIGLU) epi_swiglu(g, row, nb, lane, v0, v1, rs);
-        else *reinterpret_cast<floatx4 *>(g.logits + (size_t)row * g.N + nb * 16 + (lane >> 4) * 4) = v0 * rs;
+#pragma unroll
+    for (int it = 0; it < TPT; ++it) {
+        const int t = tid + it * FAST_THREADS;
+        if (t >= NTH) break;  // whole wavefronts leave together: NTH is a multiple of 64
+        const int u = EPI == EPI_SWIGLU ? 0 : t / (NB * 64), c = (t >> 6) % NB;
+        const int nb = nb0 + u;
+        const int row = c * 16 + (lane & 15);
+        const bool live = row < m && nb < NBt;
+        if (EPI == EPI_RESID) {
+            epi_resid(g, row, live, nb, lane, v0[it]);
+        } else if (live) {
+            const float rs = rs_s[row];
+            if (EPI == EPI_QKV) epi_qkv(g, b, row, nb, lane, v0[it], rs);
+            else if (EPI == EPI_SWIGLU) epi_swiglu(g, row, nb, lane, v0[it], v1[it], rs);
+            else *reinterpret_cast<floatx4 *>(g.logits + (size_t)row * g.N + nb * 16 + (lane >> 4) * 4) = v0[it] * rs;
+        }
     }
 }
 
@@ -328,26 +375,77 @@ __global__ __launch_bounds__(256) void embed_fast_kernel(const bf16_t *__restric
 // ---- attention ----------------------------------------------------------------------------------
 constexpr int ATTF_STRIDE_PAD = 4;  // partial record: [max, sum, -, -, O[hd]]
 
-// One workgroup: one kv head of one sequence, one slice of the keys.  Query items (row, head in
+// One workgroup: one kv head of one sequence, one slice of ATT_KEYS keys, which it first copies
+// into LDS (every load in flight at once: one memory round trip).  Query items (row, head in
 // group) are tiled 16 per MFMA column block; wavefront w takes blocks w, w+4, ...  Scores
 // S^T[key, item] = K * Q^T leave the MFMA with four consecutive keys per lane and one item per
 // lane column, which is already the B-operand layout of O^T[d, item] += V^T[d, key] * P[key, item]
-// when the V^T fragment is loaded with the same key order; the softmax statistics of an item
+// when the V^T fragment is read with the same key order; the softmax statistics of an item
 // live in the four lanes l, l+16, l+32, l+48 and are merged with two shuffles.
+constexpr int ATT_KEYS = 128;
+
 template <int HD>
 __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
                                                         float *__restrict__ part, int hq, int hkv, int n_splits,
-                                                        int chunk, float scale_log2e) {
+                                                        float scale_log2e) {
     constexpr int KD = HD / 32, DB = HD / 16, REC = HD + ATTF_STRIDE_PAD;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g4 = lane >> 4, l15 = lane & 15;
+    constexpr int KROW = HD + 8, VROW = ATT_KEYS + 8;  // padded rows: conflict-free fragment reads
+    __shared__ __align__(16) bf16_t Ks[ATT_KEYS * KROW];
+    __shared__ __align__(16) bf16_t Vs[HD * VROW];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g4 = lane >> 4, l15 = lane & 15;
     const int split = blockIdx.x, kvh = blockIdx.y;
     const SeqDesc &s = b.s[blockIdx.z];
     const int group = hq / hkv, n_items = s.nrows * group;
     const int len = s.state[0];
     const int kmax = min(len + s.nrows, s.capacity);  // keys 0..kmax-1 exist
-    const int k_begin = split * chunk, k_end = min(k_begin + chunk, kmax);
-    if (k_begin >= k_end) return;
+    const int k_begin = split * ATT_KEYS;
+    if (k_begin >= kmax) return;
     const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    // ---- stage K [key][d] and V^T [d][key] of this slice --------------------------------------
+    {
+        constexpr int KP = HD / 8;                      // 16-byte pieces per key row
+        constexpr int NK = ATT_KEYS * KP / 256;         // pieces per thread
+        u32x4 kreg[NK], vreg[NK];
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            const int pidx = i * 256 + tid, key = pidx / KP, piece = pidx % KP, t = k_begin + key;
+            kreg[i] = zero4;
+            if (t < kmax)
+                kreg[i] = *reinterpret_cast<const u32x4 *>(
+                    kv + kv_k_index(layer, s.n_pages, kv_page(s, t), hkv, kvh, t % VF_TILE, piece * 8, HD));
+        }
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            // V^T tiles: per 64-key page [d][64]; piece = 8 consecutive keys of one d
+            const int pidx = i * 256 + tid, d = pidx / (ATT_KEYS / 8), piece = pidx % (ATT_KEYS / 8);
+            const int t = k_begin + piece * 8;
+            vreg[i] = zero4;
+            if (t < kmax)
+                vreg[i] = *reinterpret_cast<const u32x4 *>(
+                    kv + kv_v_index(layer, s.n_pages, kv_page(s, t), hkv, kvh, t % VF_TILE, d, HD));
+        }
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            const int pidx = i * 256 + tid, key = pidx / KP, piece = pidx % KP;
+            *reinterpret_cast<u32x4 *>(Ks + key * KROW + piece * 8) = kreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            const int pidx = i * 256 + tid, d = pidx / (ATT_KEYS / 8), piece = pidx % (ATT_KEYS / 8);
+            const int t = k_begin + piece * 8;
+            bf16x8 v = __builtin_bit_cast(bf16x8, vreg[i]);
+            if (t + 8 > kmax) {  // cache rows past the last key may hold anything: zero them
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (t + j >= kmax) v[j] = (bf16_t)0.f;
+            }
+            *reinterpret_cast<bf16x8 *>(Vs + d * VROW + piece * 8) = v;
+        }
+    }
+    __syncthreads();
+
     const int nqb = (n_items + 15) >> 4;
     for (int qb = wave; qb < nqb; qb += 4) {
         const int item = qb * 16 + l15;
@@ -355,6 +453,7 @@ __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, cons
         const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
         const int row = s.row0 + r;
         const int last_key = valid ? len + r : -1;
+        const int qb_last = len + min(s.nrows - 1, (qb * 16 + 15) / group);  // last key any item of the block sees
         bf16x8 qf[KD];
 #pragma unroll
         for (int kd = 0; kd < KD; ++kd)
@@ -363,15 +462,15 @@ __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, cons
 #pragma unroll
         for (int db = 0; db < DB; ++db) o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
         float m_run = -1e30f, l_run = 0.f;
-        for (int t0 = k_begin; t0 < k_end; t0 += 32) {
-            const int page = kv_page(s, t0), tin0 = t0 % VF_TILE;
-            const bf16_t *kbase = kv + kv_k_index(layer, s.n_pages, page, hkv, kvh, tin0, 0, HD);
-            const bf16_t *vbase = kv + kv_v_index(layer, s.n_pages, page, hkv, kvh, tin0, 0, HD);
+#pragma unroll 1
+        for (int tl = 0; tl < ATT_KEYS; tl += 32) {
+            const int t0 = k_begin + tl;
+            if (t0 > qb_last) break;
             floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kd = 0; kd < KD; ++kd) {
-                const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(kbase + (size_t)l15 * HD + kd * 32 + g4 * 8);
-                const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(kbase + (size_t)(16 + l15) * HD + kd * 32 + g4 * 8);
+                const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(Ks + (tl + l15) * KROW + kd * 32 + g4 * 8);
+                const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(Ks + (tl + 16 + l15) * KROW + kd * 32 + g4 * 8);
                 s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[kd], s0, 0, 0, 0);
                 s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[kd], s1, 0, 0, 0);
             }
@@ -400,23 +499,14 @@ __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, cons
             m_run = m_new;
             const bf16x8 pf = {(bf16_t)p[0], (bf16_t)p[1], (bf16_t)p[2], (bf16_t)p[3],
                                (bf16_t)p[4], (bf16_t)p[5], (bf16_t)p[6], (bf16_t)p[7]};
-            const bool tail = t0 + 32 > kmax;  // rows past the last key may hold anything: zero them
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                const bf16_t *vr = vbase + (size_t)(db * 16 + l15) * VF_TILE + g4 * 4;
-                u32x2 lo = *reinterpret_cast<const u32x2 *>(vr);
-                u32x2 hi = *reinterpret_cast<const u32x2 *>(vr + 16);
-                u32x4 raw = {lo[0], lo[1], hi[0], hi[1]};
-                bf16x8 vf = __builtin_bit_cast(bf16x8, raw);
-                if (tail) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        if (t0 + g4 * 4 + j >= kmax) vf[j] = (bf16_t)0.f;
-                        if (t0 + 16 + g4 * 4 + j >= kmax) vf[4 + j] = (bf16_t)0.f;
-                    }
-                }
+                const bf16_t *vr = Vs + (db * 16 + l15) * VROW + tl + g4 * 4;
+                const u32x2 lo = *reinterpret_cast<const u32x2 *>(vr);
+                const u32x2 hi = *reinterpret_cast<const u32x2 *>(vr + 16);
+                const u32x4 raw = {lo[0], lo[1], hi[0], hi[1]};
                 o[db] = o[db] * corr;
-                o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o[db], 0, 0, 0);
+                o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, raw), pf, o[db], 0, 0, 0);
             }
         }
         if (valid) {
@@ -429,37 +519,63 @@ __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, cons
     }
 }
 
+// Merge of the key slices by log-sum-exp; one workgroup per (row, head), one thread per d.
 template <int HD>
 __global__ __launch_bounds__(HD) void attn_fast_combine_kernel(Batch b, const float *__restrict__ part,
-                                                               bf16_t *__restrict__ o, int hq, int n_splits, int chunk) {
+                                                               bf16_t *__restrict__ o, int hq, int n_splits) {
     constexpr int REC = HD + ATTF_STRIDE_PAD;
+    __shared__ float ws[VF_ATTN_SPLIT_MAX], ls[VF_ATTN_SPLIT_MAX];
     const int row = blockIdx.x / hq, head = blockIdx.x % hq, d = threadIdx.x;
     const SeqDesc &s = b.s[find_seq(b, row)];
     const int kmax = min(s.state[0] + s.nrows, s.capacity);
-    const int used = min(n_splits, (kmax + chunk - 1) / chunk);  // slices that had keys
+    const int used = min(n_splits, (kmax + ATT_KEYS - 1) / ATT_KEYS);  // slices that had keys
     const float *p = part + ((size_t)row * hq + head) * n_splits * REC;
-    float M = -1e30f;
-    for (int i = 0; i < used; ++i) M = fmaxf(M, p[i * REC]);
-    float L = 0.f, acc = 0.f;
-    for (int i = 0; i < used; ++i) {
-        const float w = exp2f(p[i * REC] - M);
-        L += p[i * REC + 1] * w;
-        acc += p[i * REC + ATTF_STRIDE_PAD + d] * w;
+    for (int i = d; i < used; i += HD) {
+        ws[i] = p[i * REC];
+        ls[i] = p[i * REC + 1];
     }
+    __syncthreads();
+    float M = -1e30f;
+    for (int i = 0; i < used; ++i) M = fmaxf(M, ws[i]);
+    __syncthreads();
+    for (int i = d; i < used; i += HD) ws[i] = exp2f(ws[i] - M);
+    __syncthreads();
+    float L = 0.f, acc = 0.f;
+    for (int i = 0; i < used; ++i) L += ls[i] * ws[i];
+    int i = 0;
+    for (; i + 8 <= used; i += 8) {
+        float t[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = p[(i + j) * REC + ATTF_STRIDE_PAD + d];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc += t[j] * ws[i + j];
+    }
+    for (; i < used; ++i) acc += p[i * REC + ATTF_STRIDE_PAD + d] * ws[i];
     o[(size_t)row * hq * HD + head * HD + d] = (bf16_t)(acc / L);
 }
 
 // ---- host side -------------------------------------------------------------------------------------
 
-constexpr size_t LDS_X_BUDGET = 96 * 1024;
+constexpr size_t LDS_X_BUDGET = 53 * 1024;
+// launch shapes: wavefronts per workgroup and the workgroup count to reach by splitting K
+#ifndef QKV_NW
+#define QKV_NW 16
+#define QKV_WGS 0
+#define O_NW 16
+#define O_WGS 0
+#define GU_NW 4
+#define GU_WGS 0
+#define DOWN_NW 4
+#define DOWN_WGS 768
+#define HEAD_NW 4
+#endif
 
-template <int NB, int UB, int PD, int EPI>
-int launch_gemm(FastGemm g, const Batch &b, int units, hipStream_t st) {
+// want_wgs: workgroups to aim for by splitting K across workgroups (0: never split).
+template <int NB, int UB, int PD, int EPI, int NW>
+int launch_gemm(FastGemm g, const Batch &b, int units, int want_wgs, hipStream_t st) {
     const int m = g.m;
-    // K split across workgroups so that roughly 2 workgroups per CU are in flight
     int ks = 1;
-    while (units * ks < 384 && g.KB / (ks * 2) >= FAST_WAVES) ks *= 2;
-    if (EPI == EPI_LOGITS) ks = 1;
+    while (units * ks < want_wgs && g.KB / (ks * 2) >= NW) ks *= 2;
     int kbps = (g.KB + ks - 1) / ks;
     ks = (g.KB + kbps - 1) / kbps;
     int kch = kbps;
@@ -468,16 +584,16 @@ int launch_gemm(FastGemm g, const Batch &b, int units, hipStream_t st) {
     g.kbps = kbps;
     g.kch = kch;
     size_t lds = (size_t)kch * m * 64;
-    const size_t red = (size_t)FAST_WAVES * UB * NB * 1024;
+    const size_t red = (size_t)NW * UB * NB * 1024;
     if (red > lds) lds = red;
-    auto kern = gemm_fast_kernel<NB, UB, PD, EPI>;
+    auto kern = gemm_fast_kernel<NB, UB, PD, EPI, NW>;
     static bool attr_done = false;
     if (!attr_done) {
         VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)(LDS_X_BUDGET > red ? LDS_X_BUDGET : red)));
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(units, ks), dim3(FAST_THREADS), lds, st, g, b);
+    hipLaunchKernelGGL(kern, dim3(units, ks), dim3(NW * 64), lds, st, g, b);
     VF_LAUNCH_CHECK("gemm_fast");
     return VF_OK;
 }
@@ -517,14 +633,8 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
     // attention split
     int max_keys = 0;
     for (int i = 0; i < b.n_seqs; ++i) max_keys = max(max_keys, b.s[i].len_ub + b.s[i].nrows);
-    const int chunk = 128;
-    int n_splits = (max_keys + chunk - 1) / chunk;
-    const int room = ((c.max_rows + 15) / 16 * 16) * 16 / rows;
-    int achunk = chunk;
-    while (n_splits > room || n_splits > VF_ATTN_SPLIT_MAX) {
-        achunk *= 2;
-        n_splits = (max_keys + achunk - 1) / achunk;
-    }
+    const int n_splits = (max_keys + ATT_KEYS - 1) / ATT_KEYS;
+    if (n_splits > VF_ATTN_SPLIT_MAX) return vf_fail(VF_ERR_UNSUPPORTED, "context of %d keys", max_keys);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)hd);
 
     for (int l = 0; l < c.n_layers; ++l) {
@@ -534,20 +644,20 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
             FastGemm g = base;
             g.W = (const u32x4 *)lp.wqkv; g.N = nq + 2 * nkv; g.KB = d / 32; g.X = xg;
             g.bias = c.qkv_bias ? lp.bqkv : nullptr; g.layer = l;
-            if ((rc = launch_gemm<NB, 1, 8, EPI_QKV>(g, b, g.N / 16, st))) return rc;
+            if ((rc = launch_gemm<NB, 1, 8, EPI_QKV, QKV_NW>(g, b, g.N / 16, QKV_WGS, st))) return rc;
         }
         {
             ProfScope ps(m, VF_SITE_ATTN, st);
             if (hd == 128) {
                 hipLaunchKernelGGL(attn_fast_kernel<128>, dim3(n_splits, c.n_kv_heads, b.n_seqs), dim3(256), 0, st, b, l,
-                                   q, m->attn_part, c.n_q_heads, c.n_kv_heads, n_splits, achunk, scale_log2e);
+                                   q, m->attn_part, c.n_q_heads, c.n_kv_heads, n_splits, scale_log2e);
                 hipLaunchKernelGGL(attn_fast_combine_kernel<128>, dim3(rows * c.n_q_heads), dim3(128), 0, st, b,
-                                   m->attn_part, o, c.n_q_heads, n_splits, achunk);
+                                   m->attn_part, o, c.n_q_heads, n_splits);
             } else {
                 hipLaunchKernelGGL(attn_fast_kernel<64>, dim3(n_splits, c.n_kv_heads, b.n_seqs), dim3(256), 0, st, b, l,
-                                   q, m->attn_part, c.n_q_heads, c.n_kv_heads, n_splits, achunk, scale_log2e);
+                                   q, m->attn_part, c.n_q_heads, c.n_kv_heads, n_splits, scale_log2e);
                 hipLaunchKernelGGL(attn_fast_combine_kernel<64>, dim3(rows * c.n_q_heads), dim3(64), 0, st, b,
-                                   m->attn_part, o, c.n_q_heads, n_splits, achunk);
+                                   m->attn_part, o, c.n_q_heads, n_splits);
             }
             VF_LAUNCH_CHECK("attn_fast");
         }
@@ -555,20 +665,20 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
             ProfScope ps(m, VF_SITE_O, st);
             FastGemm g = base;
             g.W = (const u32x4 *)lp.wo; g.N = d; g.KB = nq / 32; g.X = o; g.gain_next = lp.ffn_norm;
-            if ((rc = launch_gemm<NB, 1, 8, EPI_RESID>(g, b, d / 16, st))) return rc;
+            if ((rc = launch_gemm<NB, 1, 8, EPI_RESID, O_NW>(g, b, d / 16, O_WGS, st))) return rc;
         }
         {
             ProfScope ps(m, VF_SITE_GATEUP, st);
             FastGemm g = base;
             g.W = (const u32x4 *)lp.wgu; g.N = 2 * F; g.KB = d / 32; g.X = xg;
-            if ((rc = launch_gemm<NB, 2, 8, EPI_SWIGLU>(g, b, F / 16, st))) return rc;
+            if ((rc = launch_gemm<NB, 2, 6, EPI_SWIGLU, GU_NW>(g, b, F / 16, GU_WGS, st))) return rc;
         }
         {
             ProfScope ps(m, VF_SITE_DOWN, st);
             FastGemm g = base;
             g.W = (const u32x4 *)lp.wd; g.N = d; g.KB = F / 32; g.X = a;
             g.gain_next = l + 1 < c.n_layers ? m->layers[l + 1].attn_norm : m->final_norm;
-            if ((rc = launch_gemm<NB, 1, 8, EPI_RESID>(g, b, d / 16, st))) return rc;
+            if ((rc = launch_gemm<NB, 1, 8, EPI_RESID, DOWN_NW>(g, b, d / 16, DOWN_WGS, st))) return rc;
         }
     }
     {
@@ -576,7 +686,7 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
         FastGemm g = base;
         g.W = (const u32x4 *)m->lm_head; g.N = c.vocab; g.KB = d / 32; g.X = xg; g.logits = logits_out;
         const int units = (c.vocab / 16 + 1) / 2;
-        if ((rc = launch_gemm<NB, 2, 8, EPI_LOGITS>(g, b, units, st))) return rc;
+        if ((rc = launch_gemm<NB, 2, 6, EPI_LOGITS, HEAD_NW>(g, b, units, 0, st))) return rc;
     }
     return VF_OK;
 }

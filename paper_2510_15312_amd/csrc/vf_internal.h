@@ -11,7 +11,7 @@
 #include <vector>
 
 #define VF_TILE 64            // tokens per KV tile / page
-#define VF_ATTN_SPLIT_MAX 64  // most key splits one query row can have
+#define VF_ATTN_SPLIT_MAX 128 // most key slices one query row can have
 #define VF_STAT_CHUNKS 64     // vocabulary chunks of the row-statistics pass (one per lane)
 
 typedef __bf16 bf16_t;
