@@ -8,10 +8,9 @@
 //   down    : a * Wd^T            -> residual add, next norm's input and sums of squares
 // and the output head  x * E^T -> row scale -> float32 logits.
 //
-// RMSNorm is split around the GEMM that consumes it: the producer of the residual stream h
-// writes x = bf16(h * gain) and per-16-column sums of h^2; the consumer multiplies its
-// accumulators by rsqrt(mean(h^2) + eps) of the row.  This is the same product
-// (h * gain * rstd) * W with the row factor moved outside the dot product.
+// RMSNorm is fused into the GEMM that consumes it: the producer of the residual stream h also
+// writes per-16-column sums of h^2; the consumer turns them into rstd = rsqrt(mean(h^2) + eps)
+// per row and builds its bfloat16 operand x = bf16(h * rstd * gain) while staging h in LDS.
 //
 // GEMM kernel: one workgroup per unit of UB weight blocks (16 rows each); its wavefronts split
 // the K range, stream their weight fragments from HBM straight into registers (1 KiB per
@@ -32,7 +31,9 @@ enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
 struct FastGemm {
     const u32x4 *W;   // packed fragments
     int N, KB;        // output features, K / 32
-    const bf16_t *X;  // [m, K] row-major
+    const bf16_t *X;  // [m, K] row-major bfloat16 operand (EPI_RESID)
+    const float *Xh;  // [m, K] float32 residual stream, normalised while staging (other epilogues)
+    const float *gain;  // RMSNorm gain applied with Xh
     int m;
     int ks, kbps;     // K split across workgroups, k-blocks per split
     int kch;          // k-blocks staged in LDS at a time
@@ -43,8 +44,6 @@ struct FastGemm {
     float inv_d, eps;
     // EPI_RESID
     float *h;
-    const float *gain_next;
-    bf16_t *xg_out;
     float *ss_out;
     // EPI_SWIGLU
     bf16_t *a_out;
@@ -88,9 +87,6 @@ __device__ inline void epi_resid(const FastGemm &g, int row, bool live, int nb, 
         float *hp = g.h + (size_t)row * g.N + n0;
         hv = *reinterpret_cast<floatx4 *>(hp) + v;
         *reinterpret_cast<floatx4 *>(hp) = hv;
-        const floatx4 gn = *reinterpret_cast<const floatx4 *>(g.gain_next + n0);
-        *reinterpret_cast<u32x2 *>(g.xg_out + (size_t)row * g.N + n0) =
-            pack4_bf16(hv[0] * gn[0], hv[1] * gn[1], hv[2] * gn[2], hv[3] * gn[3]);
     }
     float ssq = hv[0] * hv[0] + hv[1] * hv[1] + hv[2] * hv[2] + hv[3] * hv[3];
     ssq += __shfl_xor(ssq, 16, 64);
@@ -98,10 +94,9 @@ __device__ inline void epi_resid(const FastGemm &g, int row, bool live, int nb, 
     if (live && (lane >> 4) == 0) g.ss_out[nb * 64 + row] = ssq;
 }
 
-__device__ inline void epi_qkv(const FastGemm &g, const Batch &b, int row, int nb, int lane, floatx4 v, float rs) {
+__device__ inline void epi_qkv(const FastGemm &g, const Batch &b, int row, int nb, int lane, floatx4 v) {
     const int n0 = nb * 16 + (lane >> 4) * 4;
     const int hd = g.hd, half = hd >> 1;
-    for (int i = 0; i < 4; ++i) v[i] *= rs;
     if (g.bias)
         for (int i = 0; i < 4; ++i) v[i] += g.bias[n0 + i];
     const SeqDesc &s = b.s[find_seq(b, row)];
@@ -134,12 +129,12 @@ __device__ inline void epi_qkv(const FastGemm &g, const Batch &b, int row, int n
     }
 }
 
-__device__ inline void epi_swiglu(const FastGemm &g, int row, int nb_gate, int lane, floatx4 vg, floatx4 vu, float rs) {
+__device__ inline void epi_swiglu(const FastGemm &g, int row, int nb_gate, int lane, floatx4 vg, floatx4 vu) {
     const int f0 = (nb_gate >> 1) * 16 + (lane >> 4) * 4;
     float o[4];
     for (int i = 0; i < 4; ++i) {
-        const float gt = vg[i] * rs, up = vu[i] * rs;
-        o[i] = gt / (1.0f + __expf(-gt)) * up;
+        const float gt = vg[i], up = vu[i];
+        o[i] = gt / (1.0f + expf(-gt)) * up;
     }
     *reinterpret_cast<u32x2 *>(g.a_out + (size_t)row * g.F + f0) = pack4_bf16(o[0], o[1], o[2], o[3]);
 }
@@ -173,23 +168,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_fast_kernel(FastGemm g, Batch b)
 #pragma unroll
     for (int c = 0; c < NB; ++c) rowc[c] = min(c * 16 + (lane & 15), m - 1);
 
-    // row scale rstd[row] from the per-block sums of squares: lane = row, wavefront = every
-    // NW-th block of 16 columns
-    if (EPI != EPI_RESID) {
-        float sum = 0.f;
-        if (lane < m) {
-            for (int j0 = wave; j0 < g.n_ss; j0 += FAST_WAVES * 16) {
-                float t[16];
+    // Loads go out in the order: row statistics (needed first), weights, activations.
+    constexpr bool NORMED = EPI != EPI_RESID;
+    float rs_t[16];
+    if (NORMED) {
+        // lane = row, wavefront = every NW-th block of 16 columns (first 16 * NW blocks)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int j = j0 + i * FAST_WAVES;
-                    t[i] = j < g.n_ss ? g.ss_in[j * 64 + lane] : 0.f;
-                }
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sum += t[i];
-            }
+        for (int i = 0; i < 16; ++i) {
+            const int j = wave + i * FAST_WAVES;
+            rs_t[i] = (lane < m && j < g.n_ss) ? g.ss_in[j * 64 + lane] : 0.f;
         }
-        rs_tmp[wave][lane] = sum;
     }
 
     for (int kc0 = kb0; kc0 < kb1; kc0 += g.kch) {
@@ -201,24 +189,66 @@ __global__ __launch_bounds__(NW * 64) void gemm_fast_kernel(FastGemm g, Batch b)
             if (d < nw)
 #pragma unroll
                 for (int u = 0; u < UB; ++u) w[d][u] = load_stream(wp[u] + (size_t)(wk0 + d) * 64);
-        __syncthreads();  // previous chunk consumed
-        const int chunks = nk * 4;
-        for (int base = tid; base < m * chunks; base += FAST_THREADS * 4) {
-            u32x4 v[4];
+        if (NORMED && kc0 == kb0) {
+            float sum = 0.f;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int idx = base + i * FAST_THREADS;
-                if (idx < m * chunks) {
-                    const int row = idx / chunks, c = idx % chunks;
-                    v[i] = *reinterpret_cast<const u32x4 *>(g.X + (size_t)row * KB * 32 + (size_t)kc0 * 32 + c * 8);
+            for (int i = 0; i < 16; ++i) sum += rs_t[i];
+            if (lane < m)
+                for (int j = wave + 16 * FAST_WAVES; j < g.n_ss; j += FAST_WAVES) sum += g.ss_in[j * 64 + lane];
+            rs_tmp[wave][lane] = sum;
+            __syncthreads();
+            if (tid < 64) {
+                float tot = 0.f;
+                for (int j = 0; j < FAST_WAVES; ++j) tot += rs_tmp[j][tid];
+                rs_s[tid] = 1.0f / sqrtf(tot * g.inv_d + g.eps);
+            }
+        }
+        __syncthreads();  // previous chunk consumed; row scales visible
+        if (NORMED) {
+            // x = bf16(h * rstd * gain): pieces of four columns
+            const int chunks = nk * 8, pieces = m * chunks;
+            for (int base = tid; base < pieces; base += FAST_THREADS * 4) {
+                floatx4 v[4], gn[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int idx = base + i * FAST_THREADS;
+                    if (idx < pieces) {
+                        const int row = idx / chunks, c = idx % chunks;
+                        v[i] = *reinterpret_cast<const floatx4 *>(g.Xh + (size_t)row * KB * 32 + (size_t)kc0 * 32 + c * 4);
+                        gn[i] = *reinterpret_cast<const floatx4 *>(g.gain + (size_t)kc0 * 32 + c * 4);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int idx = base + i * FAST_THREADS;
+                    if (idx < pieces) {
+                        const int row = idx / chunks, c = idx % chunks;
+                        const float r = rs_s[row];
+                        u32x2 *dst = reinterpret_cast<u32x2 *>(xs) + (((c >> 3) * m + row) * 8 + (c & 7));
+                        *dst = pack4_bf16(v[i][0] * r * gn[i][0], v[i][1] * r * gn[i][1], v[i][2] * r * gn[i][2],
+                                          v[i][3] * r * gn[i][3]);
+                    }
                 }
             }
+        } else {
+            const int chunks = nk * 4, pieces = m * chunks;
+            for (int base = tid; base < pieces; base += FAST_THREADS * 4) {
+                u32x4 v[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int idx = base + i * FAST_THREADS;
-                if (idx < m * chunks) {
-                    const int row = idx / chunks, c = idx % chunks;
-                    xs[((c >> 2) * m + row) * 4 + (c & 3)] = v[i];
+                for (int i = 0; i < 4; ++i) {
+                    const int idx = base + i * FAST_THREADS;
+                    if (idx < pieces) {
+                        const int row = idx / chunks, c = idx % chunks;
+                        v[i] = *reinterpret_cast<const u32x4 *>(g.X + (size_t)row * KB * 32 + (size_t)kc0 * 32 + c * 8);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int idx = base + i * FAST_THREADS;
+                    if (idx < pieces) {
+                        const int row = idx / chunks, c = idx % chunks;
+                        xs[((c >> 2) * m + row) * 4 + (c & 3)] = v[i];
+                    }
                 }
             }
         }
@@ -252,11 +282,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_fast_kernel(FastGemm g, Batch b)
     for (int u = 0; u < UB; ++u)
 #pragma unroll
         for (int c = 0; c < NB; ++c) red[((wave * UB + u) * NB + c) * 64 + lane] = acc[u][c];
-    if (EPI != EPI_RESID && tid < 64) {
-        float sum = 0.f;
-        for (int j = 0; j < FAST_WAVES; ++j) sum += rs_tmp[j][tid];
-        rs_s[tid] = 1.0f / sqrtf(sum * g.inv_d + g.eps);
-    }
     __syncthreads();
 
     constexpr int NT = UB * NB * 64;                           // tiles of 4 outputs per unit
@@ -338,18 +363,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_fast_kernel(FastGemm g, Batch b)
         if (EPI == EPI_RESID) {
             epi_resid(g, row, live, nb, lane, v0[it]);
         } else if (live) {
-            const float rs = rs_s[row];
-            if (EPI == EPI_QKV) epi_qkv(g, b, row, nb, lane, v0[it], rs);
-            else if (EPI == EPI_SWIGLU) epi_swiglu(g, row, nb, lane, v0[it], v1[it], rs);
-            else *reinterpret_cast<floatx4 *>(g.logits + (size_t)row * g.N + nb * 16 + (lane >> 4) * 4) = v0[it] * rs;
+            if (EPI == EPI_QKV) epi_qkv(g, b, row, nb, lane, v0[it]);
+            else if (EPI == EPI_SWIGLU) epi_swiglu(g, row, nb, lane, v0[it], v1[it]);
+            else *reinterpret_cast<floatx4 *>(g.logits + (size_t)row * g.N + nb * 16 + (lane >> 4) * 4) = v0[it];
         }
     }
 }
 
 // ---- embedding ----------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void embed_fast_kernel(const bf16_t *__restrict__ E, const int32_t *__restrict__ tokens,
-                                                         Batch b, float *__restrict__ h, bf16_t *__restrict__ xg,
-                                                         const float *__restrict__ gain, float *__restrict__ ss,
+                                                         Batch b, float *__restrict__ h, float *__restrict__ ss,
                                                          int d, int vocab) {
     const int row = blockIdx.x;
     int tok = tokens[row];
@@ -361,7 +384,6 @@ __global__ __launch_bounds__(256) void embed_fast_kernel(const bf16_t *__restric
         if (k < d) {
             v = (float)E[wfrag_index(tok, k, d)];
             h[(size_t)row * d + k] = v;
-            xg[(size_t)row * d + k] = (bf16_t)(v * gain[k]);
         }
         float sq = v * v;
         sq += __shfl_xor(sq, 8, 64);
@@ -497,16 +519,24 @@ __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, cons
             psum += __shfl_xor(psum, 32, 64);
             l_run = l_run * corr + psum;
             m_run = m_new;
-            const bf16x8 pf = {(bf16_t)p[0], (bf16_t)p[1], (bf16_t)p[2], (bf16_t)p[3],
-                               (bf16_t)p[4], (bf16_t)p[5], (bf16_t)p[6], (bf16_t)p[7]};
+            // probabilities as a sum of two bfloat16 values (16 significant bits): the P * V product
+            // then carries no more rounding than its bfloat16 V operand
+            bf16x8 pf, pl;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                pf[j] = (bf16_t)p[j];
+                pl[j] = (bf16_t)(p[j] - (float)pf[j]);
+            }
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
                 const bf16_t *vr = Vs + (db * 16 + l15) * VROW + tl + g4 * 4;
                 const u32x2 lo = *reinterpret_cast<const u32x2 *>(vr);
                 const u32x2 hi = *reinterpret_cast<const u32x2 *>(vr + 16);
                 const u32x4 raw = {lo[0], lo[1], hi[0], hi[1]};
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, raw);
                 o[db] = o[db] * corr;
-                o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, raw), pf, o[db], 0, 0, 0);
+                o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o[db], 0, 0, 0);
+                o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o[db], 0, 0, 0);
             }
         }
         if (valid) {
@@ -603,10 +633,10 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
     const vf_config &c = m->cfg;
     const int rows = b.total_rows;
     const int d = c.d_model, F = c.d_ffn, hd = c.head_dim, nq = c.n_q_heads * hd, nkv = c.n_kv_heads * hd;
-    bf16_t *xg = (bf16_t *)m->x, *o = (bf16_t *)m->o, *a = (bf16_t *)m->a, *q = (bf16_t *)m->q;
+    bf16_t *o = (bf16_t *)m->o, *a = (bf16_t *)m->a, *q = (bf16_t *)m->q;
     int rc;
-    hipLaunchKernelGGL(embed_fast_kernel, dim3(rows), dim3(256), 0, st, (const bf16_t *)m->embed, tokens, b, m->h, xg,
-                       m->layers[0].attn_norm, m->ss, d, c.vocab);
+    hipLaunchKernelGGL(embed_fast_kernel, dim3(rows), dim3(256), 0, st, (const bf16_t *)m->embed, tokens, b, m->h,
+                       m->ss, d, c.vocab);
     VF_LAUNCH_CHECK("embed_fast");
 
     FastGemm base;
@@ -619,7 +649,6 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
     base.inv_d = 1.0f / (float)d;
     base.eps = c.rms_eps;
     base.h = m->h;
-    base.xg_out = xg;
     base.ss_out = m->ss;
     base.a_out = a;
     base.F = F;
@@ -642,7 +671,7 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
         {
             ProfScope ps(m, VF_SITE_QKV, st);
             FastGemm g = base;
-            g.W = (const u32x4 *)lp.wqkv; g.N = nq + 2 * nkv; g.KB = d / 32; g.X = xg;
+            g.W = (const u32x4 *)lp.wqkv; g.N = nq + 2 * nkv; g.KB = d / 32; g.Xh = m->h; g.gain = lp.attn_norm;
             g.bias = c.qkv_bias ? lp.bqkv : nullptr; g.layer = l;
             if ((rc = launch_gemm<NB, 1, 8, EPI_QKV, QKV_NW>(g, b, g.N / 16, QKV_WGS, st))) return rc;
         }
@@ -664,27 +693,26 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
         {
             ProfScope ps(m, VF_SITE_O, st);
             FastGemm g = base;
-            g.W = (const u32x4 *)lp.wo; g.N = d; g.KB = nq / 32; g.X = o; g.gain_next = lp.ffn_norm;
+            g.W = (const u32x4 *)lp.wo; g.N = d; g.KB = nq / 32; g.X = o;
             if ((rc = launch_gemm<NB, 1, 8, EPI_RESID, O_NW>(g, b, d / 16, O_WGS, st))) return rc;
         }
         {
             ProfScope ps(m, VF_SITE_GATEUP, st);
             FastGemm g = base;
-            g.W = (const u32x4 *)lp.wgu; g.N = 2 * F; g.KB = d / 32; g.X = xg;
+            g.W = (const u32x4 *)lp.wgu; g.N = 2 * F; g.KB = d / 32; g.Xh = m->h; g.gain = lp.ffn_norm;
             if ((rc = launch_gemm<NB, 2, 6, EPI_SWIGLU, GU_NW>(g, b, F / 16, GU_WGS, st))) return rc;
         }
         {
             ProfScope ps(m, VF_SITE_DOWN, st);
             FastGemm g = base;
             g.W = (const u32x4 *)lp.wd; g.N = d; g.KB = F / 32; g.X = a;
-            g.gain_next = l + 1 < c.n_layers ? m->layers[l + 1].attn_norm : m->final_norm;
             if ((rc = launch_gemm<NB, 1, 8, EPI_RESID, DOWN_NW>(g, b, d / 16, DOWN_WGS, st))) return rc;
         }
     }
     {
         ProfScope ps(m, VF_SITE_HEAD, st);
         FastGemm g = base;
-        g.W = (const u32x4 *)m->lm_head; g.N = c.vocab; g.KB = d / 32; g.X = xg; g.logits = logits_out;
+        g.W = (const u32x4 *)m->lm_head; g.N = c.vocab; g.KB = d / 32; g.Xh = m->h; g.gain = m->final_norm; g.logits = logits_out;
         const int units = (c.vocab / 16 + 1) / 2;
         if ((rc = launch_gemm<NB, 2, 6, EPI_LOGITS, HEAD_NW>(g, b, units, 0, st))) return rc;
     }

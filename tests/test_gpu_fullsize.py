@@ -1,0 +1,179 @@
+"""GPU parity at the full sizes of the workload configs (the launch configuration bench.py times).
+
+The 0.5B and 1.5B shapes are checked element by element against the oracle run at full size;
+the 3B shape, whose
+oracle would take minutes, is checked through properties that hold at any size: a multi-row
+verify equals successive single-row decodes, and greedy acceptance of the target's own
+continuation accepts every draft.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle.loop import truncate
+import workloads as wl
+import paper_2510_15312_amd as vf
+from util_oracle import rel_inf, spec_of, weights_of
+from util_gpu import DEV, Pair, i32, f32, gpu_accept, accept_margin_ok
+
+pytestmark = pytest.mark.gpu
+C = wl.CONFIGS
+
+
+def test_config2_full_size_greedy_verify():
+    cfg = C["0.5b_k8"]
+    k = cfg.k
+    pair = Pair(cfg, max_rows=cfg.chunk, max_positions=cfg.ctx + 64)
+    s = pair.s
+    ctx = wl.make_context(cfg.vocab, cfg.ctx, s.context)
+    cache, seq = oracle.KVCache(pair.spec, cfg.ctx + 32), pair.new_seq(cfg.ctx + 32)
+    z_or, z_gpu = pair.prefill_both(seq, cache, ctx, cfg.chunk)
+    err = rel_inf(z_gpu[None], z_or[None]).max()
+    print(f"0.5b full size: prefill last-row error {err:.3e}", flush=True)
+    assert err < 2e-2
+    pending = oracle.first_token(z_or)
+    for attempt, drafts in enumerate([wl.copy_span_drafts(ctx, k, cfg.p_copy, cfg.vocab, s.drafts),
+                                      None]):
+        if drafts is None:      # supplementary drafts: the target's own continuation, one mismatch
+            c2 = cache.clone()
+            cont = oracle.loop.plain_greedy(pair.spec, pair.ow, c2, pending, k)
+            drafts = wl.inject_mismatch(cont, 6, cfg.vocab, s.drafts)
+        z = oracle.verify(pair.spec, pair.ow, cache, pending, drafts)
+        truncate(cache, cfg.ctx)
+        tokens = i32(np.concatenate([[pending], drafts]))
+        logits = torch.empty((k + 1, cfg.vocab), dtype=torch.float32, device=DEV)
+        vf.vf_verify(pair.model, [seq], tokens, [0, k + 1], logits)
+        torch.cuda.synchronize()
+        zg = logits.cpu().numpy()
+        err = rel_inf(zg, z).max()
+        print(f"0.5b full size: verify error {err:.3e}", flush=True)
+        assert err < 2e-2
+        a_or, out_or, y_or = oracle.greedy_accept(z, drafts)
+        n_acc, out, y = gpu_accept(pair, [seq], tokens, [0, k + 1], [(vf.VF_GREEDY, 0.0, None, None)])
+        a2, out2, y2 = oracle.greedy_accept(zg, drafts)
+        assert np.array_equal(y, y2) and n_acc[0] == a2 and np.array_equal(out[:a2 + 1], out2)
+        if accept_margin_ok(z.astype(np.float32), drafts, "greedy", None, None, 1.0, 2 * err):
+            assert n_acc[0] == a_or and np.array_equal(out[:a_or + 1], out_or)
+            print(f"0.5b full size: direct match, accepted {a_or} of {k}", flush=True)
+        vf.vf_seq_set_len(seq, cfg.ctx)
+
+
+def test_config3_full_size_stochastic_steps():
+    """1.5B shape, context 2048 in 256-token chunks, successive k=16 stochastic steps with a dense
+    draft distribution; every step is teacher-forced from the oracle's trajectory."""
+    cfg = C["1.5b_k16"]
+    k, m, n_steps = cfg.k, cfg.k + 1, 3
+    dt = np.float64
+    s = wl.streams(cfg)
+    wd = wl.make_weights(cfg, s.weights)
+    spec, ow = spec_of(cfg), weights_of(wd, dt)
+    cap = cfg.ctx + (n_steps + 1) * m
+    model = vf.vf_model_create(vf.config_from(cfg, cfg.chunk, cap), vf.upload_weights(wd, cfg.dtype, DEV), DEV)
+    seq = vf.vf_seq_create(model, cap)
+    ctx = wl.make_context(cfg.vocab, cfg.ctx, s.context)
+    cache = oracle.KVCache(spec, cap, dt)
+    print("1.5b full size: oracle prefill ...", flush=True)
+    z_last = oracle.prefill(spec, ow, cache, ctx, cfg.chunk, dt)
+    toks = i32(ctx)
+    out = torch.empty(cfg.vocab, dtype=torch.float32, device=DEV)
+    for c0 in range(0, cfg.ctx, cfg.chunk):
+        last = c0 + cfg.chunk >= cfg.ctx
+        vf.vf_prefill_chunk(model, seq, toks[c0:c0 + cfg.chunk], logits_mode=1 if last else 0,
+                            logits_out=out if last else None)
+    torch.cuda.synchronize()
+    err = rel_inf(out.cpu().numpy()[None], z_last[None]).max()
+    print(f"1.5b full size: prefill last-row error {err:.3e}", flush=True)
+    assert err < 2e-2
+    u0 = wl.make_uniforms(1, s.uniforms)
+    pending = oracle.first_token(z_last, cfg.temperature, u0[1])
+    worst, decisions, screened = 0.0, 0, 0
+    pair = type("P", (), {"model": model})
+    for step in range(n_steps):
+        scratch = cache.clone()
+
+        def next_logits(tok, scratch=scratch):
+            return oracle.forward(spec, ow, scratch, [tok], dt)[0]
+        drafts, q = wl.gumbel_drafts(next_logits, pending, k, cfg.temperature, 0.5, s.gumbel, s.drafts)
+        u = wl.make_uniforms(m, s.uniforms)
+        ln = cache.len
+        z = oracle.verify(spec, ow, cache, pending, drafts, dt)
+        a_or, out_or, y_or = oracle.stochastic_accept(z, drafts, q, u, cfg.temperature)
+        truncate(cache, ln + 1 + a_or)
+        tokens = i32(np.concatenate([[pending], drafts]))
+        logits = torch.empty((m, cfg.vocab), dtype=torch.float32, device=DEV)
+        vf.vf_seq_set_len(seq, ln)                       # teacher forcing: the oracle's state
+        vf.vf_verify(model, [seq], tokens, [0, m], logits)
+        torch.cuda.synchronize()
+        zg = logits.cpu().numpy()
+        err = rel_inf(zg, z).max()
+        worst = max(worst, err)
+        params = [(vf.VF_STOCHASTIC, cfg.temperature, f32(q), f32(u))]
+        n_acc, out_t, y = gpu_accept(pair, [seq], tokens, [0, m], params)
+        a2, out2, y2 = oracle.stochastic_accept(zg, drafts, q, u, cfg.temperature)
+        assert np.array_equal(y, y2)
+        if accept_margin_ok(zg, drafts, "stochastic", q, u, cfg.temperature, 1e-9):
+            assert n_acc[0] == a2 and np.array_equal(out_t[:a2 + 1], out2)
+        decisions += 1
+        if n_acc[0] != a_or:
+            screened += 1                                # inside the logit-error margin
+        print(f"1.5b full size: step {step} verify error {err:.3e}, oracle accepted {a_or}, gpu {n_acc[0]}", flush=True)
+        pending = int(out_or[-1])
+    print(f"1.5b full size: worst logit error {worst:.3e}; steps {decisions}, differing accept counts {screened}", flush=True)
+    assert worst < 2e-2
+
+
+def test_config4_full_size_properties():
+    """3B shape, context 4096, k = 32 (33 rows): properties that need no oracle."""
+    cfg = C["3b_k32"]
+    k, m = cfg.k, cfg.k + 1
+    s = wl.streams(cfg)
+    wd = wl.make_weights(cfg, s.weights)
+    cap = cfg.ctx + 2 * m
+    model = vf.vf_model_create(vf.config_from(cfg, cfg.chunk, cap), vf.upload_weights(wd, cfg.dtype, DEV), DEV)
+    del wd
+    seq = vf.vf_seq_create(model, cap)
+    ctx = wl.make_context(cfg.vocab, cfg.ctx, s.context)
+    toks = i32(ctx)
+    print("3b full size: prefill ...", flush=True)
+    for c0 in range(0, cfg.ctx, cfg.chunk):
+        vf.vf_prefill_chunk(model, seq, toks[c0:c0 + cfg.chunk], sample_first=c0 + cfg.chunk >= cfg.ctx)
+    ln, pending = vf.vf_seq_get_state(seq)
+    assert ln == cfg.ctx
+    # greedy continuation by single-row steps (verify with no drafts + accept = plain decoding)
+    n_acc = torch.zeros(1, dtype=torch.int32, device=DEV)
+    out_t = torch.zeros(m, dtype=torch.int32, device=DEV)
+    y_t = torch.zeros(m, dtype=torch.int32, device=DEV)
+    single = torch.empty((m, cfg.vocab), dtype=torch.float32, device=DEV)
+    cont, tok = [], pending
+    for i in range(m):
+        t = i32([tok])
+        vf.vf_verify(model, [seq], t, [0, 1], single[i:i + 1])
+        vf.vf_accept(model, [seq], t, [0, 1], [(vf.VF_GREEDY, 0.0, None, None)], n_acc, out_t, y_t)
+        tok = int(out_t[0].item())
+        cont.append(tok)
+    assert vf.vf_seq_get_state(seq)[0] == cfg.ctx + m
+    # the same rows in one verify: logits of row i must match the i-th single-row decode
+    vf.vf_seq_set_len(seq, cfg.ctx)
+    drafts = cont[:k]
+    tokens = i32([pending] + drafts)
+    multi = torch.empty((m, cfg.vocab), dtype=torch.float32, device=DEV)
+    vf.vf_verify(model, [seq], tokens, [0, m], multi)
+    torch.cuda.synchronize()
+    err = rel_inf(multi.cpu().numpy(), single.cpu().numpy()).max()
+    print(f"3b full size: 33-row verify vs 33 single-row decodes: {err:.3e}", flush=True)
+    # both sides are GPU results, each allowed 2e-2 against the exact model: 4e-2 between them
+    assert err < 4e-2
+    # greedy speculative step on the target's own continuation: all accepted (up to logit ties)
+    vf.vf_accept(model, [seq], tokens, [0, m], [(vf.VF_GREEDY, 0.0, None, None)], n_acc, out_t, y_t)
+    torch.cuda.synchronize()
+    a = int(n_acc.item())
+    y = y_t.cpu().numpy()
+    zs = single.cpu().numpy()
+    first_diff = next((i for i in range(k) if y[i] != drafts[i]), k)
+    assert a == first_diff
+    if a < k:   # a flip is only allowed where the top-2 gap is within the logit error
+        top2 = np.partition(zs[a], -2)[-2:]
+        assert top2[1] - top2[0] <= 2 * err * np.abs(zs[a]).max(), (a, top2)
+    print(f"3b full size: accepted {a} of {k} drafts from the target's own continuation", flush=True)
+    assert vf.vf_seq_get_state(seq)[0] == cfg.ctx + 1 + a
