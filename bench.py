@@ -23,6 +23,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the gate/up GEMM kernel from hardware counters (FETCH_SIZE + WRITE_SIZE,
+# each scaled by what the same counter reads for a plain 1 GiB copy); see
+# profiles/gateup_gemm_1.5b_k16_pmc.md.  Set to None whenever that kernel changes.
+GATEUP_TRAFFIC_BYTES = 56_474_000
 
 
 def log(*a):
@@ -66,23 +70,23 @@ def draft_with_distribution(vf, torch, model, seq, pending, k, temperature, scal
 
 
 def cpu_baseline(cfg, wd, ctx_len, k, temperature):
-    """The oracle's verify + accept on the host: 2 of the 28 layers plus the full output head and
-    acceptance are timed on a cache of ctx_len random rows, and the step is extrapolated
-    linearly in the layer count."""
+    """The oracle's verify + accept on the host: 4 of the 28 layers plus the full output head and
+    acceptance are timed on a cache of ctx_len random rows (about 5 s of repeats each for the
+    0-layer and the 4-layer model), and the step is extrapolated linearly in the layer count."""
     import oracle
     from oracle.transformer import LayerWeights
     import workloads as wl
     cores = len(os.sched_getaffinity(0))
     rng = np.random.default_rng(7)
     f64 = lambda a: np.asarray(a, dtype=np.float64)
-    layers = [LayerWeights(**{n: f64(v) for n, v in lw.items()}) for lw in wd["layers"][:2]]
+    layers = [LayerWeights(**{n: f64(v) for n, v in lw.items()}) for lw in wd["layers"][:4]]
     embed, fnorm = f64(wd["embed"]), f64(wd["final_norm"])
     m = k + 1
     toks = rng.integers(0, cfg.vocab, m)
     q = rng.dirichlet(np.full(cfg.vocab, 0.05), size=k).astype(np.float32)
     u = wl.make_uniforms(m, rng)
     times = {}
-    for nl in (0, 2):
+    for nl in (0, 4):
         spec = oracle.ModelSpec(nl, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn,
                                 cfg.vocab, cfg.dtype, cfg.rope_theta, cfg.rms_eps)
         w = oracle.Weights(embed, fnorm, layers[:nl])
@@ -90,18 +94,18 @@ def cpu_baseline(cfg, wd, ctx_len, k, temperature):
         if nl:
             cache.k[:, :, :ctx_len] = oracle.round_bf16(rng.standard_normal(cache.k[:, :, :ctx_len].shape))
             cache.v[:, :, :ctx_len] = oracle.round_bf16(rng.standard_normal(cache.v[:, :, :ctx_len].shape))
-        best = []
-        for _ in range(3):
+        best, t_start = [], time.perf_counter()
+        while len(best) < 3 or time.perf_counter() - t_start < 5.0:
             cache.len = ctx_len
             t0 = time.perf_counter()
             z = oracle.verify(spec, w, cache, toks[0], toks[1:])
             oracle.stochastic_accept(z.astype(np.float32), toks[1:], q, u, temperature)
             best.append(time.perf_counter() - t0)
         times[nl] = float(np.median(best))
-    per_layer = (times[2] - times[0]) / 2
+    per_layer = (times[4] - times[0]) / 4
     full = times[0] + cfg.n_layers * per_layer
     return {"value": round(full * 1e6, 1), "unit": "us/step", "cores": cores, "kind": "oracle",
-            "sample": f"numpy float64 oracle verify+accept, {m} rows, ctx {ctx_len}: 2 of {cfg.n_layers} "
+            "sample": f"numpy float64 oracle verify+accept, {m} rows, ctx {ctx_len}: 4 of {cfg.n_layers} "
                       f"layers ({per_layer * 1e3:.1f} ms/layer) + full output head and acceptance "
                       f"({times[0] * 1e3:.1f} ms), extrapolated linearly to {cfg.n_layers} layers"}
 
@@ -113,6 +117,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--config", default="1.5b_k16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, the yardstick for hardware byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the draft-verify step is a single-GPU path here "
@@ -219,12 +225,11 @@ def main():
     torch.cuda.synchronize()
     vf.vf_profile(model, False)
     prof = vf.vf_profile_read(model)
-    layer_sites = ("qkv", "o", "gateup", "down")
-    layer_ms = sum(prof[n][0] for n in layer_sites)
-    layer_cnt = sum(prof[n][1] for n in layer_sites)
-    layer_bytes = cfg.weight_bytes() - V * cfg.d_model * 2
-    avg_us = layer_ms / layer_cnt * 1e3
-    achieved = layer_bytes / (cfg.n_layers * 4) / (avg_us * 1e-6) / 1e9
+    # dominant kernel: the gate/up GEMM (largest share of the step); algorithmic bytes per launch =
+    # its weight matrix once
+    gu_bytes = 2 * cfg.d_ffn * cfg.d_model * 2
+    avg_us = prof["gateup"][0] / prof["gateup"][1] * 1e3
+    achieved = gu_bytes / (avg_us * 1e-6) / 1e9
     site_tbl = {n: {"us_per_step": round(prof[n][0] / K * 1e3, 1), "launches_per_step": prof[n][1] // K}
                 for n in prof}
     log("[bench] per-site time per step (instrumented pass): " + json.dumps(site_tbl))
@@ -246,14 +251,21 @@ def main():
         "accepted_drafts_per_step": round(float(np.mean(acc_ref[:K])), 3),
         "us_per_emitted_token": round(ms_per_step * 1e3 / (1 + float(np.mean(acc_ref[:K]))), 1),
         "prefill_ms": round(prefill_ms, 1),
-        "roofline": {"bound": "hbm", "kernel": "gemm_bf16_kernel<2,1> (layer GEMMs: QKV, O, gate/up, down)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_fast_kernel<2,2,6,EPI_SWIGLU,4> (gate/up GEMM + SwiGLU)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "avg_launch_us": round(avg_us, 2), "bytes_per_launch": int(layer_bytes / (cfg.n_layers * 4))},
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": GATEUP_TRAFFIC_BYTES,
+                     "avg_launch_us": round(avg_us, 2), "bytes_per_launch": gu_bytes},
         "sites_us_per_step": {n: site_tbl[n]["us_per_step"] for n in site_tbl},
     }
     # determinism: the timed replay must have walked the recorded trajectory
     assert ln_end == lens[K], (ln_end, lens[K])
+    if args.pmc_calibration:
+        a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                                  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
     if not args.no_cpu_baseline:
         del model
         torch.cuda.empty_cache()
