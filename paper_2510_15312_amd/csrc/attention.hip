@@ -134,6 +134,7 @@ int launch(const vf_model *m, const Batch &b, int layer, hipStream_t st) {
 int vf_launch_attention(const vf_model *m, const Batch &b, int layer, hipStream_t st) {
     const vf_config &c = m->cfg;
     if (c.dtype == VF_BF16) {
+        if (m->fast_path) return vf_launch_attention_rows(m, b, layer, st);  // MFMA kernel
         if (c.head_dim == 64) return launch<bf16_t, 64>(m, b, layer, st);
         if (c.head_dim == 128) return launch<bf16_t, 128>(m, b, layer, st);
     } else {

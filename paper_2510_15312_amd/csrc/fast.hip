@@ -406,14 +406,137 @@ constexpr int ATTF_STRIDE_PAD = 4;  // partial record: [max, sum, -, -, O[hd]]
 // live in the four lanes l, l+16, l+32, l+48 and are merged with two shuffles.
 constexpr int ATT_KEYS = 128;
 
+template <int HD> struct AttLds {
+    static constexpr int KROW = HD + 8, VROW = ATT_KEYS + 8;  // padded rows: conflict-free fragment reads
+    bf16_t Ks[ATT_KEYS * KROW];
+    bf16_t Vs[HD * VROW];
+};
+
+// Copies keys [k_begin, k_begin + 128) of one kv head into LDS: K as [key][d], V^T as [d][key];
+// keys at or past kmax read as zero.  256 threads; every load is issued before the first store.
+template <int HD>
+__device__ inline void att_stage(const SeqDesc &s, int layer, int hkv, int kvh, int k_begin, int kmax,
+                                 AttLds<HD> &L, int tid) {
+    constexpr int KROW = AttLds<HD>::KROW, VROW = AttLds<HD>::VROW;
+    constexpr int KP = HD / 8;               // 16-byte pieces per key row
+    constexpr int NK = ATT_KEYS * KP / 256;  // pieces per thread
+    const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    u32x4 kreg[NK], vreg[NK];
+#pragma unroll
+    for (int i = 0; i < NK; ++i) {
+        const int pidx = i * 256 + tid, key = pidx / KP, piece = pidx % KP, t = k_begin + key;
+        kreg[i] = zero4;
+        if (t < kmax)
+            kreg[i] = *reinterpret_cast<const u32x4 *>(
+                kv + kv_k_index(layer, s.n_pages, kv_page(s, t), hkv, kvh, t % VF_TILE, piece * 8, HD));
+    }
+#pragma unroll
+    for (int i = 0; i < NK; ++i) {
+        // V^T tiles: per 64-key page [d][64]; piece = 8 consecutive keys of one d
+        const int pidx = i * 256 + tid, d = pidx / (ATT_KEYS / 8), piece = pidx % (ATT_KEYS / 8);
+        const int t = k_begin + piece * 8;
+        vreg[i] = zero4;
+        if (t < kmax)
+            vreg[i] = *reinterpret_cast<const u32x4 *>(
+                kv + kv_v_index(layer, s.n_pages, kv_page(s, t), hkv, kvh, t % VF_TILE, d, HD));
+    }
+#pragma unroll
+    for (int i = 0; i < NK; ++i) {
+        const int pidx = i * 256 + tid, key = pidx / KP, piece = pidx % KP;
+        *reinterpret_cast<u32x4 *>(L.Ks + key * KROW + piece * 8) = kreg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < NK; ++i) {
+        const int pidx = i * 256 + tid, d = pidx / (ATT_KEYS / 8), piece = pidx % (ATT_KEYS / 8);
+        const int t = k_begin + piece * 8;
+        bf16x8 v = __builtin_bit_cast(bf16x8, vreg[i]);
+        if (t + 8 > kmax) {  // cache rows past the last key may hold anything: zero them
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (t + j >= kmax) v[j] = (bf16_t)0.f;
+        }
+        *reinterpret_cast<bf16x8 *>(L.Vs + d * VROW + piece * 8) = v;
+    }
+}
+
+// Online-softmax state of one block of 16 query items in one wavefront.
+template <int HD> struct AttState {
+    floatx4 o[HD / 16];
+    float m_run, l_run;
+};
+
+// One staged slice for one block of 16 items: S^T = K Q^T, masked online softmax, O^T += V^T P.
+// last_key: last visible key of this lane's item; blk_last: of any item in the block.
+template <int HD>
+__device__ inline void att_slice(AttState<HD> &st, const bf16x8 (&qf)[HD / 32], const AttLds<HD> &L, int k_begin,
+                                 int last_key, int blk_last, float scale_log2e, int lane) {
+    constexpr int KD = HD / 32, DB = HD / 16, KROW = AttLds<HD>::KROW, VROW = AttLds<HD>::VROW;
+    const int g4 = lane >> 4, l15 = lane & 15;
+#pragma unroll 1
+    for (int tl = 0; tl < ATT_KEYS; tl += 32) {
+        const int t0 = k_begin + tl;
+        if (t0 > blk_last) break;
+        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kd = 0; kd < KD; ++kd) {
+            const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(L.Ks + (tl + l15) * KROW + kd * 32 + g4 * 8);
+            const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(L.Ks + (tl + 16 + l15) * KROW + kd * 32 + g4 * 8);
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[kd], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[kd], s1, 0, 0, 0);
+        }
+        // lane holds keys t0 + 4*g4 + j (s0) and t0 + 16 + 4*g4 + j (s1) of item l15
+        float tmax = -1e30f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            s0[j] = (t0 + g4 * 4 + j <= last_key) ? s0[j] * scale_log2e : -1e30f;
+            s1[j] = (t0 + 16 + g4 * 4 + j <= last_key) ? s1[j] * scale_log2e : -1e30f;
+            tmax = fmaxf(tmax, fmaxf(s0[j], s1[j]));
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float m_new = fmaxf(st.m_run, tmax);
+        const float corr = exp2f(st.m_run - m_new);
+        float p[8], psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            p[j] = (t0 + g4 * 4 + j <= last_key) ? exp2f(s0[j] - m_new) : 0.f;
+            p[4 + j] = (t0 + 16 + g4 * 4 + j <= last_key) ? exp2f(s1[j] - m_new) : 0.f;
+            psum += p[j] + p[4 + j];
+        }
+        psum += __shfl_xor(psum, 16, 64);
+        psum += __shfl_xor(psum, 32, 64);
+        st.l_run = st.l_run * corr + psum;
+        st.m_run = m_new;
+        // probabilities as a sum of two bfloat16 values (16 significant bits): the P * V product
+        // then carries no more rounding than its bfloat16 V operand
+        bf16x8 pf, pl;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            pf[j] = (bf16_t)p[j];
+            pl[j] = (bf16_t)(p[j] - (float)pf[j]);
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const bf16_t *vr = L.Vs + (db * 16 + l15) * VROW + tl + g4 * 4;
+            const u32x2 lo = *reinterpret_cast<const u32x2 *>(vr);
+            const u32x2 hi = *reinterpret_cast<const u32x2 *>(vr + 16);
+            const u32x4 raw = {lo[0], lo[1], hi[0], hi[1]};
+            const bf16x8 vf = __builtin_bit_cast(bf16x8, raw);
+            st.o[db] = st.o[db] * corr;
+            st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, st.o[db], 0, 0, 0);
+            st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, st.o[db], 0, 0, 0);
+        }
+    }
+}
+
+// Few rows: one workgroup per (key slice, kv head, sequence); partial results per slice.
 template <int HD>
 __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
                                                         float *__restrict__ part, int hq, int hkv, int n_splits,
                                                         float scale_log2e) {
     constexpr int KD = HD / 32, DB = HD / 16, REC = HD + ATTF_STRIDE_PAD;
-    constexpr int KROW = HD + 8, VROW = ATT_KEYS + 8;  // padded rows: conflict-free fragment reads
-    __shared__ __align__(16) bf16_t Ks[ATT_KEYS * KROW];
-    __shared__ __align__(16) bf16_t Vs[HD * VROW];
+    __shared__ __align__(16) AttLds<HD> L;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g4 = lane >> 4, l15 = lane & 15;
     const int split = blockIdx.x, kvh = blockIdx.y;
     const SeqDesc &s = b.s[blockIdx.z];
@@ -422,52 +545,8 @@ __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, cons
     const int kmax = min(len + s.nrows, s.capacity);  // keys 0..kmax-1 exist
     const int k_begin = split * ATT_KEYS;
     if (k_begin >= kmax) return;
-    const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-
-    // ---- stage K [key][d] and V^T [d][key] of this slice --------------------------------------
-    {
-        constexpr int KP = HD / 8;                      // 16-byte pieces per key row
-        constexpr int NK = ATT_KEYS * KP / 256;         // pieces per thread
-        u32x4 kreg[NK], vreg[NK];
-#pragma unroll
-        for (int i = 0; i < NK; ++i) {
-            const int pidx = i * 256 + tid, key = pidx / KP, piece = pidx % KP, t = k_begin + key;
-            kreg[i] = zero4;
-            if (t < kmax)
-                kreg[i] = *reinterpret_cast<const u32x4 *>(
-                    kv + kv_k_index(layer, s.n_pages, kv_page(s, t), hkv, kvh, t % VF_TILE, piece * 8, HD));
-        }
-#pragma unroll
-        for (int i = 0; i < NK; ++i) {
-            // V^T tiles: per 64-key page [d][64]; piece = 8 consecutive keys of one d
-            const int pidx = i * 256 + tid, d = pidx / (ATT_KEYS / 8), piece = pidx % (ATT_KEYS / 8);
-            const int t = k_begin + piece * 8;
-            vreg[i] = zero4;
-            if (t < kmax)
-                vreg[i] = *reinterpret_cast<const u32x4 *>(
-                    kv + kv_v_index(layer, s.n_pages, kv_page(s, t), hkv, kvh, t % VF_TILE, d, HD));
-        }
-#pragma unroll
-        for (int i = 0; i < NK; ++i) {
-            const int pidx = i * 256 + tid, key = pidx / KP, piece = pidx % KP;
-            *reinterpret_cast<u32x4 *>(Ks + key * KROW + piece * 8) = kreg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < NK; ++i) {
-            const int pidx = i * 256 + tid, d = pidx / (ATT_KEYS / 8), piece = pidx % (ATT_KEYS / 8);
-            const int t = k_begin + piece * 8;
-            bf16x8 v = __builtin_bit_cast(bf16x8, vreg[i]);
-            if (t + 8 > kmax) {  // cache rows past the last key may hold anything: zero them
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (t + j >= kmax) v[j] = (bf16_t)0.f;
-            }
-            *reinterpret_cast<bf16x8 *>(Vs + d * VROW + piece * 8) = v;
-        }
-    }
+    att_stage<HD>(s, layer, hkv, kvh, k_begin, kmax, L, tid);
     __syncthreads();
-
     const int nqb = (n_items + 15) >> 4;
     for (int qb = wave; qb < nqb; qb += 4) {
         const int item = qb * 16 + l15;
@@ -475,76 +554,74 @@ __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, cons
         const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
         const int row = s.row0 + r;
         const int last_key = valid ? len + r : -1;
-        const int qb_last = len + min(s.nrows - 1, (qb * 16 + 15) / group);  // last key any item of the block sees
+        const int blk_last = len + min(s.nrows - 1, (qb * 16 + 15) / group);
         bf16x8 qf[KD];
 #pragma unroll
         for (int kd = 0; kd < KD; ++kd)
             qf[kd] = *reinterpret_cast<const bf16x8 *>(q + ((size_t)row * hq + head) * HD + kd * 32 + g4 * 8);
-        floatx4 o[DB];
+        AttState<HD> st;
 #pragma unroll
-        for (int db = 0; db < DB; ++db) o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
-        float m_run = -1e30f, l_run = 0.f;
-#pragma unroll 1
-        for (int tl = 0; tl < ATT_KEYS; tl += 32) {
-            const int t0 = k_begin + tl;
-            if (t0 > qb_last) break;
-            floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kd = 0; kd < KD; ++kd) {
-                const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(Ks + (tl + l15) * KROW + kd * 32 + g4 * 8);
-                const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(Ks + (tl + 16 + l15) * KROW + kd * 32 + g4 * 8);
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[kd], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[kd], s1, 0, 0, 0);
-            }
-            // lane holds keys t0 + 4*g4 + j (s0) and t0 + 16 + 4*g4 + j (s1) of item l15
-            float tmax = -1e30f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                s0[j] = (t0 + g4 * 4 + j <= last_key) ? s0[j] * scale_log2e : -1e30f;
-                s1[j] = (t0 + 16 + g4 * 4 + j <= last_key) ? s1[j] * scale_log2e : -1e30f;
-                tmax = fmaxf(tmax, fmaxf(s0[j], s1[j]));
-            }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float m_new = fmaxf(m_run, tmax);
-            const float corr = exp2f(m_run - m_new);
-            float p[8], psum = 0.f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                p[j] = (t0 + g4 * 4 + j <= last_key) ? exp2f(s0[j] - m_new) : 0.f;
-                p[4 + j] = (t0 + 16 + g4 * 4 + j <= last_key) ? exp2f(s1[j] - m_new) : 0.f;
-                psum += p[j] + p[4 + j];
-            }
-            psum += __shfl_xor(psum, 16, 64);
-            psum += __shfl_xor(psum, 32, 64);
-            l_run = l_run * corr + psum;
-            m_run = m_new;
-            // probabilities as a sum of two bfloat16 values (16 significant bits): the P * V product
-            // then carries no more rounding than its bfloat16 V operand
-            bf16x8 pf, pl;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                pf[j] = (bf16_t)p[j];
-                pl[j] = (bf16_t)(p[j] - (float)pf[j]);
-            }
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const bf16_t *vr = Vs + (db * 16 + l15) * VROW + tl + g4 * 4;
-                const u32x2 lo = *reinterpret_cast<const u32x2 *>(vr);
-                const u32x2 hi = *reinterpret_cast<const u32x2 *>(vr + 16);
-                const u32x4 raw = {lo[0], lo[1], hi[0], hi[1]};
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, raw);
-                o[db] = o[db] * corr;
-                o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o[db], 0, 0, 0);
-                o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o[db], 0, 0, 0);
-            }
-        }
+        for (int db = 0; db < DB; ++db) st.o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
+        st.m_run = -1e30f;
+        st.l_run = 0.f;
+        att_slice<HD>(st, qf, L, k_begin, last_key, blk_last, scale_log2e, lane);
         if (valid) {
             float *out = part + (((size_t)row * hq + head) * n_splits + split) * REC;
-            if (g4 == 0) { out[0] = m_run; out[1] = l_run; }
+            if (g4 == 0) { out[0] = st.m_run; out[1] = st.l_run; }
 #pragma unroll
             for (int db = 0; db < DB; ++db)
-                *reinterpret_cast<floatx4 *>(out + ATTF_STRIDE_PAD + db * 16 + g4 * 4) = o[db];
+                *reinterpret_cast<floatx4 *>(out + ATTF_STRIDE_PAD + db * 16 + g4 * 4) = st.o[db];
+        }
+    }
+}
+
+// Many rows (a prefill chunk, or a large batch): one workgroup per (64 query items, kv head,
+// sequence) walks all key slices its items can see; each wavefront owns one block of 16 items for
+// the whole walk, so no partial results leave the workgroup.  Output in the bf16 activation
+// (MFMA B-operand) layout the general GEMM reads.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_rows_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
+                                                        bf16_t *__restrict__ o, int hq, int hkv, int ncb,
+                                                        float scale_log2e) {
+    constexpr int KD = HD / 32, DB = HD / 16;
+    __shared__ __align__(16) AttLds<HD> L;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g4 = lane >> 4, l15 = lane & 15;
+    const int kvh = blockIdx.y;
+    const SeqDesc &s = b.s[blockIdx.z];
+    const int group = hq / hkv, n_items = s.nrows * group;
+    const int item0 = blockIdx.x * 64;
+    if (item0 >= n_items) return;
+    const int len = s.state[0];
+    const int kmax = min(len + s.nrows, s.capacity);
+    const int item = item0 + wave * 16 + l15;
+    const bool valid = item < n_items;
+    const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
+    const int row = s.row0 + r;
+    const int last_key = valid ? len + r : -1;
+    const int blk_last = len + min(s.nrows - 1, (item0 + wave * 16 + 15) / group);
+    const int wg_last = min(kmax - 1, len + min(s.nrows - 1, (item0 + 63) / group));
+    bf16x8 qf[KD];
+#pragma unroll
+    for (int kd = 0; kd < KD; ++kd)
+        qf[kd] = *reinterpret_cast<const bf16x8 *>(q + ((size_t)row * hq + head) * HD + kd * 32 + g4 * 8);
+    AttState<HD> st;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) st.o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
+    st.m_run = -1e30f;
+    st.l_run = 0.f;
+    for (int k_begin = 0; k_begin <= wg_last; k_begin += ATT_KEYS) {
+        __syncthreads();  // previous slice consumed
+        att_stage<HD>(s, layer, hkv, kvh, k_begin, kmax, L, tid);
+        __syncthreads();
+        att_slice<HD>(st, qf, L, k_begin, last_key, blk_last, scale_log2e, lane);
+    }
+    if (valid) {
+        const float inv = 1.0f / st.l_run;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const int k = head * HD + db * 16 + g4 * 4;
+            *reinterpret_cast<u32x2 *>(o + xfrag_index(row, k, ncb)) =
+                pack4_bf16(st.o[db][0] * inv, st.o[db][1] * inv, st.o[db][2] * inv, st.o[db][3] * inv);
         }
     }
 }
@@ -720,6 +797,24 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
 }
 
 }  // namespace
+
+int vf_launch_attention_rows(const vf_model *m, const Batch &b, int layer, hipStream_t st) {
+    const vf_config &c = m->cfg;
+    const int group = c.n_q_heads / c.n_kv_heads;
+    int max_items = 0;
+    for (int i = 0; i < b.n_seqs; ++i) max_items = max(max_items, b.s[i].nrows * group);
+    const dim3 grid((max_items + 63) / 64, c.n_kv_heads, b.n_seqs);
+    const int ncb = (b.total_rows + 15) >> 4;
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)c.head_dim);
+    if (c.head_dim == 128)
+        hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(256), 0, st, b, layer, (const bf16_t *)m->q,
+                           (bf16_t *)m->o, c.n_q_heads, c.n_kv_heads, ncb, scale_log2e);
+    else
+        hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(256), 0, st, b, layer, (const bf16_t *)m->q,
+                           (bf16_t *)m->o, c.n_q_heads, c.n_kv_heads, ncb, scale_log2e);
+    VF_LAUNCH_CHECK("attn_rows");
+    return VF_OK;
+}
 
 bool vf_fast_path_ok(const vf_model *m, int total_rows) {
     return m->cfg.dtype == VF_BF16 && total_rows <= 48 && m->cfg.d_model % 64 == 0;

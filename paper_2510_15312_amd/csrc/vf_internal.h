@@ -190,6 +190,7 @@ __device__ inline int find_seq(const Batch &b, int row) {
 struct GemmPlan {
     int ks;        // K splits (partials)
     int nbw;       // n-blocks per wavefront
+    int tnb;       // > 0: many-row kernel with this many weight blocks per workgroup
 };
 GemmPlan vf_gemm_plan(const vf_model *m, int N, int K, int rows, int force_single);
 // Y partials [ks][R][N] (R = ld_rows) for rows [row_lo, row_hi) of X.
@@ -216,6 +217,7 @@ int vf_launch_kv_read(const vf_model *m, const SeqDesc &s, int layer, int t0, in
 int vf_launch_accept(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
                      const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y,
                      hipStream_t st);
+int vf_launch_attention_rows(const vf_model *m, const Batch &b, int layer, hipStream_t st);
 bool vf_fast_path_ok(const vf_model *m, int total_rows);
 int vf_run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, hipStream_t st);
 int vf_launch_first_token(const vf_model *m, const SeqDesc &s, const float *logits_row, const float *u,
