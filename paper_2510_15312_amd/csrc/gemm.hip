@@ -110,60 +110,71 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_bf16_kernel(
     }
 }
 
-// Many rows (a prefill chunk): workgroup tile = 256 rows x TNB weight blocks, four wavefronts of
-// 64 rows each.  Per 32-wide K step the TNB weight fragments and the 16 activation fragments go
+// Many rows (a prefill chunk): workgroup tile = 16*MB rows x TNB weight blocks, four wavefronts
+// of 4*MB rows each.  Per K step of KSTEP 32-wide k-blocks the weight and activation fragments go
 // through a double-buffered LDS stage (one barrier per step, the next step's global loads in
-// flight during the MFMAs), so every weight byte is read once per 256 rows.
-template <int TNB>
+// flight during the MFMAs).
+template <int TNB, int MB, int KSTEP>
 __global__ __launch_bounds__(256) void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp,
                                                         float *__restrict__ part, int N, int KB, int ncb, int row_lo,
                                                         int row_hi, int ld_rows, int kb_per_split) {
-    constexpr int NF = TNB + 16;           // fragments per stage
-    constexpr int NL = (NF * 64 + 255) / 256;  // 16-byte loads per thread and stage
-    __shared__ u32x4 lds[2][NF * 64];
+    constexpr int NF = TNB + MB;               // fragments per 32-wide k-block
+    constexpr int NL = (KSTEP * NF * 64 + 255) / 256;  // 16-byte loads per thread and stage
+    constexpr int WC = MB / 4;                 // activation blocks per wavefront
+    __shared__ u32x4 lds[2][KSTEP * NF * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int NBt = N >> 4;
     const int nb0 = blockIdx.x * TNB;
-    const int cb0 = (row_lo >> 4) + blockIdx.z * 16;
+    const int cb0 = (row_lo >> 4) + blockIdx.z * MB;
     const int kb_begin = blockIdx.y * kb_per_split, kb_end = min(KB, kb_begin + kb_per_split);
-    floatx4 acc[TNB][4];
+    floatx4 acc[TNB][WC];
 #pragma unroll
     for (int n = 0; n < TNB; ++n)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc[n][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < WC; ++c) acc[n][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     u32x4 r[NL];
     auto fetch = [&](int kb) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int idx = tid + i * 256, f = idx >> 6, l = idx & 63;
+            const int idx = tid + i * 256, half = idx / (NF * 64), rem = idx % (NF * 64), f = rem >> 6, l = rem & 63;
+            const int k = kb + half;
             r[i] = u32x4{0u, 0u, 0u, 0u};
-            if (f < TNB) {
-                const int nb = min(nb0 + f, NBt - 1);
-                r[i] = __builtin_nontemporal_load(Wp + ((size_t)nb * KB + kb) * 64 + l);
-            } else if (f < NF) {
-                const int cb = cb0 + f - TNB;
-                if (cb < ncb) r[i] = Xp[((size_t)kb * ncb + cb) * 64 + l];
+            if (half < KSTEP && k < kb_end) {
+                if (f < TNB) {
+                    const int nb = min(nb0 + f, NBt - 1);
+                    r[i] = __builtin_nontemporal_load(Wp + ((size_t)nb * KB + k) * 64 + l);
+                } else {
+                    const int cb = cb0 + f - TNB;
+                    if (cb < ncb) r[i] = Xp[((size_t)k * ncb + cb) * 64 + l];
+                }
             }
         }
     };
     if (kb_begin < kb_end) fetch(kb_begin);
     int buf = 0;
-    for (int kb = kb_begin; kb < kb_end; ++kb, buf ^= 1) {
+    for (int kb = kb_begin; kb < kb_end; kb += KSTEP, buf ^= 1) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int idx = tid + i * 256;
-            if (idx < NF * 64) lds[buf][idx] = r[i];
+            if (idx < KSTEP * NF * 64) lds[buf][idx] = r[i];
         }
         __syncthreads();
-        if (kb + 1 < kb_end) fetch(kb + 1);
-        bf16x8 bfr[4];
+        if (kb + KSTEP < kb_end) fetch(kb + KSTEP);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) bfr[c] = __builtin_bit_cast(bf16x8, lds[buf][(TNB + wave * 4 + c) * 64 + lane]);
+        for (int half = 0; half < KSTEP; ++half) {
+            if (kb + half < kb_end) {
+                const u32x4 *st = lds[buf] + half * NF * 64;
+                bf16x8 bfr[WC];
 #pragma unroll
-        for (int n = 0; n < TNB; ++n) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, lds[buf][n * 64 + lane]);
+                for (int c = 0; c < WC; ++c) bfr[c] = __builtin_bit_cast(bf16x8, st[(TNB + wave * WC + c) * 64 + lane]);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) acc[n][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bfr[c], acc[n][c], 0, 0, 0);
+                for (int n = 0; n < TNB; ++n) {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, st[n * 64 + lane]);
+#pragma unroll
+                    for (int c = 0; c < WC; ++c)
+                        acc[n][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bfr[c], acc[n][c], 0, 0, 0);
+                }
+            }
         }
     }
     float *out = part + (size_t)blockIdx.y * ld_rows * N;
@@ -171,8 +182,8 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(const u32x4 *__restrict_
     for (int n = 0; n < TNB; ++n) {
         if (nb0 + n >= NBt) break;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int row = (cb0 + wave * 4 + c) * 16 + (lane & 15);
+        for (int c = 0; c < WC; ++c) {
+            const int row = (cb0 + wave * WC + c) * 16 + (lane & 15);
             if (row >= row_lo && row < row_hi)
                 *reinterpret_cast<floatx4 *>(out + (size_t)row * N + (nb0 + n) * 16 + (lane >> 4) * 4) = acc[n][c];
         }
@@ -233,12 +244,12 @@ GemmPlan vf_gemm_plan(const vf_model *m, int N, int K, int rows, int force_singl
     if (m->cfg.dtype == VF_F32) return p;
     const int NBt = N >> 4, KB = K >> 5;
     if (rows > 64 && m->fast_path) {
-        // many-row kernel: 8 weight blocks per workgroup for wide matrices, 2 for narrow ones
-        p.tnb = NBt >= 1024 ? 8 : 2;
-        const int groups = (NBt + p.tnb - 1) / p.tnb * ((rows + 255) / 256);
+        // many-row kernel: 256 rows x 8 weight blocks per workgroup for wide matrices, 128 x 4 for narrow ones
+        p.tnb = NBt >= 1024 ? 8 : 4;
+        const int groups = (NBt + p.tnb - 1) / p.tnb * (p.tnb == 8 ? (rows + 255) / 256 : (rows + 127) / 128);
         int ks = 1;
         if (!force_single)
-            while (groups * ks < 192 && KB / (ks * 2) >= 8 &&
+            while (groups * ks < 384 && KB / (ks * 2) >= 8 &&
                    (size_t)ks * 2 * m->cfg.max_rows * N <= m->part_floats) ks *= 2;
         p.ks = ks;
         return p;
@@ -263,13 +274,14 @@ int vf_launch_gemm(const vf_model *m, const void *W, const void *X, float *part,
         const int KB = K >> 5, NBt = N >> 4, ncb = (rows_total + 15) >> 4;
         const int kbps = (KB + plan.ks - 1) / plan.ks;
         const int cbs = ((row_hi + 15) >> 4) - (row_lo >> 4);
-        dim3 grid((NBt + plan.tnb - 1) / plan.tnb, plan.ks, (cbs + 15) / 16);
+        const int mb = plan.tnb == 8 ? 16 : 8;
+        dim3 grid((NBt + plan.tnb - 1) / plan.tnb, plan.ks, (cbs + mb - 1) / mb);
         if (plan.tnb == 8)
-            hipLaunchKernelGGL(gemm_rows_kernel<8>, grid, dim3(256), 0, st, (const u32x4 *)W, (const u32x4 *)X, part,
-                               N, KB, ncb, row_lo, row_hi, ld_rows, kbps);
+            hipLaunchKernelGGL((gemm_rows_kernel<8, 16, 1>), grid, dim3(256), 0, st, (const u32x4 *)W, (const u32x4 *)X,
+                               part, N, KB, ncb, row_lo, row_hi, ld_rows, kbps);
         else
-            hipLaunchKernelGGL(gemm_rows_kernel<2>, grid, dim3(256), 0, st, (const u32x4 *)W, (const u32x4 *)X, part,
-                               N, KB, ncb, row_lo, row_hi, ld_rows, kbps);
+            hipLaunchKernelGGL((gemm_rows_kernel<4, 8, 2>), grid, dim3(256), 0, st, (const u32x4 *)W, (const u32x4 *)X,
+                               part, N, KB, ncb, row_lo, row_hi, ld_rows, kbps);
         VF_LAUNCH_CHECK("gemm_rows");
         return VF_OK;
     }
