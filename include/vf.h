@@ -147,6 +147,13 @@ int vf_seq_get_state(vf_seq *s, int32_t *len_host, int32_t *pending_host, void *
 int vf_kv_read(vf_model *m, vf_seq *s, int layer, int t0, int n, float *k_out_dev,
                float *v_out_dev, void *stream);
 
+/* The inverse: overwrites K and V of `layer` for positions [t0, t0+n) with the given float32
+ * arrays of shape [n, n_kv_heads, head_dim] (rounded to the model dtype; K is taken as is, i.e.
+ * with the rotary embedding already applied).  Imports a cache computed elsewhere; the length
+ * is not changed (use vf_seq_set_len). */
+int vf_kv_write(vf_model *m, vf_seq *s, int layer, int t0, int n, const float *k_in_dev,
+                const float *v_in_dev, void *stream);
+
 /* ---- the three operations ------------------------------------------------------------------ */
 
 /* Chunked prefill (paper Sec. 2, Sec. 4.1): runs n_tokens ids (tokens_dev, int32) at
@@ -203,12 +210,22 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
  * the fused few-row kernels; 0 forces the general kernels (any row count), which compute the
  * same function. */
 #define VF_OPT_FAST_PATH 1
+/* VF_OPT_PERSISTENT (default 0): when the few-row kernels apply and the activations of the call fit
+ * on-chip memory, vf_verify runs the whole forward pass as one persistent kernel whose phases are
+ * separated by grid-wide barriers; 0 keeps one kernel per GEMM.  Same function, same rounding
+ * points; sums are taken in a different (fixed) order.  The persistent kernel occupies the whole
+ * GPU: two vf_verify calls on the same model must not overlap (they share its workspace anyway),
+ * and a barrier that cannot complete within seconds (the GPU shared with another process that
+ * keeps workgroups from becoming resident) gives up; vf_seq_get_state and vf_profile_read then
+ * report VF_ERR_HIP. */
+#define VF_OPT_PERSISTENT 2
 int vf_set_option(vf_model *m, int option, int value);
 
 /* ---- measurement hook (not part of the method) ---------------------------------------------- */
 
 /* Kernel sites timed by vf_profile: the five GEMMs of the forward pass, attention (both
- * kernels), the small norm / epilogue kernels together, and acceptance. */
+ * kernels), the small norm / epilogue kernels together, acceptance, and the persistent whole-pass kernel
+ * (which replaces the first six when it runs). */
 #define VF_SITE_QKV     0
 #define VF_SITE_O       1
 #define VF_SITE_GATEUP  2
@@ -217,7 +234,8 @@ int vf_set_option(vf_model *m, int option, int value);
 #define VF_SITE_ATTN    5
 #define VF_SITE_SMALL   6
 #define VF_SITE_ACCEPT  7
-#define VF_N_SITES      8
+#define VF_SITE_STEP    8
+#define VF_N_SITES      9
 
 /* enable != 0: from now on every launch group of the sites above is bracketed by a pair of
  * HIP events on the call's stream (costs about a microsecond per event; leave it off when

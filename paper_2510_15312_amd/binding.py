@@ -19,14 +19,15 @@ VF_GREEDY, VF_STOCHASTIC = 0, 1
 VF_PENDING = -1
 VF_MAX_BATCH, VF_MAX_DRAFTS = 32, 32
 VF_OPT_FAST_PATH = 1
+VF_OPT_PERSISTENT = 2
 
 EXPORTS = [
     "vf_last_error", "vf_model_packed_bytes", "vf_model_create", "vf_model_destroy",
     "vf_seq_state_bytes", "vf_kv_bytes", "vf_seq_create", "vf_seq_destroy", "vf_seq_set_len",
-    "vf_seq_set_pending", "vf_seq_get_state", "vf_kv_read", "vf_prefill_chunk", "vf_verify",
+    "vf_seq_set_pending", "vf_seq_get_state", "vf_kv_read", "vf_kv_write", "vf_prefill_chunk", "vf_verify",
     "vf_accept", "vf_profile", "vf_profile_read", "vf_set_option",
 ]
-SITES = ["qkv", "o", "gateup", "down", "head", "attn", "small", "accept"]
+SITES = ["qkv", "o", "gateup", "down", "head", "attn", "small", "accept", "step"]
 
 
 class VfError(RuntimeError):
@@ -75,6 +76,7 @@ def _load():
         "vf_seq_set_pending": (C.c_int, [vp, i32, vp]),
         "vf_seq_get_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
         "vf_kv_read": (C.c_int, [vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp]),
+        "vf_kv_write": (C.c_int, [vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp]),
         "vf_prefill_chunk": (C.c_int, [vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp, C.c_float, vp]),
         "vf_verify": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), vp, vp]),
         "vf_accept": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(vf_accept_params),
@@ -207,6 +209,11 @@ def vf_kv_read(model, seq, layer, t0, n):
     v = torch.empty(shape, dtype=torch.float32, device=seq.state.device)
     _check(lib.vf_kv_read(model.handle, seq.handle, layer, t0, n, _ptr(k), _ptr(v), _stream()))
     return k, v
+
+
+def vf_kv_write(model, seq, layer, t0, k, v):
+    """k, v: float32 device tensors [n, n_kv_heads, head_dim]."""
+    _check(lib.vf_kv_write(model.handle, seq.handle, layer, t0, k.shape[0], _ptr(k), _ptr(v), _stream()))
 
 
 def vf_prefill_chunk(model, seq, tokens, logits_mode=0, logits_out=None, sample_first=False, u=None,

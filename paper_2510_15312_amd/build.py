@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libvf.so")
-SOURCES = ["api.hip", "gemm.hip", "elementwise.hip", "attention.hip", "accept.hip", "fast.hip"]
+SOURCES = ["api.hip", "gemm.hip", "elementwise.hip", "attention.hip", "accept.hip", "fast.hip", "fused.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -20,10 +20,11 @@ def build(verbose=True):
     bdir = os.path.join(PKG, "_build")
     os.makedirs(bdir, exist_ok=True)
     procs, objs = [], []
+    extra = os.environ.get("VF_HIPCC_FLAGS", "").split()   # e.g. -DFUSED_TRACE=0 for a phase timeline
     for src in SOURCES:
         obj = os.path.join(bdir, src.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for src, p in procs:
         out, _ = p.communicate()

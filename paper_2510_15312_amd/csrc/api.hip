@@ -100,6 +100,7 @@ size_t carve_model(vf_model *m, char *base) {
     m->scratch_i32 = (int32_t *)cv.take(64 * 4);
     m->ss = (float *)cv.take((d / 16) * 64 * 4);
     m->counters = (int32_t *)cv.take(VF_N_COUNTERS * 4);
+    m->fz_ws = (char *)cv.take(vf_fused_workspace_bytes(c));
     return (cv.off + 255) & ~(size_t)255;
 }
 
@@ -205,6 +206,7 @@ int vf_model_create(const vf_config *cfg, const vf_weights *w, void *packed_dev,
     m->cfg = *cfg;
     m->es = cfg->dtype == VF_BF16 ? 2 : 4;
     m->fast_path = 1;
+    m->persistent = 0;
     m->prof = new std::vector<vf_model::ProfRec>();
     m->prof_pool = new std::vector<hipEvent_t>();
     m->layers = new (std::nothrow) LayerPacked[cfg->n_layers];
@@ -246,6 +248,7 @@ int vf_model_create(const vf_config *cfg, const vf_weights *w, void *packed_dev,
     TRY(vf_launch_rope_table(m, st));
     // activation buffers start at zero so that padding rows of a 16-row block are finite
     TRYHIP(hipMemsetAsync(m->h, 0, (size_t)((char *)m->base + m->bytes - (char *)m->h), st));
+    if (c.dtype == VF_BF16) TRY(vf_fused_init(m, m->fz_ws, st));
 #undef TRY
 #undef TRYHIP
     *out = m;
@@ -345,7 +348,7 @@ int vf_seq_get_state(vf_seq *s, int32_t *len_host, int32_t *pending_host, void *
     if (tmp[0] >= 0 && tmp[0] <= s->capacity) s->len_ub = tmp[0];
     if (len_host) *len_host = tmp[0];
     if (pending_host) *pending_host = tmp[1];
-    return VF_OK;
+    return vf_fused_check(s->m);
 }
 
 int vf_kv_read(vf_model *m, vf_seq *s, int layer, int t0, int n, float *k_out_dev, float *v_out_dev,
@@ -354,6 +357,15 @@ int vf_kv_read(vf_model *m, vf_seq *s, int layer, int t0, int n, float *k_out_de
     if (layer < 0 || layer >= m->cfg.n_layers || t0 < 0 || n < 0 || t0 + n > s->capacity)
         return vf_fail(VF_ERR_ARG, "vf_kv_read: range outside the cache");
     return vf_launch_kv_read(m, describe(s, 0, 0), layer, t0, n, k_out_dev, v_out_dev, (hipStream_t)stream);
+}
+
+int vf_kv_write(vf_model *m, vf_seq *s, int layer, int t0, int n, const float *k_in_dev, const float *v_in_dev,
+                void *stream) {
+    if (!m || !s || !k_in_dev || !v_in_dev) return vf_fail(VF_ERR_ARG, "vf_kv_write: NULL argument");
+    if (s->m != m) return vf_fail(VF_ERR_ARG, "sequence belongs to another model");
+    if (layer < 0 || layer >= m->cfg.n_layers || t0 < 0 || n < 0 || t0 + n > s->capacity)
+        return vf_fail(VF_ERR_ARG, "vf_kv_write: range outside the cache");
+    return vf_launch_kv_write(m, describe(s, 0, 0), layer, t0, n, k_in_dev, v_in_dev, (hipStream_t)stream);
 }
 
 int vf_prefill_chunk(vf_model *m, vf_seq *s, const int32_t *tokens_dev, int n_tokens, int logits_mode,
@@ -426,7 +438,9 @@ int vf_verify(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
                            b.s[i].nrows, seqs[i]->capacity);
     hipStream_t st = (hipStream_t)stream;
     float *dst = logits_out_dev ? logits_out_dev : m->logits;
-    if (m->fast_path && vf_fast_path_ok(m, b.total_rows)) {
+    if (m->fast_path && m->persistent && vf_fused_ok(m, b)) {
+        if ((rc = vf_run_fused(m, b, tokens_dev, dst, st))) return rc;
+    } else if (m->fast_path && vf_fast_path_ok(m, b.total_rows)) {
         if ((rc = vf_run_fast(m, b, tokens_dev, dst, st))) return rc;
     } else {
         int tail = 0;
@@ -478,6 +492,7 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
 int vf_set_option(vf_model *m, int option, int value) {
     if (!m) return vf_fail(VF_ERR_ARG, "vf_set_option: NULL");
     if (option == VF_OPT_FAST_PATH) { m->fast_path = value != 0; return VF_OK; }
+    if (option == VF_OPT_PERSISTENT) { m->persistent = value != 0; return VF_OK; }
     return vf_fail(VF_ERR_ARG, "vf_set_option: unknown option %d", option);
 }
 
@@ -500,7 +515,7 @@ int vf_profile_read(vf_model *m, float *ms_host, int32_t *count_host) {
         m->prof_pool->push_back(r.b);
     }
     m->prof->clear();
-    return VF_OK;
+    return vf_fused_check(m);
 }
 
 }  // extern "C"

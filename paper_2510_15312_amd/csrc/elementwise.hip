@@ -197,6 +197,19 @@ __global__ void kv_read_kernel(SeqDesc s, int layer, int t0, int n, int hkv, int
     v_out[idx] = to_f32(kv[kv_v_index(layer, s.n_pages, page, hkv, head, tin, d, hd)]);
 }
 
+template <typename T>
+__global__ void kv_write_kernel(SeqDesc s, int layer, int t0, int n, int hkv, int hd, const float *__restrict__ k_in,
+                                const float *__restrict__ v_in) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n * hkv * hd) return;
+    const int r = idx / (hkv * hd), head = (idx / hd) % hkv, d = idx % hd;
+    const int t = t0 + r;
+    T *kv = reinterpret_cast<T *>(s.kv);
+    const int page = kv_page(s, t), tin = t % VF_TILE;
+    kv[kv_k_index(layer, s.n_pages, page, hkv, head, tin, d, hd)] = from_f32<T>(k_in[idx]);
+    kv[kv_v_index(layer, s.n_pages, page, hkv, head, tin, d, hd)] = from_f32<T>(v_in[idx]);
+}
+
 inline int nblocks(size_t n, int bs) { return (int)((n + bs - 1) / bs); }
 
 __global__ void pack_vec_kernel(const float *__restrict__ src, float *__restrict__ dst, int n, int perm_hd) {
@@ -313,6 +326,21 @@ int vf_launch_state_set(int32_t *state, int idx, int32_t value, hipStream_t st) 
 int vf_launch_state_add(int32_t *state, int idx, int32_t delta, hipStream_t st) {
     hipLaunchKernelGGL(state_add_kernel, dim3(1), dim3(1), 0, st, state, idx, delta);
     VF_LAUNCH_CHECK("state_add");
+    return VF_OK;
+}
+
+int vf_launch_kv_write(const vf_model *m, const SeqDesc &s, int layer, int t0, int n, const float *k_in,
+                       const float *v_in, hipStream_t st) {
+    const vf_config &c = m->cfg;
+    const int total = n * c.n_kv_heads * c.head_dim;
+    if (total <= 0) return VF_OK;
+    if (c.dtype == VF_BF16)
+        hipLaunchKernelGGL(kv_write_kernel<bf16_t>, dim3(nblocks(total, 256)), dim3(256), 0, st, s, layer, t0, n,
+                           c.n_kv_heads, c.head_dim, k_in, v_in);
+    else
+        hipLaunchKernelGGL(kv_write_kernel<float>, dim3(nblocks(total, 256)), dim3(256), 0, st, s, layer, t0, n,
+                           c.n_kv_heads, c.head_dim, k_in, v_in);
+    VF_LAUNCH_CHECK("kv_write");
     return VF_OK;
 }
 

@@ -18,126 +18,9 @@
 // partial sums are added in LDS in a fixed order.  With a K split across workgroups (ks > 1)
 // each workgroup leaves its partial tile in memory and the last one to arrive adds them in split
 // order, so results do not depend on timing.
-#include "vf_internal.h"
+#include "fast_common.h"
 
 namespace {
-
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
-
-struct FastGemm {
-    const u32x4 *W;   // packed fragments
-    int N, KB;        // output features, K / 32
-    const bf16_t *X;  // [m, K] row-major bfloat16 operand (EPI_RESID)
-    const float *Xh;  // [m, K] float32 residual stream, normalised while staging (other epilogues)
-    const float *gain;  // RMSNorm gain applied with Xh
-    int m;
-    int ks, kbps;     // K split across workgroups, k-blocks per split
-    int kch;          // k-blocks staged in LDS at a time
-    float *part;      // ks > 1: partial tiles
-    int *counters;    // ks > 1: arrivals per unit
-    const float *ss_in;  // per-16-column sums of squares of the rows of h, [n_ss][64]
-    int n_ss;
-    float inv_d, eps;
-    // EPI_RESID
-    float *h;
-    float *ss_out;
-    // EPI_SWIGLU
-    bf16_t *a_out;
-    int F;
-    // EPI_LOGITS
-    float *logits;
-    // EPI_QKV
-    const float *bias, *cosv, *sinv;
-    bf16_t *q;
-    int layer, hq, hkv, hd;
-};
-
-__device__ inline u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
-
-__device__ inline void store_coherent(float *p, floatx4 v) {
-    __hip_atomic_store(p + 0, v[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(p + 1, v[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(p + 2, v[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(p + 3, v[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline floatx4 load_coherent(const float *p) {
-    floatx4 v;
-    v[0] = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v[1] = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v[2] = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v[3] = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return v;
-}
-
-__device__ inline u32x2 pack4_bf16(float a, float b, float c, float d) {
-    bf16x4 v = {(bf16_t)a, (bf16_t)b, (bf16_t)c, (bf16_t)d};
-    return __builtin_bit_cast(u32x2, v);
-}
-
-// ---- epilogues: thread holds Y[row][n0 .. n0+3] ------------------------------------------------
-
-__device__ inline void epi_resid(const FastGemm &g, int row, bool live, int nb, int lane, floatx4 v) {
-    const int n0 = nb * 16 + (lane >> 4) * 4;
-    floatx4 hv = {0.f, 0.f, 0.f, 0.f};
-    if (live) {
-        float *hp = g.h + (size_t)row * g.N + n0;
-        hv = *reinterpret_cast<floatx4 *>(hp) + v;
-        *reinterpret_cast<floatx4 *>(hp) = hv;
-    }
-    float ssq = hv[0] * hv[0] + hv[1] * hv[1] + hv[2] * hv[2] + hv[3] * hv[3];
-    ssq += __shfl_xor(ssq, 16, 64);
-    ssq += __shfl_xor(ssq, 32, 64);
-    if (live && (lane >> 4) == 0) g.ss_out[nb * 64 + row] = ssq;
-}
-
-__device__ inline void epi_qkv(const FastGemm &g, const Batch &b, int row, int nb, int lane, floatx4 v) {
-    const int n0 = nb * 16 + (lane >> 4) * 4;
-    const int hd = g.hd, half = hd >> 1;
-    if (g.bias)
-        for (int i = 0; i < 4; ++i) v[i] += g.bias[n0 + i];
-    const SeqDesc &s = b.s[find_seq(b, row)];
-    const int pos = s.state[0] + (row - s.row0);
-    if (pos < 0 || pos >= s.capacity) return;
-    const int head = n0 / hd, p0 = n0 % hd;
-    bf16_t *kv = reinterpret_cast<bf16_t *>(s.kv);
-    if (head < g.hq + g.hkv) {
-        const int i0 = p0 >> 1;  // packed columns 2i, 2i+1 are elements i and i + hd/2
-        const float c0 = g.cosv[(size_t)pos * half + i0], s0 = g.sinv[(size_t)pos * half + i0];
-        const float c1 = g.cosv[(size_t)pos * half + i0 + 1], s1 = g.sinv[(size_t)pos * half + i0 + 1];
-        const float a0 = v[0] * c0 - v[1] * s0, b0 = v[1] * c0 + v[0] * s0;
-        const float a1 = v[2] * c1 - v[3] * s1, b1 = v[3] * c1 + v[2] * s1;
-        bf16_t *dst;
-        if (head < g.hq) {
-            dst = g.q + ((size_t)row * g.hq + head) * hd;
-        } else {
-            const int page = kv_page(s, pos), tin = pos % VF_TILE;
-            dst = kv + kv_k_index(g.layer, s.n_pages, page, g.hkv, head - g.hq, tin, 0, hd);
-        }
-        dst[i0] = (bf16_t)a0;
-        dst[i0 + 1] = (bf16_t)a1;
-        dst[i0 + half] = (bf16_t)b0;
-        dst[i0 + half + 1] = (bf16_t)b1;
-    } else {
-        const int vh = head - g.hq - g.hkv;
-        const int page = kv_page(s, pos), tin = pos % VF_TILE;
-        for (int i = 0; i < 4; ++i)
-            kv[kv_v_index(g.layer, s.n_pages, page, g.hkv, vh, tin, p0 + i, hd)] = (bf16_t)v[i];
-    }
-}
-
-__device__ inline void epi_swiglu(const FastGemm &g, int row, int nb_gate, int lane, floatx4 vg, floatx4 vu) {
-    const int f0 = (nb_gate >> 1) * 16 + (lane >> 4) * 4;
-    float o[4];
-    for (int i = 0; i < 4; ++i) {
-        const float gt = vg[i], up = vu[i];
-        o[i] = gt / (1.0f + expf(-gt)) * up;
-    }
-    *reinterpret_cast<u32x2 *>(g.a_out + (size_t)row * g.F + f0) = pack4_bf16(o[0], o[1], o[2], o[3]);
-}
 
 // NB: 16-row activation blocks (rows <= 16*NB); UB: weight blocks per unit; PD: fragments in flight
 // per weight stream and wavefront; NW: wavefronts per workgroup.
@@ -361,10 +244,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_fast_kernel(FastGemm g, Batch b)
         const int row = c * 16 + (lane & 15);
         const bool live = row < m && nb < NBt;
         if (EPI == EPI_RESID) {
-            epi_resid(g, row, live, nb, lane, v0[it]);
+            epi_resid<false>(g, row, live, nb, lane, v0[it]);
         } else if (live) {
-            if (EPI == EPI_QKV) epi_qkv(g, b, row, nb, lane, v0[it]);
-            else if (EPI == EPI_SWIGLU) epi_swiglu(g, row, nb, lane, v0[it], v1[it]);
+            if (EPI == EPI_QKV) epi_qkv<false>(g, b, row, nb, lane, v0[it]);
+            else if (EPI == EPI_SWIGLU) epi_swiglu<false>(g, row, nb, lane, v0[it], v1[it]);
             else *reinterpret_cast<floatx4 *>(g.logits + (size_t)row * g.N + nb * 16 + (lane >> 4) * 4) = v0[it];
         }
     }
@@ -395,141 +278,6 @@ __global__ __launch_bounds__(256) void embed_fast_kernel(const bf16_t *__restric
 }
 
 // ---- attention ----------------------------------------------------------------------------------
-constexpr int ATTF_STRIDE_PAD = 4;  // partial record: [max, sum, -, -, O[hd]]
-
-// One workgroup: one kv head of one sequence, one slice of ATT_KEYS keys, which it first copies
-// into LDS (every load in flight at once: one memory round trip).  Query items (row, head in
-// group) are tiled 16 per MFMA column block; wavefront w takes blocks w, w+4, ...  Scores
-// S^T[key, item] = K * Q^T leave the MFMA with four consecutive keys per lane and one item per
-// lane column, which is already the B-operand layout of O^T[d, item] += V^T[d, key] * P[key, item]
-// when the V^T fragment is read with the same key order; the softmax statistics of an item
-// live in the four lanes l, l+16, l+32, l+48 and are merged with two shuffles.
-constexpr int ATT_KEYS = 128;
-
-template <int HD> struct AttLds {
-    static constexpr int KROW = HD + 8, VROW = ATT_KEYS + 8;  // padded rows: conflict-free fragment reads
-    bf16_t Ks[ATT_KEYS * KROW];
-    bf16_t Vs[HD * VROW];
-};
-
-// Copies keys [k_begin, k_begin + 128) of one kv head into LDS: K as [key][d], V^T as [d][key];
-// keys at or past kmax read as zero.  256 threads; every load is issued before the first store.
-template <int HD>
-__device__ inline void att_stage(const SeqDesc &s, int layer, int hkv, int kvh, int k_begin, int kmax,
-                                 AttLds<HD> &L, int tid) {
-    constexpr int KROW = AttLds<HD>::KROW, VROW = AttLds<HD>::VROW;
-    constexpr int KP = HD / 8;               // 16-byte pieces per key row
-    constexpr int NK = ATT_KEYS * KP / 256;  // pieces per thread
-    const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    u32x4 kreg[NK], vreg[NK];
-#pragma unroll
-    for (int i = 0; i < NK; ++i) {
-        const int pidx = i * 256 + tid, key = pidx / KP, piece = pidx % KP, t = k_begin + key;
-        kreg[i] = zero4;
-        if (t < kmax)
-            kreg[i] = *reinterpret_cast<const u32x4 *>(
-                kv + kv_k_index(layer, s.n_pages, kv_page(s, t), hkv, kvh, t % VF_TILE, piece * 8, HD));
-    }
-#pragma unroll
-    for (int i = 0; i < NK; ++i) {
-        // V^T tiles: per 64-key page [d][64]; piece = 8 consecutive keys of one d
-        const int pidx = i * 256 + tid, d = pidx / (ATT_KEYS / 8), piece = pidx % (ATT_KEYS / 8);
-        const int t = k_begin + piece * 8;
-        vreg[i] = zero4;
-        if (t < kmax)
-            vreg[i] = *reinterpret_cast<const u32x4 *>(
-                kv + kv_v_index(layer, s.n_pages, kv_page(s, t), hkv, kvh, t % VF_TILE, d, HD));
-    }
-#pragma unroll
-    for (int i = 0; i < NK; ++i) {
-        const int pidx = i * 256 + tid, key = pidx / KP, piece = pidx % KP;
-        *reinterpret_cast<u32x4 *>(L.Ks + key * KROW + piece * 8) = kreg[i];
-    }
-#pragma unroll
-    for (int i = 0; i < NK; ++i) {
-        const int pidx = i * 256 + tid, d = pidx / (ATT_KEYS / 8), piece = pidx % (ATT_KEYS / 8);
-        const int t = k_begin + piece * 8;
-        bf16x8 v = __builtin_bit_cast(bf16x8, vreg[i]);
-        if (t + 8 > kmax) {  // cache rows past the last key may hold anything: zero them
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (t + j >= kmax) v[j] = (bf16_t)0.f;
-        }
-        *reinterpret_cast<bf16x8 *>(L.Vs + d * VROW + piece * 8) = v;
-    }
-}
-
-// Online-softmax state of one block of 16 query items in one wavefront.
-template <int HD> struct AttState {
-    floatx4 o[HD / 16];
-    float m_run, l_run;
-};
-
-// One staged slice for one block of 16 items: S^T = K Q^T, masked online softmax, O^T += V^T P.
-// last_key: last visible key of this lane's item; blk_last: of any item in the block.
-template <int HD>
-__device__ inline void att_slice(AttState<HD> &st, const bf16x8 (&qf)[HD / 32], const AttLds<HD> &L, int k_begin,
-                                 int last_key, int blk_last, float scale_log2e, int lane) {
-    constexpr int KD = HD / 32, DB = HD / 16, KROW = AttLds<HD>::KROW, VROW = AttLds<HD>::VROW;
-    const int g4 = lane >> 4, l15 = lane & 15;
-#pragma unroll 1
-    for (int tl = 0; tl < ATT_KEYS; tl += 32) {
-        const int t0 = k_begin + tl;
-        if (t0 > blk_last) break;
-        floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kd = 0; kd < KD; ++kd) {
-            const bf16x8 k0 = *reinterpret_cast<const bf16x8 *>(L.Ks + (tl + l15) * KROW + kd * 32 + g4 * 8);
-            const bf16x8 k1 = *reinterpret_cast<const bf16x8 *>(L.Ks + (tl + 16 + l15) * KROW + kd * 32 + g4 * 8);
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[kd], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[kd], s1, 0, 0, 0);
-        }
-        // lane holds keys t0 + 4*g4 + j (s0) and t0 + 16 + 4*g4 + j (s1) of item l15
-        float tmax = -1e30f;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            s0[j] = (t0 + g4 * 4 + j <= last_key) ? s0[j] * scale_log2e : -1e30f;
-            s1[j] = (t0 + 16 + g4 * 4 + j <= last_key) ? s1[j] * scale_log2e : -1e30f;
-            tmax = fmaxf(tmax, fmaxf(s0[j], s1[j]));
-        }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-        const float m_new = fmaxf(st.m_run, tmax);
-        const float corr = exp2f(st.m_run - m_new);
-        float p[8], psum = 0.f;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            p[j] = (t0 + g4 * 4 + j <= last_key) ? exp2f(s0[j] - m_new) : 0.f;
-            p[4 + j] = (t0 + 16 + g4 * 4 + j <= last_key) ? exp2f(s1[j] - m_new) : 0.f;
-            psum += p[j] + p[4 + j];
-        }
-        psum += __shfl_xor(psum, 16, 64);
-        psum += __shfl_xor(psum, 32, 64);
-        st.l_run = st.l_run * corr + psum;
-        st.m_run = m_new;
-        // probabilities as a sum of two bfloat16 values (16 significant bits): the P * V product
-        // then carries no more rounding than its bfloat16 V operand
-        bf16x8 pf, pl;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            pf[j] = (bf16_t)p[j];
-            pl[j] = (bf16_t)(p[j] - (float)pf[j]);
-        }
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            const bf16_t *vr = L.Vs + (db * 16 + l15) * VROW + tl + g4 * 4;
-            const u32x2 lo = *reinterpret_cast<const u32x2 *>(vr);
-            const u32x2 hi = *reinterpret_cast<const u32x2 *>(vr + 16);
-            const u32x4 raw = {lo[0], lo[1], hi[0], hi[1]};
-            const bf16x8 vf = __builtin_bit_cast(bf16x8, raw);
-            st.o[db] = st.o[db] * corr;
-            st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, st.o[db], 0, 0, 0);
-            st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, st.o[db], 0, 0, 0);
-        }
-    }
-}
-
 // Few rows: one workgroup per (key slice, kv head, sequence); partial results per slice.
 template <int HD>
 __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
@@ -725,6 +473,7 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
     base.n_ss = d / 16;
     base.inv_d = 1.0f / (float)d;
     base.eps = c.rms_eps;
+    base.h_in = m->h;
     base.h = m->h;
     base.ss_out = m->ss;
     base.a_out = a;

@@ -1,0 +1,923 @@
+// The whole verify forward pass (paper Sec. 3 / Sec. 4.3: rows [T, x_1..x_k] of every sequence of
+// the batch through all decoder layers and the output head) as ONE persistent kernel.
+//
+// The grid is sized so that every workgroup is resident at once; the phases of the pass
+//   embed | per layer: QKV, attention, merge, O, gate/up, down | output head
+// are separated by grid-wide barriers instead of kernel boundaries.  What this buys over a chain
+// of kernels: no launch gap and no ramp-up per phase, and the weight stream never stops -- a
+// workgroup issues the first loads of its next phase (weights do not depend on the previous
+// phase) between arriving at a barrier and waiting on it, and inside a phase it refills its
+// register ring with the next work item's fragments while the current item is reduced.
+//
+// Memory protocol between workgroups (different compute dies have separate L2 caches):
+//   * everything one workgroup writes and another reads later in the launch is stored through
+//     to memory (agent-scope stores) and the barrier waits for those stores to complete;
+//   * bulk data is read with ordinary loads from single-assignment buffers -- one version of
+//     the residual stream per half layer, one q / attention output / SwiGLU buffer per layer --
+//     so no cache can hold a stale line of it: a line is never read before its only write in a
+//     launch, and caches start clean at every launch;
+//   * data in reused buffers (split-K partial tiles, attention partials, counters) is read with
+//     agent-scope loads.
+// The KV cache is written (new rows) and read (all rows) once per layer and launch, in that
+// order, so it follows the single-assignment rule as well.
+#include "fast_common.h"
+
+namespace {
+
+constexpr int FW = 8;            // wavefronts per workgroup
+constexpr int FT = FW * 64;      // threads per workgroup
+constexpr int FROWS = 48;        // most rows of a call
+constexpr int BAR_GROUP = 16;    // workgroups per first-level barrier counter
+constexpr int LDS_SMALL = 76 * 1024;   // dynamic LDS with which two workgroups fit one CU (static part included)
+constexpr int LDS_BIG = 152 * 1024;    // one workgroup per CU
+constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (seconds, not microseconds)
+
+// One workgroup of 8 wavefronts per CU: two wavefronts per SIMD, so each may use up to 256 vector
+// registers (weight ring + staging loads in flight) without spilling.
+#ifndef FUSED_PREFETCH_EARLY
+#define FUSED_PREFETCH_EARLY 1   // first weight loads of a phase go out before the barrier wait
+#endif
+#ifndef FUSED_G
+#define FUSED_G 256
+#endif
+
+struct FusedLayer {
+    const u32x4 *wqkv, *wo, *wgu, *wd;
+    const float *attn_norm, *ffn_norm, *bqkv;
+};
+
+struct FusedArgs {
+    const FusedLayer *layers;
+    const bf16_t *embed;
+    const u32x4 *lm_head;
+    const float *final_norm, *cosv, *sinv;
+    const int32_t *tokens;
+    float *hv;        // residual stream, [2L+1][FROWS][d]
+    float *ssv;       // sums of squares of its rows per 16 columns, [2L+1][d/16][64]
+    bf16_t *qv, *ov, *av;  // per layer: q [FROWS][Hq*hd], attention output, SwiGLU product [FROWS][F]
+    float *attn_part, *part;
+    int *counters;
+    unsigned *bar, *fail;
+    float *logits;
+    int n_layers, d, F, hq, hkv, hd, vocab, m, n_splits, has_bias;
+    float inv_d, eps, scale_log2e;
+    unsigned root0;   // value of the barrier's root counter when this launch starts
+    int ks_qkv, ks_o, ks_gu, ks_down;
+    int lds_total;    // dynamic LDS bytes of this launch
+};
+
+// Two-level counting barrier, split into arrive and wait.  Counters only ever grow: every barrier
+// adds one to the root counter per group of BAR_GROUP workgroups, so barrier number e of a launch is
+// complete when the root counter reaches its value at launch start + e * groups.
+struct GridBar {
+    unsigned *mem, *fail;
+    unsigned target, ng;
+    bool dead;
+    __device__ __forceinline__ void arrive() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this thread's stores have completed
+        __syncthreads();
+        target += ng;
+        if (threadIdx.x == 0) {
+            unsigned *gc = mem + 64 + (blockIdx.x % ng) * 64;
+            const unsigned old = __hip_atomic_fetch_add(gc, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (((old + 1u) & (BAR_GROUP - 1)) == 0u)
+                __hip_atomic_fetch_add(mem, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    __device__ __forceinline__ void wait() {
+        if (threadIdx.x == 0 && !dead) {
+            long long spins = 0;
+            while ((int)(__hip_atomic_load(mem, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+                __builtin_amdgcn_s_sleep(1);
+                ++spins;
+                if (spins > SPIN_LIMIT ||
+                    ((spins & 1023) == 0 && __hip_atomic_load(fail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                    __hip_atomic_store(fail, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    dead = true;  // give up for good: the launch drains without waiting again
+                    break;
+                }
+            }
+        }
+        __syncthreads();
+    }
+};
+
+// Optional phase timeline of one workgroup (build with -DFUSED_TRACE=<workgroup>): thread 0 stamps the
+// constant-rate clock at the marked points into the second half of the barrier block.
+#ifdef FUSED_TRACE
+struct Trace {
+    unsigned long long *buf;
+    int n;
+    __device__ __forceinline__ void mark(int id) {
+        if (blockIdx.x == FUSED_TRACE && threadIdx.x == 0 && n < 2040) {
+            buf[2 * n] = wall_clock64();
+            buf[2 * n + 1] = ((unsigned long long)clock64() << 8) | (unsigned long long)id;  // shader-clock count
+            ++n;
+        }
+    }
+};
+#define TRACE(id) trace.mark(id)
+#define TRACE_ARG , Trace &trace
+#define TRACE_PASS , trace
+#else
+#define TRACE(id)
+#define TRACE_ARG
+#define TRACE_PASS
+#endif
+
+struct FusedShared {
+    float rs_s[64];
+    float rs_tmp[FW][64];
+    int s_last;
+};
+
+// ---- embedding: row r by workgroup r ---------------------------------------------------------------
+__device__ __forceinline__ void embed_phase(const FusedArgs &a, const Batch &b) {
+    const int d = a.d;
+    for (int row = blockIdx.x; row < a.m; row += gridDim.x) {
+        int tok = a.tokens[row];
+        if (tok == VF_PENDING) tok = b.s[find_seq(b, row)].state[1];
+        if (tok < 0 || tok >= a.vocab) tok = 0;
+        for (int k0 = 0; k0 < d; k0 += FT) {
+            const int k = k0 + threadIdx.x;
+            float v = 0.f;
+            if (k < d) {
+                v = (float)a.embed[wfrag_index(tok, k, d)];
+                st_f32<true>(a.hv + (size_t)row * d + k, v);
+            }
+            float sq = v * v;
+            sq += __shfl_xor(sq, 8, 64);
+            sq += __shfl_xor(sq, 4, 64);
+            sq += __shfl_xor(sq, 2, 64);
+            sq += __shfl_xor(sq, 1, 64);
+            if (k < d && (threadIdx.x & 15) == 0) st_f32<true>(a.ssv + (k >> 4) * 64 + row, sq);
+        }
+    }
+}
+
+// ---- GEMM phase -------------------------------------------------------------------------------------
+// Work items = (unit of UB weight blocks) x (K split); workgroup w takes items w, w + G, ...  G is
+// a multiple of ks, so all items of a workgroup share one K slice and its activations are staged
+// in LDS once.  The wavefronts split the slice into equal runs of `cnt` k-blocks (the last run may
+// reach past the slice: those steps load a valid fragment again and multiply it by zero), and
+// each streams its fragments through a ring of PD registers per weight block, refilled with the
+// next item's fragments in the last round.  Trip counts are the same for every wavefront, so the
+// loop has no divergent branches.  The caller has arrived at the grid barrier; this function
+// waits on it after issuing the first loads.
+template <int NB, int UB, int PD, int EPI>
+__device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, GridBar &bar, unsigned char *smem,
+                                  int lds_total, FusedShared &sh TRACE_ARG) {
+    constexpr bool NORMED = EPI != EPI_RESID;
+    constexpr bool COH = EPI != EPI_LOGITS;  // logits are read by the next kernel only
+    constexpr int RW = FW / 2;               // wavefronts whose partial sums sit in LDS at a time
+    constexpr int RED_BYTES = RW * 2 * NB * 1024;
+    constexpr int XP = 16;                   // staging loads in flight per thread
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));  // per-thread index math is redone per phase instead of living across all of them
+    const int lane = tid & 63, wave = tid >> 6;
+    const int G = gridDim.x, wg = blockIdx.x;
+    const int m = g.m, KB = g.KB, NBt = g.N >> 4;
+    const int n_units = (NBt + UB - 1) / UB;
+    const int items = n_units * g.ks;
+    const int n_my = wg < items ? (items - wg + G - 1) / G : 0;
+    const int split = wg % g.ks;
+    const int kb0 = split * g.kbps, kb1 = min(KB, kb0 + g.kbps), nk = kb1 - kb0;
+    const int cnt = (nk + FW - 1) / FW;          // k-blocks per wavefront, the same for all
+    const int rounds = (cnt + PD - 1) / PD;
+    const int wk0 = kb0 + wave * cnt;            // this wavefront's run: wk0 .. wk0 + cnt - 1, valid below kb1
+    u32x4 *xs = reinterpret_cast<u32x4 *>(smem);
+    floatx4 *red = reinterpret_cast<floatx4 *>(smem + lds_total - RED_BYTES);
+    float *gain_s = reinterpret_cast<float *>(smem + lds_total - RED_BYTES);  // staging only: red is idle then
+
+    const u32x4 *wp[UB], *wpn[UB];
+    u32x4 w[PD][UB];
+#pragma unroll
+    for (int d = 0; d < PD; ++d)
+#pragma unroll
+        for (int u = 0; u < UB; ++u) w[d][u] = u32x4{0u, 0u, 0u, 0u};
+    auto unit_ptrs = [&](int it, const u32x4 *(&dst)[UB]) {
+        const int unit = (wg + it * G) / g.ks;
+#pragma unroll
+        for (int u = 0; u < UB; ++u) dst[u] = g.W + (size_t)min(unit * UB + u, NBt - 1) * KB * 64 + lane;
+    };
+    auto frag = [&](const u32x4 *base, int kbl) { return load_stream(base + (size_t)min(wk0 + kbl, kb1 - 1) * 64); };
+    auto first_fragments = [&]() {
+        unit_ptrs(0, wp);
+#pragma unroll
+        for (int d = 0; d < PD; ++d)
+            if (d < cnt)
+#pragma unroll
+                for (int u = 0; u < UB; ++u) w[d][u] = frag(wp[u], d);
+    };
+    if (FUSED_PREFETCH_EARLY && n_my > 0) first_fragments();
+    TRACE(1);
+    bar.wait();
+    TRACE(2);
+    if (n_my == 0) return;
+
+    // ---- stage the activations of this K slice: every global load goes out before the first use ----
+    if (NORMED) {
+        // x = bf16(h * rstd * gain) with rstd = 1/rms from the per-16-column sums of squares
+        // (lane = row, wavefront = every FW-th block of columns); pieces of four columns
+        const int chunks = nk * 8, pieces = m * chunks;
+        const int qstep = FT / chunks, rstep = FT % chunks;
+        float t[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int j = wave + i * FW;
+            t[i] = (lane < m && j < g.n_ss) ? g.ss_in[j * 64 + lane] : 0.f;
+        }
+        floatx4 gn = {0.f, 0.f, 0.f, 0.f};
+        if (tid < chunks) gn = *reinterpret_cast<const floatx4 *>(g.gain + (size_t)kb0 * 32 + tid * 4);
+        for (int base = 0; base < pieces; base += FT * XP) {
+            floatx4 v[XP];
+            int row = (base + tid) / chunks, c = (base + tid) % chunks;
+            const int row0 = row, c0 = c;
+#pragma unroll
+            for (int i = 0; i < XP; ++i) {
+                if (base + tid + i * FT < pieces)
+                    v[i] = *reinterpret_cast<const floatx4 *>(g.Xh + (size_t)row * KB * 32 + (size_t)kb0 * 32 + c * 4);
+                row += qstep;
+                c += rstep;
+                if (c >= chunks) { c -= chunks; ++row; }
+            }
+            if (base == 0) {
+                if (!FUSED_PREFETCH_EARLY) first_fragments();
+                float sum = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum += t[i];
+                if (lane < m)
+                    for (int j = wave + 16 * FW; j < g.n_ss; j += FW) sum += g.ss_in[j * 64 + lane];
+                sh.rs_tmp[wave][lane] = sum;
+                for (int cc = tid; cc < chunks; cc += FT) {
+                    if (cc != tid) gn = *reinterpret_cast<const floatx4 *>(g.gain + (size_t)kb0 * 32 + cc * 4);
+                    *reinterpret_cast<floatx4 *>(gain_s + cc * 4) = gn;
+                }
+                __syncthreads();
+                TRACE(6);
+                if (tid < 64) {
+                    float tot = 0.f;
+#pragma unroll
+                    for (int j = 0; j < FW; ++j) tot += sh.rs_tmp[j][tid];
+                    sh.rs_s[tid] = 1.0f / sqrtf(tot * g.inv_d + g.eps);
+                }
+                __syncthreads();
+                TRACE(7);
+            }
+            row = row0;
+            c = c0;
+#pragma unroll
+            for (int i = 0; i < XP; ++i) {
+                if (base + tid + i * FT < pieces) {
+                    const float r = sh.rs_s[row];
+                    const floatx4 gv = *reinterpret_cast<const floatx4 *>(gain_s + c * 4);
+                    u32x2 *dst = reinterpret_cast<u32x2 *>(xs) + (((c >> 3) * m + row) * 8 + (c & 7));
+                    *dst = pack4_bf16(v[i][0] * r * gv[0], v[i][1] * r * gv[1], v[i][2] * r * gv[2], v[i][3] * r * gv[3]);
+                }
+                row += qstep;
+                c += rstep;
+                if (c >= chunks) { c -= chunks; ++row; }
+            }
+        }
+    } else {
+        const int chunks = nk * 4, pieces = m * chunks;
+        const int qstep = FT / chunks, rstep = FT % chunks;
+        for (int base = 0; base < pieces; base += FT * XP) {
+            u32x4 v[XP];
+            int row = (base + tid) / chunks, c = (base + tid) % chunks;
+            const int row0 = row, c0 = c;
+#pragma unroll
+            for (int i = 0; i < XP; ++i) {
+                if (base + tid + i * FT < pieces)
+                    v[i] = *reinterpret_cast<const u32x4 *>(g.X + (size_t)row * KB * 32 + (size_t)kb0 * 32 + c * 8);
+                row += qstep;
+                c += rstep;
+                if (c >= chunks) { c -= chunks; ++row; }
+            }
+            if (!FUSED_PREFETCH_EARLY && base == 0) first_fragments();
+            row = row0;
+            c = c0;
+#pragma unroll
+            for (int i = 0; i < XP; ++i) {
+                if (base + tid + i * FT < pieces) xs[((c >> 2) * m + row) * 4 + (c & 3)] = v[i];
+                row += qstep;
+                c += rstep;
+                if (c >= chunks) { c -= chunks; ++row; }
+            }
+        }
+    }
+    __syncthreads();
+    TRACE(3);
+
+    int rowc[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) rowc[c] = min(c * 16 + (lane & 15), m - 1);
+
+    for (int it = 0; it < n_my; ++it) {
+        const bool has_next = it + 1 < n_my;
+        if (has_next) unit_ptrs(it + 1, wpn);
+        const int unit = (wg + it * G) / g.ks;
+        const int nb0 = unit * UB;
+        floatx4 acc[UB][NB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+#pragma unroll
+            for (int c = 0; c < NB; ++c) acc[u][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+        for (int r = 0; r < rounds; ++r) {
+            const bool last_round = r + 1 == rounds;
+#pragma unroll
+            for (int d = 0; d < PD; ++d) {
+                const int kbl = r * PD + d;
+                if (kbl < cnt) {  // the same for every wavefront
+                    const bool live = wk0 + kbl < kb1;
+                    bf16x8 a[UB];
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) a[u] = __builtin_bit_cast(bf16x8, live ? w[d][u] : u32x4{0u, 0u, 0u, 0u});
+                    if (!last_round) {
+                        if (kbl + PD < cnt)
+#pragma unroll
+                            for (int u = 0; u < UB; ++u) w[d][u] = frag(wp[u], kbl + PD);
+                    } else if (has_next) {
+                        if (d < cnt)
+#pragma unroll
+                            for (int u = 0; u < UB; ++u) w[d][u] = frag(wpn[u], d);
+                    }
+                    const int kx = min(wk0 + kbl, kb1 - 1) - kb0;
+#pragma unroll
+                    for (int c = 0; c < NB; ++c) {
+                        const bf16x8 bb = __builtin_bit_cast(bf16x8, xs[(kx * m + rowc[c]) * 4 + (lane >> 4)]);
+#pragma unroll
+                        for (int u = 0; u < UB; ++u)
+                            acc[u][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], bb, acc[u][c], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        TRACE(4);
+        // ---- wavefront partial sums: upper half through LDS into the lower half, then all four ----
+        if (wave >= RW) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+#pragma unroll
+                for (int c = 0; c < NB; ++c) red[(((wave - RW) * UB + u) * NB + c) * 64 + lane] = acc[u][c];
+        }
+        __syncthreads();
+        if (wave < RW) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+#pragma unroll
+                for (int c = 0; c < NB; ++c) {
+                    const int idx = ((wave * UB + u) * NB + c) * 64 + lane;
+                    red[idx] = acc[u][c] + red[idx];
+                }
+        }
+        __syncthreads();
+
+        constexpr int NT = UB * NB * 64;                       // tiles of 4 outputs per unit
+        constexpr int NTH = EPI == EPI_SWIGLU ? NB * 64 : NT;  // tiles with an epilogue of their own
+        static_assert(NTH <= FT, "one tile per thread");
+        const int t = tid;
+        floatx4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
+        if (t < NTH) {
+            if (EPI == EPI_SWIGLU) {
+                const int c = t >> 6;
+#pragma unroll
+                for (int ww = 0; ww < RW; ++ww) {
+                    v0 += red[((ww * UB + 0) * NB + c) * 64 + lane];
+                    v1 += red[((ww * UB + (UB - 1)) * NB + c) * 64 + lane];
+                }
+            } else {
+                const int u = t / (NB * 64), c = (t >> 6) % NB;
+#pragma unroll
+                for (int ww = 0; ww < RW; ++ww) v0 += red[((ww * UB + u) * NB + c) * 64 + lane];
+            }
+        }
+        bool do_epi = true;
+        if (g.ks > 1) {
+            float *mine = g.part + ((size_t)(unit * g.ks + split) * NT) * 4;
+            if (t < NTH) {
+                store_coherent(mine + (size_t)t * 4, v0);
+                if (EPI == EPI_SWIGLU) store_coherent(mine + (size_t)(NTH + t) * 4, v1);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __syncthreads();
+            if (tid == 0) {
+                const int old = __hip_atomic_fetch_add(g.counters + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                sh.s_last = old == g.ks - 1;
+                if (old == g.ks - 1) __hip_atomic_store(g.counters + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __syncthreads();
+            do_epi = sh.s_last != 0;
+            if (do_epi && t < NTH) {
+                v0 = floatx4{0.f, 0.f, 0.f, 0.f};
+                v1 = floatx4{0.f, 0.f, 0.f, 0.f};
+                for (int sp0 = 0; sp0 < g.ks; sp0 += 8) {
+                    floatx4 t0[8], t1[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        t0[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+                        t1[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+                        if (sp0 + i < g.ks) {
+                            const float *p = g.part + ((size_t)(unit * g.ks + sp0 + i) * NT) * 4;
+                            t0[i] = load_coherent(p + (size_t)t * 4);
+                            if (EPI == EPI_SWIGLU) t1[i] = load_coherent(p + (size_t)(NTH + t) * 4);
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        v0 += t0[i];
+                        v1 += t1[i];
+                    }
+                }
+            }
+        }
+        if (do_epi && t < NTH) {  // whole wavefronts: NTH is a multiple of 64
+            const int u = EPI == EPI_SWIGLU ? 0 : t / (NB * 64), c = (t >> 6) % NB;
+            const int nb = nb0 + u;
+            const int row = c * 16 + (lane & 15);
+            const bool live = row < m && nb < NBt;
+            if (EPI == EPI_RESID) {
+                epi_resid<COH>(g, row, live, nb, lane, v0);
+            } else if (live) {
+                if (EPI == EPI_QKV) epi_qkv<COH>(g, b, row, nb, lane, v0);
+                else if (EPI == EPI_SWIGLU) epi_swiglu<COH>(g, row, nb, lane, v0, v1);
+                else __builtin_nontemporal_store(v0, reinterpret_cast<floatx4 *>(g.logits + (size_t)row * g.N + nb * 16 + (lane >> 4) * 4));
+            }
+        }
+        TRACE(5);
+        if (has_next) {
+            __syncthreads();  // the partial sums in LDS are consumed before the next item's arrive
+#pragma unroll
+            for (int u = 0; u < UB; ++u) wp[u] = wpn[u];
+        }
+    }
+}
+
+// ---- attention phase: work item = (key slice, kv head, sequence) ---------------------------------------
+template <int HD>
+__device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, int layer, const bf16_t *q, GridBar &bar,
+                                  unsigned char *smem TRACE_ARG) {
+    constexpr int KD = HD / 32, DB = HD / 16, REC = HD + ATTF_STRIDE_PAD;
+    AttLds<HD> &L = *reinterpret_cast<AttLds<HD> *>(smem);
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = tid >> 6, g4 = lane >> 4, l15 = lane & 15;
+    const int G = gridDim.x, hq = a.hq, hkv = a.hkv, group = hq / hkv;
+    const int per_seq = a.n_splits * hkv;
+    const int items = per_seq * b.n_seqs;
+    AttStage<HD, FT> stage;
+    // keys below the sequence length were written by earlier calls: their loads may precede the barrier
+    bool preloaded = false;
+    if ((int)blockIdx.x < items) {
+        const int i = blockIdx.x;
+        const SeqDesc &s = b.s[i / per_seq];
+        const int split = i % a.n_splits, kvh = (i % per_seq) / a.n_splits;
+        const int len = s.state[0];
+        const int k_begin = split * ATT_KEYS;
+        if (k_begin + ATT_KEYS <= len) {
+            stage.load(s, layer, hkv, kvh, k_begin, len, tid);
+            preloaded = true;
+        }
+    }
+    TRACE(1);
+    bar.wait();
+    TRACE(2);
+    for (int i = blockIdx.x; i < items; i += G) {
+        const SeqDesc &s = b.s[i / per_seq];
+        const int split = i % a.n_splits, kvh = (i % per_seq) / a.n_splits;
+        const int n_items = s.nrows * group;
+        const int len = s.state[0];
+        const int kmax = min(len + s.nrows, s.capacity);  // keys 0..kmax-1 exist
+        const int k_begin = split * ATT_KEYS;
+        if (k_begin >= kmax) continue;                    // the same for the whole workgroup
+        if (!preloaded) stage.load(s, layer, hkv, kvh, k_begin, kmax, tid);
+        const int nqb = (n_items + 15) >> 4;
+        // the first query block's fragments travel while the slice is written to LDS
+        bf16x8 qf[KD];
+        {
+            const int item = wave * 16 + l15;
+            const bool valid = wave < nqb && item < n_items;
+            const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
+#pragma unroll
+            for (int kd = 0; kd < KD; ++kd)
+                qf[kd] = *reinterpret_cast<const bf16x8 *>(q + ((size_t)(s.row0 + r) * hq + head) * HD + kd * 32 + g4 * 8);
+        }
+        if (i != (int)blockIdx.x) __syncthreads();  // previous slice consumed
+        stage.store(L, k_begin, preloaded ? len : kmax, tid);
+        preloaded = false;
+        __syncthreads();
+        for (int qb = wave; qb < nqb; qb += FW) {
+            const int item = qb * 16 + l15;
+            const bool valid = item < n_items;
+            const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
+            const int row = s.row0 + r;
+            const int last_key = valid ? len + r : -1;
+            const int blk_last = len + min(s.nrows - 1, (qb * 16 + 15) / group);
+            if (qb != wave) {
+#pragma unroll
+                for (int kd = 0; kd < KD; ++kd)
+                    qf[kd] = *reinterpret_cast<const bf16x8 *>(q + ((size_t)row * hq + head) * HD + kd * 32 + g4 * 8);
+            }
+            AttState<HD> st;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) st.o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
+            st.m_run = -1e30f;
+            st.l_run = 0.f;
+            att_slice<HD>(st, qf, L, k_begin, last_key, blk_last, a.scale_log2e, lane);
+            if (valid) {
+                float *out = a.attn_part + (((size_t)row * hq + head) * a.n_splits + split) * REC;
+                if (g4 == 0) st_u32x2<true>(out, __builtin_bit_cast(u32x2, float2{st.m_run, st.l_run}));
+#pragma unroll
+                for (int db = 0; db < DB; ++db) st_f32x4<true>(out + ATTF_STRIDE_PAD + db * 16 + g4 * 4, st.o[db]);
+            }
+        }
+    }
+}
+
+// ---- merge of the key slices by log-sum-exp: one wavefront per (row, head) ------------------------------
+template <int HD>
+__device__ __forceinline__ void combine_phase(const FusedArgs &a, const Batch &b, bf16_t *o) {
+    constexpr int REC = HD + ATTF_STRIDE_PAD, DPL = HD / 64;  // d values per lane
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = tid >> 6;
+    const int G = gridDim.x, hq = a.hq, n_splits = a.n_splits;
+    const int n_items = a.m * hq;
+    for (int i = blockIdx.x + G * wave; i < n_items; i += G * FW) {
+        const int row = i / hq, head = i % hq;
+        const SeqDesc &s = b.s[find_seq(b, row)];
+        const int kmax = min(s.state[0] + s.nrows, s.capacity);
+        const int used = min(n_splits, (kmax + ATT_KEYS - 1) / ATT_KEYS);  // slices that had keys
+        const float *p = a.attn_part + ((size_t)row * hq + head) * n_splits * REC;
+        // slice maxima and sums: lane j holds slices j and j + 64
+        float mv[2], lv[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int j = lane + h * 64;
+            mv[h] = -1e30f;
+            lv[h] = 0.f;
+            if (j < used) {
+                const unsigned long long raw = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p + (size_t)j * REC),
+                                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float2 ml = __builtin_bit_cast(float2, raw);
+                mv[h] = ml.x;
+                lv[h] = ml.y;
+            }
+        }
+        float M = fmaxf(mv[0], mv[1]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+        float wv[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) wv[h] = (lane + h * 64 < used) ? exp2f(mv[h] - M) : 0.f;
+        float Lsum = 0.f, acc[DPL];
+#pragma unroll
+        for (int j = 0; j < DPL; ++j) acc[j] = 0.f;
+        for (int j0 = 0; j0 < used; j0 += 8) {
+            float t[8][DPL], wj[8];
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {
+                const int j = j0 + jj;
+                const int src = j & 63;
+                const float wlo = __shfl(wv[0], src, 64), whi = __shfl(wv[1], src, 64);
+                const float llo = __shfl(lv[0], src, 64), lhi = __shfl(lv[1], src, 64);
+                wj[jj] = j < used ? (j < 64 ? wlo : whi) : 0.f;
+                const float lj = j < used ? (j < 64 ? llo : lhi) : 0.f;
+                Lsum += lj * wj[jj];
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) t[jj][e] = 0.f;
+                if (j < used) {
+                    const float *src_p = p + (size_t)j * REC + ATTF_STRIDE_PAD + lane * DPL;
+                    if (DPL == 2) {
+                        const unsigned long long raw = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(src_p),
+                                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const float2 v = __builtin_bit_cast(float2, raw);
+                        t[jj][0] = v.x;
+                        t[jj][DPL - 1] = v.y;
+                    } else {
+                        t[jj][0] = load_coherent1(src_p);
+                    }
+                }
+            }
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj)
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) acc[e] += t[jj][e] * wj[jj];
+        }
+        bf16_t *dst = o + (size_t)row * hq * HD + head * HD + lane * DPL;
+        if (DPL == 2) {
+            st_u32<true>(dst, pack2_bf16(acc[0] / Lsum, acc[DPL - 1] / Lsum));
+        } else {
+            const bf16_t x = (bf16_t)(acc[0] / Lsum);
+            st_u16<true>(dst, __builtin_bit_cast(unsigned short, x));
+        }
+    }
+}
+
+template <int NB, int HD>
+#ifndef FUSED_MINW
+#define FUSED_MINW 2
+#endif
+__global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs a, Batch b) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ FusedShared sh;
+    GridBar bar{a.bar, a.fail, a.root0, gridDim.x / BAR_GROUP, false};
+    const int d = a.d, F = a.F, hd = a.hd, nq = a.hq * hd, nkv = a.hkv * hd;
+#ifdef FUSED_ALIAS_PROBE
+    const size_t hstride = 0, sstride = 0;
+#else
+    const size_t hstride = (size_t)FROWS * d, sstride = (size_t)(d / 16) * 64;
+#endif
+
+#ifdef FUSED_TRACE
+    Trace trace{reinterpret_cast<unsigned long long *>(a.bar + 8192), 0};
+#endif
+    TRACE(0);
+    embed_phase(a, b);
+    bar.arrive();
+
+    FastGemm base;
+    base.m = a.m;
+    base.part = a.part;
+    base.counters = a.counters;
+    base.n_ss = d / 16;
+    base.inv_d = a.inv_d;
+    base.eps = a.eps;
+    base.F = F;
+    base.cosv = a.cosv;
+    base.sinv = a.sinv;
+    base.hq = a.hq;
+    base.hkv = a.hkv;
+    base.hd = hd;
+    base.kch = 0;
+    base.X = nullptr; base.Xh = nullptr; base.gain = nullptr; base.ss_in = nullptr; base.h_in = nullptr;
+    base.h = nullptr; base.ss_out = nullptr; base.a_out = nullptr; base.logits = nullptr; base.bias = nullptr;
+    base.q = nullptr; base.layer = 0;
+
+#pragma unroll 1
+    for (int l = 0; l < a.n_layers; ++l) {
+        const FusedLayer lp = a.layers[l];
+        float *h0 = a.hv + (size_t)(2 * l) * hstride, *h1 = h0 + hstride, *h2 = h1 + hstride;
+        float *ss0 = a.ssv + (size_t)(2 * l) * sstride, *ss1 = ss0 + sstride, *ss2 = ss1 + sstride;
+        bf16_t *q = a.qv + (size_t)l * FROWS * nq, *o = a.ov + (size_t)l * FROWS * nq;
+        bf16_t *act = a.av + (size_t)l * FROWS * F;
+        {
+            FastGemm g = base;
+            g.W = lp.wqkv; g.N = nq + 2 * nkv; g.KB = d / 32; g.Xh = h0; g.gain = lp.attn_norm; g.ss_in = ss0;
+            g.bias = a.has_bias ? lp.bqkv : nullptr; g.layer = l; g.q = q;
+            g.ks = a.ks_qkv; g.kbps = (g.KB + g.ks - 1) / g.ks;
+            gemm_phase<NB, 1, 8, EPI_QKV>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+        }
+        bar.arrive();
+        TRACE(10);
+        attn_phase<HD>(a, b, l, q, bar, smem TRACE_PASS);
+        bar.arrive();
+        TRACE(11);
+        bar.wait();
+        TRACE(12);
+        combine_phase<HD>(a, b, o);
+        bar.arrive();
+        TRACE(13);
+        {
+            FastGemm g = base;
+            g.W = lp.wo; g.N = d; g.KB = nq / 32; g.X = o; g.h_in = h0; g.h = h1; g.ss_out = ss1;
+            g.ks = a.ks_o; g.kbps = (g.KB + g.ks - 1) / g.ks;
+            gemm_phase<NB, 1, 8, EPI_RESID>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+        }
+        bar.arrive();
+        TRACE(14);
+        {
+            FastGemm g = base;
+            g.W = lp.wgu; g.N = 2 * F; g.KB = d / 32; g.Xh = h1; g.gain = lp.ffn_norm; g.ss_in = ss1; g.a_out = act;
+            g.ks = a.ks_gu; g.kbps = (g.KB + g.ks - 1) / g.ks;
+            gemm_phase<NB, 2, 6, EPI_SWIGLU>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+        }
+        bar.arrive();
+        TRACE(15);
+        {
+            FastGemm g = base;
+            g.W = lp.wd; g.N = d; g.KB = F / 32; g.X = act; g.h_in = h1; g.h = h2; g.ss_out = ss2;
+            g.ks = a.ks_down; g.kbps = (g.KB + g.ks - 1) / g.ks;
+            gemm_phase<NB, 2, 6, EPI_RESID>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+        }
+        bar.arrive();
+        TRACE(16);
+    }
+    {
+        FastGemm g = base;
+        g.W = a.lm_head; g.N = a.vocab; g.KB = d / 32;
+        g.Xh = a.hv + (size_t)(2 * a.n_layers) * hstride; g.gain = a.final_norm;
+        g.ss_in = a.ssv + (size_t)(2 * a.n_layers) * sstride; g.logits = a.logits;
+        g.ks = 1; g.kbps = g.KB;
+        gemm_phase<NB, 2, 6, EPI_LOGITS>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+    }
+    TRACE(99);
+}
+
+// ---- host side -------------------------------------------------------------------------------------
+
+// Largest K slice (in 32-wide blocks) whose activations fit LDS next to the partial sums.
+int slice_limit(int lds_total, int rows, int nb) {
+    const int x_bytes = lds_total - (FW / 2) * 2 * nb * 1024;
+    return x_bytes / (rows * 64);
+}
+
+// K split for a phase: a divisor of G, at least what LDS demands; with allow_fill as many more
+// splits as keep the item count within one item per workgroup.  0: nothing fits.
+int pick_split(int G, int lds_total, int units, int KB, int rows, int nb, bool allow_fill) {
+    const int lim = slice_limit(lds_total, rows, nb);
+    int best = 0;
+    for (int ks = 1; ks <= G && ks <= KB; ++ks) {
+        if (G % ks) continue;
+        const int kbps = (KB + ks - 1) / ks;
+        if ((KB + kbps - 1) / kbps != ks) continue;  // every split must own k-blocks
+        if (kbps > lim) continue;
+        if (!best) best = ks;
+        if (!allow_fill) break;
+        if (units * ks <= G && kbps >= FW) best = ks;
+    }
+    return best;
+}
+
+template <int NB, int HD>
+int launch_fused(vf_model *m, FusedArgs &a, const Batch &b, int G, hipStream_t st) {
+    auto kern = verify_fused_kernel<NB, HD>;
+    static int max_wgs[2] = {-1, -1};  // resident workgroups with LDS_SMALL / LDS_BIG
+    const int which = a.lds_total == LDS_BIG;
+    if (max_wgs[which] < 0) {
+        VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   LDS_BIG));
+        int per_cu = 0, dev = 0;
+        hipDeviceProp_t prop;
+        VF_HIP(hipGetDevice(&dev));
+        VF_HIP(hipGetDeviceProperties(&prop, dev));
+        VF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kern), FT,
+                                                            a.lds_total));
+        max_wgs[which] = per_cu * prop.multiProcessorCount;
+    }
+    if (G > max_wgs[which])
+        return vf_fail(VF_ERR_UNSUPPORTED, "persistent kernel: %d workgroups wanted, %d can be resident", G,
+                       max_wgs[which]);
+    hipLaunchKernelGGL(kern, dim3(G), dim3(FT), a.lds_total, st, a, b);
+    VF_LAUNCH_CHECK("verify_fused");
+    return VF_OK;
+}
+
+}  // namespace
+
+size_t vf_fused_workspace_bytes(const vf_config &c) {
+    if (c.dtype != VF_BF16) return 0;
+    const size_t L = c.n_layers, d = c.d_model, nq = (size_t)c.n_q_heads * c.head_dim, F = c.d_ffn;
+    size_t n = 0;
+    auto add = [&](size_t bytes) { n += (bytes + 255) & ~(size_t)255; };
+    add((2 * L + 1) * FROWS * d * 4);
+    add((2 * L + 1) * (d / 16) * 64 * 4);
+    add(L * FROWS * nq * 2);
+    add(L * FROWS * nq * 2);
+    add(L * FROWS * F * 2);
+    add(65536);
+    add(L * sizeof(FusedLayer));
+    return n;
+}
+
+int vf_fused_init(vf_model *m, char *ws, hipStream_t st) {
+    const vf_config &c = m->cfg;
+    const size_t L = c.n_layers, d = c.d_model, nq = (size_t)c.n_q_heads * c.head_dim, F = c.d_ffn;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char *p = ws + off; off += (bytes + 255) & ~(size_t)255; return p; };
+    m->fz_h = (float *)take((2 * L + 1) * FROWS * d * 4);
+    m->fz_ss = (float *)take((2 * L + 1) * (d / 16) * 64 * 4);
+    m->fz_q = take(L * FROWS * nq * 2);
+    m->fz_o = take(L * FROWS * nq * 2);
+    m->fz_a = take(L * FROWS * F * 2);
+    m->fz_bar = (unsigned *)take(65536);
+    m->fz_layers = take(L * sizeof(FusedLayer));
+    std::vector<FusedLayer> host(L);
+    for (size_t l = 0; l < L; ++l) {
+        const LayerPacked &lp = m->layers[l];
+        host[l] = FusedLayer{(const u32x4 *)lp.wqkv, (const u32x4 *)lp.wo, (const u32x4 *)lp.wgu, (const u32x4 *)lp.wd,
+                             lp.attn_norm, lp.ffn_norm, lp.bqkv};
+    }
+    VF_HIP(hipMemcpyAsync(m->fz_layers, host.data(), L * sizeof(FusedLayer), hipMemcpyHostToDevice, st));
+    VF_HIP(hipStreamSynchronize(st));  // the host array goes away
+    m->fz_epoch = 0;
+    return VF_OK;
+}
+
+// Whether the persistent kernel can run this call; fills the grid size, LDS size and K splits.
+static bool plan_fused(const vf_model *m, const Batch &b, FusedArgs &a, int *G_out) {
+    const vf_config &c = m->cfg;
+    if (c.dtype != VF_BF16 || !m->fz_h || b.total_rows > FROWS || c.d_model % 64) return false;
+    const int rows = b.total_rows, nb = (rows + 15) / 16;
+    const int d = c.d_model, F = c.d_ffn, hd = c.head_dim, nq = c.n_q_heads * hd, nkv = c.n_kv_heads * hd;
+    if (std::max((nq + 2 * nkv) / 16, F / 16) > VF_N_COUNTERS) return false;
+    for (int big = 0; big < 2; ++big) {
+        const int G = big ? 256 : FUSED_G, lds = big ? LDS_BIG : LDS_SMALL;
+        if (G % BAR_GROUP) continue;
+        a.ks_qkv = pick_split(G, lds, (nq + 2 * nkv) / 16, d / 32, rows, nb, false);
+        a.ks_o = pick_split(G, lds, d / 16, nq / 32, rows, nb, false);
+        a.ks_gu = pick_split(G, lds, F / 16, d / 32, rows, nb, false);
+        a.ks_down = pick_split(G, lds, (d / 16 + 1) / 2, F / 32, rows, nb, true);
+        const int ks_head = pick_split(G, lds, (c.vocab / 16 + 1) / 2, d / 32, rows, nb, false);
+        if (!a.ks_qkv || !a.ks_o || !a.ks_gu || !a.ks_down || ks_head != 1) continue;
+        // the gain slice of a normalising phase is staged where the partial sums go later
+        const int red_bytes = (FW / 2) * 2 * nb * 1024;
+        if ((d / 32 + a.ks_gu - 1) / a.ks_gu * 128 > red_bytes || (d / 32 + a.ks_qkv - 1) / a.ks_qkv * 128 > red_bytes ||
+            d / 32 * 128 > red_bytes)
+            continue;
+        // partial tiles of the split phases: units * ks tiles of UB * NB * 256 floats
+        const size_t tiles = std::max(std::max((nq + 2 * nkv) / 16 * a.ks_qkv, d / 16 * a.ks_o),
+                                      std::max(F / 16 * a.ks_gu, (d / 16 + 1) / 2 * a.ks_down));
+        if (tiles * 2 * nb * 256 > m->part_floats) continue;
+        a.lds_total = lds;
+        *G_out = G;
+        return true;
+    }
+    return false;
+}
+
+bool vf_fused_ok(const vf_model *m, const Batch &b) {
+    FusedArgs a;
+    int G;
+    return plan_fused(m, b, a, &G);
+}
+
+int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, hipStream_t st) {
+    const vf_config &c = m->cfg;
+    FusedArgs a;
+    memset(&a, 0, sizeof a);
+    int G = 0;
+    if (!plan_fused(m, b, a, &G)) return vf_fail(VF_ERR_UNSUPPORTED, "persistent kernel does not apply to this call");
+    int max_keys = 0;
+    for (int i = 0; i < b.n_seqs; ++i) max_keys = std::max(max_keys, b.s[i].len_ub + b.s[i].nrows);
+    const int n_splits = (max_keys + ATT_KEYS - 1) / ATT_KEYS;
+    if (n_splits > VF_ATTN_SPLIT_MAX) return vf_fail(VF_ERR_UNSUPPORTED, "context of %d keys", max_keys);
+    a.layers = (const FusedLayer *)m->fz_layers;
+    a.embed = (const bf16_t *)m->embed;
+    a.lm_head = (const u32x4 *)m->lm_head;
+    a.final_norm = m->final_norm;
+    a.cosv = m->rope_cos;
+    a.sinv = m->rope_sin;
+    a.tokens = tokens;
+    a.hv = m->fz_h;
+    a.ssv = m->fz_ss;
+    a.qv = (bf16_t *)m->fz_q;
+    a.ov = (bf16_t *)m->fz_o;
+    a.av = (bf16_t *)m->fz_a;
+    a.attn_part = m->attn_part;
+    a.part = m->part;
+    a.counters = m->counters;
+    a.bar = m->fz_bar;
+    a.fail = m->fz_bar + 8000;
+    a.logits = logits_out;
+    a.n_layers = c.n_layers;
+    a.d = c.d_model;
+    a.F = c.d_ffn;
+    a.hq = c.n_q_heads;
+    a.hkv = c.n_kv_heads;
+    a.hd = c.head_dim;
+    a.vocab = c.vocab;
+    a.m = b.total_rows;
+    a.n_splits = n_splits;
+    a.has_bias = c.qkv_bias;
+    a.inv_d = 1.0f / (float)c.d_model;
+    a.eps = c.rms_eps;
+    a.scale_log2e = 1.4426950408889634f / sqrtf((float)c.head_dim);
+    a.root0 = m->fz_epoch;
+    m->fz_epoch += (1u + 6u * (unsigned)c.n_layers) * (unsigned)(G / BAR_GROUP);  // barriers per launch x groups
+    const int rows = b.total_rows;
+    ProfScope ps(m, VF_SITE_STEP, st);
+    if (c.head_dim == 128) {
+        if (rows <= 16) return launch_fused<1, 128>(m, a, b, G, st);
+        if (rows <= 32) return launch_fused<2, 128>(m, a, b, G, st);
+        return launch_fused<3, 128>(m, a, b, G, st);
+    }
+    if (rows <= 16) return launch_fused<1, 64>(m, a, b, G, st);
+    if (rows <= 32) return launch_fused<2, 64>(m, a, b, G, st);
+    return launch_fused<3, 64>(m, a, b, G, st);
+}
+
+// Whether any barrier of an earlier launch gave up (the stream must be idle).
+int vf_fused_check(vf_model *m) {
+    if (!m->fz_bar) return VF_OK;
+    unsigned flag = 0;
+    VF_HIP(hipMemcpy(&flag, m->fz_bar + 8000, 4, hipMemcpyDeviceToHost));
+    if (flag) {
+        // counters are out of step now: start over from zero
+        VF_HIP(hipMemset(m->fz_bar, 0, 65536));
+        VF_HIP(hipMemset(m->counters, 0, VF_N_COUNTERS * 4));
+        m->fz_epoch = 0;
+        return vf_fail(VF_ERR_HIP, "persistent verify kernel: a grid barrier timed out; results of that call are invalid");
+    }
+    return VF_OK;
+}
+
+#ifdef FUSED_TRACE
+// Copies the phase timeline of the traced workgroup's last launch: pairs (clock, mark id).
+extern "C" int vf_debug_trace(vf_model *m, unsigned long long *out_host, int n_pairs) {
+    VF_HIP(hipDeviceSynchronize());
+    VF_HIP(hipMemcpy(out_host, m->fz_bar + 8192, (size_t)n_pairs * 16, hipMemcpyDeviceToHost));
+    return VF_OK;
+}
+#endif

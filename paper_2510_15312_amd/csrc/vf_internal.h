@@ -84,6 +84,13 @@ struct vf_model {
     float *ss;                  // per-16-column sums of squares of h rows, [d/16][64]
     int32_t *counters;          // split-K arrival counters, [VF_N_COUNTERS], zero between kernels
     int fast_path;              // option: use the few-row kernels when they apply
+    int persistent;             // option: use the persistent whole-pass kernel when it applies
+    // persistent kernel: single-assignment activation buffers, barrier counters, layer table
+    float *fz_h, *fz_ss;
+    void *fz_q, *fz_o, *fz_a, *fz_layers;
+    unsigned *fz_bar;
+    char *fz_ws;                // their workspace
+    unsigned fz_epoch;          // value the barrier's root counter has after all launches so far
     const float *last_logits;   // where the last verify left its logits
     int last_rows;
     // measurement hook
@@ -214,11 +221,18 @@ int vf_launch_state_set(int32_t *state, int idx, int32_t value, hipStream_t st);
 int vf_launch_state_add(int32_t *state, int idx, int32_t delta, hipStream_t st);
 int vf_launch_kv_read(const vf_model *m, const SeqDesc &s, int layer, int t0, int n, float *k_out,
                       float *v_out, hipStream_t st);
+int vf_launch_kv_write(const vf_model *m, const SeqDesc &s, int layer, int t0, int n, const float *k_in,
+                       const float *v_in, hipStream_t st);
 int vf_launch_accept(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
                      const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y,
                      hipStream_t st);
 int vf_launch_attention_rows(const vf_model *m, const Batch &b, int layer, hipStream_t st);
 bool vf_fast_path_ok(const vf_model *m, int total_rows);
 int vf_run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, hipStream_t st);
+size_t vf_fused_workspace_bytes(const vf_config &c);
+int vf_fused_init(vf_model *m, char *ws, hipStream_t st);
+bool vf_fused_ok(const vf_model *m, const Batch &b);
+int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, hipStream_t st);
+int vf_fused_check(vf_model *m);
 int vf_launch_first_token(const vf_model *m, const SeqDesc &s, const float *logits_row, const float *u,
                           float temperature, hipStream_t st);

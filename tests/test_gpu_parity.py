@@ -89,6 +89,17 @@ def test_prefill_verify_accept_against_oracle(name):
         torch.cuda.synchronize()
         vf.vf_set_option(pair.model, vf.VF_OPT_FAST_PATH, 1)
         _check_logits(logits_gen.cpu().numpy(), z, tol, "verify rows, general kernels")
+        # and through the persistent whole-pass kernel instead of one kernel per GEMM
+        vf.vf_set_option(pair.model, vf.VF_OPT_PERSISTENT, 1)
+        logits_p = torch.empty_like(logits)
+        vf.vf_verify(pair.model, [seq], tokens, row_off, logits_gen)
+        vf.vf_verify(pair.model, [seq], tokens, row_off, logits_p)
+        torch.cuda.synchronize()
+        vf.vf_set_option(pair.model, vf.VF_OPT_PERSISTENT, 0)
+        _check_logits(logits_gen.cpu().numpy(), z, tol, "verify rows, persistent kernel")
+        assert torch.equal(logits_gen, logits_p), "persistent kernel is not bit-reproducible run to run"
+        vf.vf_seq_get_state(seq)                         # would report a grid barrier that gave up
+        print(f"persistent kernel vs one kernel per GEMM: {rel_inf(zg, logits_gen.cpu().numpy()).max():.3e}", flush=True)
         vf.vf_verify(pair.model, [seq], tokens, row_off, logits)
         torch.cuda.synchronize()
         assert np.array_equal(logits.cpu().numpy(), zg), "verify is not bit-reproducible run to run"
