@@ -119,8 +119,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--config", default="1.5b_k16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--per-gemm", action="store_true",
-                    help="one kernel per GEMM instead of the persistent whole-pass kernel")
+    ap.add_argument("--persistent", type=int, default=None,
+                    help="1: the persistent whole-pass kernel, 0: one kernel per GEMM (default: the library's default)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the yardstick for hardware byte counters")
     args = ap.parse_args()
@@ -141,8 +141,8 @@ def main():
     n_traj = max(K, W)
     cap = (cfg.ctx + (n_traj + 1) * m + 63) // 64 * 64
     model, wd = build_model(cfg, vf, wl, torch, max(cfg.chunk, m), cap)
-    if args.per_gemm:
-        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, 0)
+    if args.persistent is not None:
+        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, args.persistent)
     s = wl.streams(cfg)
     V = cfg.vocab
     stochastic = cfg.mode == "stochastic"

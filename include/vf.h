@@ -210,7 +210,7 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
  * the fused few-row kernels; 0 forces the general kernels (any row count), which compute the
  * same function. */
 #define VF_OPT_FAST_PATH 1
-/* VF_OPT_PERSISTENT (default 0): when the few-row kernels apply and the activations of the call fit
+/* VF_OPT_PERSISTENT (default 1): when the few-row kernels apply and the activations of the call fit
  * on-chip memory, vf_verify runs the whole forward pass as one persistent kernel whose phases are
  * separated by grid-wide barriers; 0 keeps one kernel per GEMM.  Same function, same rounding
  * points; sums are taken in a different (fixed) order.  The persistent kernel occupies the whole

@@ -89,6 +89,7 @@ size_t carve_model(vf_model *m, char *base) {
         size_t recs = R * c.n_q_heads * 16;
         const size_t few = (size_t)48 * c.n_q_heads * (((size_t)c.max_positions + 127) / 128);
         if (few > recs) recs = few;
+        m->attn_part_floats = recs * (hd + 4);
         m->attn_part = (float *)cv.take(recs * (hd + 4) * 4);
     }
     m->logits = (float *)cv.take(R * V * 4);
@@ -206,7 +207,7 @@ int vf_model_create(const vf_config *cfg, const vf_weights *w, void *packed_dev,
     m->cfg = *cfg;
     m->es = cfg->dtype == VF_BF16 ? 2 : 4;
     m->fast_path = 1;
-    m->persistent = 0;
+    m->persistent = 1;
     m->prof = new std::vector<vf_model::ProfRec>();
     m->prof_pool = new std::vector<hipEvent_t>();
     m->layers = new (std::nothrow) LayerPacked[cfg->n_layers];

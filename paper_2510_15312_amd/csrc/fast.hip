@@ -199,7 +199,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_fast_kernel(FastGemm g, Batch b)
                 if (EPI == EPI_SWIGLU) store_coherent(mine + (size_t)(NTH + t) * 4, v1[it]);
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        stores_done();
         __syncthreads();
         if (tid == 0) {
             const int old = __hip_atomic_fetch_add(g.counters + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

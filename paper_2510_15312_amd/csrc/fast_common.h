@@ -73,15 +73,26 @@ template <bool COH> __device__ inline void st_f32x4(float *p, floatx4 v) {
     }
 }
 __device__ inline void store_coherent(float *p, floatx4 v) { st_f32x4<true>(p, v); }
+// Waits until every store this wavefront has issued has completed at its scope.  A workgroup-scope
+// release fence does not: within a workgroup the memory pipeline keeps stores in order, so the
+// compiler emits no wait for it, and a signal to ANOTHER workgroup (a counter increment) could
+// then overtake the write-through stores it is meant to publish.
+__device__ inline void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+#ifndef VF_COH_LOAD_SCOPE
+#define VF_COH_LOAD_SCOPE __HIP_MEMORY_SCOPE_AGENT
+#endif
 __device__ inline floatx4 load_coherent(const float *p) {
     const unsigned long long *q = reinterpret_cast<const unsigned long long *>(p);
-    const unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, VF_COH_LOAD_SCOPE);
+    const unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, VF_COH_LOAD_SCOPE);
     const u32x2 lo = __builtin_bit_cast(u32x2, a), hi = __builtin_bit_cast(u32x2, b);
     return __builtin_bit_cast(floatx4, u32x4{lo[0], lo[1], hi[0], hi[1]});
 }
+__device__ inline u32x4 load_coherent16(const void *p) {
+    return __builtin_bit_cast(u32x4, load_coherent(reinterpret_cast<const float *>(p)));
+}
 __device__ inline float load_coherent1(const float *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, VF_COH_LOAD_SCOPE);
 }
 
 __device__ inline u32x2 pack4_bf16(float a, float b, float c, float d) {
@@ -101,7 +112,8 @@ __device__ inline void epi_resid(const FastGemm &g, int row, bool live, int nb, 
     const int n0 = nb * 16 + (lane >> 4) * 4;
     floatx4 hv = {0.f, 0.f, 0.f, 0.f};
     if (live) {
-        hv = *reinterpret_cast<const floatx4 *>(g.h_in + (size_t)row * g.N + n0) + v;
+        const float *hp = g.h_in + (size_t)row * g.N + n0;
+        hv = *reinterpret_cast<const floatx4 *>(hp) + v;  // a buffer other workgroups wrote in an earlier phase, never rewritten
         st_f32x4<COH>(g.h + (size_t)row * g.N + n0, hv);
     }
     float ssq = hv[0] * hv[0] + hv[1] * hv[1] + hv[2] * hv[2] + hv[3] * hv[3];

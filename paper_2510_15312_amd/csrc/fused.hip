@@ -22,12 +22,15 @@
 // order, so it follows the single-assignment rule as well.
 #include "fast_common.h"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int FW = 8;            // wavefronts per workgroup
 constexpr int FT = FW * 64;      // threads per workgroup
 constexpr int FROWS = 48;        // most rows of a call
 constexpr int BAR_GROUP = 16;    // workgroups per first-level barrier counter
+constexpr int ATT_COUNTERS = 4096;  // arrival counters of the attention blocks inside the barrier block (uints)
 constexpr int LDS_SMALL = 76 * 1024;   // dynamic LDS with which two workgroups fit one CU (static part included)
 constexpr int LDS_BIG = 152 * 1024;    // one workgroup per CU
 constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (seconds, not microseconds)
@@ -37,9 +40,31 @@ constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (s
 #ifndef FUSED_PREFETCH_EARLY
 #define FUSED_PREFETCH_EARLY 1   // first weight loads of a phase go out before the barrier wait
 #endif
+#ifndef FUSED_MAXP
+#define FUSED_MAXP 8              // most key parts per attention block (at most 8: the merge holds them all)
+#endif
 #ifndef FUSED_G
 #define FUSED_G 256
 #endif
+
+// Pointers that reach the kernel through memory lose their address space; loads through them would
+// be generic (flat) loads, which the compiler orders against every other load in flight.
+typedef const floatx4 __attribute__((address_space(1))) *global_f4_ptr;
+__device__ inline floatx4 load_global_f4(const float *p) { return *(global_f4_ptr)(p); }
+typedef const u32x4 __attribute__((address_space(1))) *global_w_ptr;
+
+// Loads from the single-assignment buffers (one version per phase and layer, written once per launch
+// before they are read): no cache can hold an older copy of such a line, so an ordinary load will do.
+#ifndef FUSED_SSA_PLAIN
+#define FUSED_SSA_PLAIN 1
+#endif
+__device__ __forceinline__ floatx4 ssa_load_f4(const float *p) {
+    return FUSED_SSA_PLAIN ? *reinterpret_cast<const floatx4 *>(p) : load_coherent(p);
+}
+__device__ __forceinline__ u32x4 ssa_load_16(const void *p) {
+    return FUSED_SSA_PLAIN ? *reinterpret_cast<const u32x4 *>(p) : load_coherent16(p);
+}
+__device__ __forceinline__ float ssa_load_f1(const float *p) { return FUSED_SSA_PLAIN ? *p : load_coherent1(p); }
 
 struct FusedLayer {
     const u32x4 *wqkv, *wo, *wgu, *wd;
@@ -55,16 +80,32 @@ struct FusedArgs {
     float *hv;        // residual stream, [2L+1][FROWS][d]
     float *ssv;       // sums of squares of its rows per 16 columns, [2L+1][d/16][64]
     bf16_t *qv, *ov, *av;  // per layer: q [FROWS][Hq*hd], attention output, SwiGLU product [FROWS][F]
-    float *attn_part, *part;
+    float *att_rec;   // attention records of the key parts, [L][FUSED_G][16][hd + 4]
+    float *part;
     int *counters;
     unsigned *bar, *fail;
     float *logits;
-    int n_layers, d, F, hq, hkv, hd, vocab, m, n_splits, has_bias;
+    int n_layers, d, F, hq, hkv, hd, vocab, m, has_bias;
+    int att_blocks, att_parts;  // (query block, kv head, sequence) blocks of the call; key parts per block
     float inv_d, eps, scale_log2e;
     unsigned root0;   // value of the barrier's root counter when this launch starts
     int ks_qkv, ks_o, ks_gu, ks_down;
     int lds_total;    // dynamic LDS bytes of this launch
 };
+
+// Workgroup barrier for data exchanged through LDS only.  Unlike __syncthreads() it does not wait
+// for this wavefront's global loads in flight (the weight fragments prefetched for later), only for
+// its LDS operations; the empty asm statements keep the compiler from moving memory accesses
+// across it.
+__device__ __forceinline__ void lds_sync() {
+#ifdef FUSED_SYNC_FULL
+    __syncthreads();
+    return;
+#endif
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
 
 // Two-level counting barrier, split into arrive and wait.  Counters only ever grow: every barrier
 // adds one to the root counter per group of BAR_GROUP workgroups, so barrier number e of a launch is
@@ -74,7 +115,7 @@ struct GridBar {
     unsigned target, ng;
     bool dead;
     __device__ __forceinline__ void arrive() {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this thread's stores have completed
+stores_done();  // this wavefront's write-through stores have reached memory
         __syncthreads();
         target += ng;
         if (threadIdx.x == 0) {
@@ -97,8 +138,14 @@ struct GridBar {
                     break;
                 }
             }
+#ifdef FUSED_POST_WAIT_SLEEP
+            for (int i = 0; i < FUSED_POST_WAIT_SLEEP; ++i) __builtin_amdgcn_s_sleep(127);
+#endif
         }
-        __syncthreads();
+        lds_sync();
+#ifdef FUSED_ACQ_AGENT
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#endif
     }
 };
 
@@ -134,6 +181,8 @@ struct FusedShared {
 // ---- embedding: row r by workgroup r ---------------------------------------------------------------
 __device__ __forceinline__ void embed_phase(const FusedArgs &a, const Batch &b) {
     const int d = a.d;
+    if (blockIdx.x == gridDim.x - 1)  // arrival counters of the attention blocks start at zero in every launch
+        for (int i = threadIdx.x; i < a.att_blocks; i += FT) st_u32<true>(a.bar + ATT_COUNTERS + i, 0u);
     for (int row = blockIdx.x; row < a.m; row += gridDim.x) {
         int tok = a.tokens[row];
         if (tok == VF_PENDING) tok = b.s[find_seq(b, row)].state[1];
@@ -189,25 +238,29 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
     floatx4 *red = reinterpret_cast<floatx4 *>(smem + lds_total - RED_BYTES);
     float *gain_s = reinterpret_cast<float *>(smem + lds_total - RED_BYTES);  // staging only: red is idle then
 
-    const u32x4 *wp[UB], *wpn[UB];
+    global_w_ptr wp[UB], wpn[UB];
     u32x4 w[PD][UB];
 #pragma unroll
     for (int d = 0; d < PD; ++d)
 #pragma unroll
         for (int u = 0; u < UB; ++u) w[d][u] = u32x4{0u, 0u, 0u, 0u};
-    auto unit_ptrs = [&](int it, const u32x4 *(&dst)[UB]) {
+    auto unit_ptrs = [&](int it, global_w_ptr (&dst)[UB]) {
         const int unit = (wg + it * G) / g.ks;
 #pragma unroll
-        for (int u = 0; u < UB; ++u) dst[u] = g.W + (size_t)min(unit * UB + u, NBt - 1) * KB * 64 + lane;
+        for (int u = 0; u < UB; ++u) dst[u] = (global_w_ptr)g.W + (size_t)min(unit * UB + u, NBt - 1) * KB * 64 + lane;
     };
-    auto frag = [&](const u32x4 *base, int kbl) { return load_stream(base + (size_t)min(wk0 + kbl, kb1 - 1) * 64); };
+    auto frag = [&](global_w_ptr base, int kbl) {
+        return __builtin_nontemporal_load(base + (size_t)min(wk0 + kbl, kb1 - 1) * 64);
+    };
+    // Loads are never predicated: a step past the end of the run reads the run's last fragment again
+    // (a cache hit) and its product is discarded.  Straight-line loads let the compiler wait for
+    // exactly the fragment it needs instead of for everything in flight.
     auto first_fragments = [&]() {
         unit_ptrs(0, wp);
 #pragma unroll
         for (int d = 0; d < PD; ++d)
-            if (d < cnt)
 #pragma unroll
-                for (int u = 0; u < UB; ++u) w[d][u] = frag(wp[u], d);
+            for (int u = 0; u < UB; ++u) w[d][u] = frag(wp[u], min(d, cnt - 1));
     };
     if (FUSED_PREFETCH_EARLY && n_my > 0) first_fragments();
     TRACE(1);
@@ -225,18 +278,18 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int j = wave + i * FW;
-            t[i] = (lane < m && j < g.n_ss) ? g.ss_in[j * 64 + lane] : 0.f;
+            // clamped index, then a multiply by 0 or 1: a select would be turned back into a branch
+            // around the load, and the loads would wait for one another
+            t[i] = ssa_load_f1(g.ss_in + min(j, g.n_ss - 1) * 64 + min(lane, m - 1)) * ((lane < m && j < g.n_ss) ? 1.f : 0.f);
         }
-        floatx4 gn = {0.f, 0.f, 0.f, 0.f};
-        if (tid < chunks) gn = *reinterpret_cast<const floatx4 *>(g.gain + (size_t)kb0 * 32 + tid * 4);
+        floatx4 gn = load_global_f4(g.gain + (size_t)kb0 * 32 + min(tid, chunks - 1) * 4);
         for (int base = 0; base < pieces; base += FT * XP) {
             floatx4 v[XP];
             int row = (base + tid) / chunks, c = (base + tid) % chunks;
             const int row0 = row, c0 = c;
 #pragma unroll
             for (int i = 0; i < XP; ++i) {
-                if (base + tid + i * FT < pieces)
-                    v[i] = *reinterpret_cast<const floatx4 *>(g.Xh + (size_t)row * KB * 32 + (size_t)kb0 * 32 + c * 4);
+                v[i] = ssa_load_f4(g.Xh + (size_t)min(row, m - 1) * KB * 32 + (size_t)kb0 * 32 + c * 4);
                 row += qstep;
                 c += rstep;
                 if (c >= chunks) { c -= chunks; ++row; }
@@ -247,13 +300,13 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sum += t[i];
                 if (lane < m)
-                    for (int j = wave + 16 * FW; j < g.n_ss; j += FW) sum += g.ss_in[j * 64 + lane];
+                    for (int j = wave + 16 * FW; j < g.n_ss; j += FW) sum += ssa_load_f1(g.ss_in + j * 64 + lane);
                 sh.rs_tmp[wave][lane] = sum;
                 for (int cc = tid; cc < chunks; cc += FT) {
-                    if (cc != tid) gn = *reinterpret_cast<const floatx4 *>(g.gain + (size_t)kb0 * 32 + cc * 4);
+                    if (cc != tid) gn = load_global_f4(g.gain + (size_t)kb0 * 32 + cc * 4);
                     *reinterpret_cast<floatx4 *>(gain_s + cc * 4) = gn;
                 }
-                __syncthreads();
+                lds_sync();
                 TRACE(6);
                 if (tid < 64) {
                     float tot = 0.f;
@@ -261,7 +314,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
                     for (int j = 0; j < FW; ++j) tot += sh.rs_tmp[j][tid];
                     sh.rs_s[tid] = 1.0f / sqrtf(tot * g.inv_d + g.eps);
                 }
-                __syncthreads();
+                lds_sync();
                 TRACE(7);
             }
             row = row0;
@@ -288,8 +341,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
             const int row0 = row, c0 = c;
 #pragma unroll
             for (int i = 0; i < XP; ++i) {
-                if (base + tid + i * FT < pieces)
-                    v[i] = *reinterpret_cast<const u32x4 *>(g.X + (size_t)row * KB * 32 + (size_t)kb0 * 32 + c * 8);
+                v[i] = ssa_load_16(g.X + (size_t)min(row, m - 1) * KB * 32 + (size_t)kb0 * 32 + c * 8);
                 row += qstep;
                 c += rstep;
                 if (c >= chunks) { c -= chunks; ++row; }
@@ -306,7 +358,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
             }
         }
     }
-    __syncthreads();
+    lds_sync();
     TRACE(3);
 
     int rowc[NB];
@@ -315,7 +367,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 
     for (int it = 0; it < n_my; ++it) {
         const bool has_next = it + 1 < n_my;
-        if (has_next) unit_ptrs(it + 1, wpn);
+        unit_ptrs(has_next ? it + 1 : it, wpn);
         const int unit = (wg + it * G) / g.ks;
         const int nb0 = unit * UB;
         floatx4 acc[UB][NB];
@@ -323,37 +375,41 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
         for (int u = 0; u < UB; ++u)
 #pragma unroll
             for (int c = 0; c < NB; ++c) acc[u][c] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-        for (int r = 0; r < rounds; ++r) {
+        // One round = PD steps of straight-line code.  REFILL: after its use every slot is loaded
+        // again, with the same item's next round or, in the last round, the next item's first; the
+        // final round of the final item has nothing left to load and runs without.
+        auto round_body = [&](auto refill_tag, int r) {
+            constexpr bool REFILL = decltype(refill_tag)::value;
             const bool last_round = r + 1 == rounds;
+            global_w_ptr rp[UB];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) rp[u] = last_round ? wpn[u] : wp[u];
+            const int rbase = last_round ? 0 : (r + 1) * PD;
 #pragma unroll
             for (int d = 0; d < PD; ++d) {
                 const int kbl = r * PD + d;
-                if (kbl < cnt) {  // the same for every wavefront
-                    const bool live = wk0 + kbl < kb1;
-                    bf16x8 a[UB];
+                const bool live = kbl < cnt && wk0 + kbl < kb1;
+                bf16x8 a[UB];
 #pragma unroll
-                    for (int u = 0; u < UB; ++u) a[u] = __builtin_bit_cast(bf16x8, live ? w[d][u] : u32x4{0u, 0u, 0u, 0u});
-                    if (!last_round) {
-                        if (kbl + PD < cnt)
+                for (int u = 0; u < UB; ++u) a[u] = __builtin_bit_cast(bf16x8, live ? w[d][u] : u32x4{0u, 0u, 0u, 0u});
+                if (REFILL) {
 #pragma unroll
-                            for (int u = 0; u < UB; ++u) w[d][u] = frag(wp[u], kbl + PD);
-                    } else if (has_next) {
-                        if (d < cnt)
+                    for (int u = 0; u < UB; ++u) w[d][u] = frag(rp[u], min(rbase + d, cnt - 1));
+                }
+                const int kx = min(wk0 + min(kbl, cnt - 1), kb1 - 1) - kb0;
 #pragma unroll
-                            for (int u = 0; u < UB; ++u) w[d][u] = frag(wpn[u], d);
-                    }
-                    const int kx = min(wk0 + kbl, kb1 - 1) - kb0;
+                for (int c = 0; c < NB; ++c) {
+                    const bf16x8 bb = __builtin_bit_cast(bf16x8, xs[(kx * m + rowc[c]) * 4 + (lane >> 4)]);
 #pragma unroll
-                    for (int c = 0; c < NB; ++c) {
-                        const bf16x8 bb = __builtin_bit_cast(bf16x8, xs[(kx * m + rowc[c]) * 4 + (lane >> 4)]);
-#pragma unroll
-                        for (int u = 0; u < UB; ++u)
-                            acc[u][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], bb, acc[u][c], 0, 0, 0);
-                    }
+                    for (int u = 0; u < UB; ++u)
+                        acc[u][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], bb, acc[u][c], 0, 0, 0);
                 }
             }
-        }
+        };
+#pragma unroll 1
+        for (int r = 0; r + 1 < rounds; ++r) round_body(std::true_type{}, r);
+        if (has_next) round_body(std::true_type{}, rounds - 1);
+        else round_body(std::false_type{}, rounds - 1);
         TRACE(4);
         // ---- wavefront partial sums: upper half through LDS into the lower half, then all four ----
         if (wave >= RW) {
@@ -362,7 +418,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 #pragma unroll
                 for (int c = 0; c < NB; ++c) red[(((wave - RW) * UB + u) * NB + c) * 64 + lane] = acc[u][c];
         }
-        __syncthreads();
+        lds_sync();
         if (wave < RW) {
 #pragma unroll
             for (int u = 0; u < UB; ++u)
@@ -372,7 +428,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
                     red[idx] = acc[u][c] + red[idx];
                 }
         }
-        __syncthreads();
+        lds_sync();
 
         constexpr int NT = UB * NB * 64;                       // tiles of 4 outputs per unit
         constexpr int NTH = EPI == EPI_SWIGLU ? NB * 64 : NT;  // tiles with an epilogue of their own
@@ -400,7 +456,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
                 store_coherent(mine + (size_t)t * 4, v0);
                 if (EPI == EPI_SWIGLU) store_coherent(mine + (size_t)(NTH + t) * 4, v1);
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            stores_done();
             __syncthreads();
             if (tid == 0) {
                 const int old = __hip_atomic_fetch_add(g.counters + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -447,192 +503,293 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
         }
         TRACE(5);
         if (has_next) {
-            __syncthreads();  // the partial sums in LDS are consumed before the next item's arrive
+            lds_sync();  // the partial sums in LDS are consumed before the next item's arrive
 #pragma unroll
             for (int u = 0; u < UB; ++u) wp[u] = wpn[u];
         }
     }
 }
 
-// ---- attention phase: work item = (key slice, kv head, sequence) ---------------------------------------
+// ---- attention phase -----------------------------------------------------------------------------------
+// Work item = (block of 16 query items, kv head, sequence, part of the keys); a query item is a
+// (row, head of the group) pair.  The eight wavefronts of a workgroup take the 32-key tiles of the
+// part in turn; K and V^T fragments go from the cache straight into registers in MFMA operand
+// order (no LDS staging: every fragment is used by exactly one wavefront).  Scores
+// S^T[key, item] = K Q^T leave the MFMA with eight keys per lane once the K rows are fed in the
+// order 8*(rho >> 2) + (rho & 3) (+ 4 for the second 16-key block): that is the B-operand layout
+// of O^T[d, item] += V^T[d, key] P[key, item], and the matching V^T fragment is one 16-byte load.
+// Wavefront results (running max, sum, O^T) are merged through LDS; with several parts the
+// merged partials go to memory and the last workgroup to arrive merges the parts.  No second
+// grid-wide phase is needed for the merge.
+constexpr int FKT = 32;  // keys per tile
+
+// (sequence, kv head, query block, key part) of attention work item i
+struct AttItem { int seq, kvh, qb, part, blk; };
+__device__ __forceinline__ AttItem att_item(const FusedArgs &a, const Batch &b, int i) {
+    const int group = a.hq / a.hkv;
+    AttItem it;
+    it.part = i / a.att_blocks;
+    it.blk = i % a.att_blocks;
+    int blk = it.blk, seq = 0;
+    while (seq + 1 < b.n_seqs) {
+        const int nb_seq = a.hkv * ((b.s[seq].nrows * group + 15) >> 4);
+        if (blk < nb_seq) break;
+        blk -= nb_seq;
+        ++seq;
+    }
+    const int nqb = (b.s[seq].nrows * group + 15) >> 4;
+    it.seq = seq;
+    it.kvh = blk / nqb;
+    it.qb = blk % nqb;
+    return it;
+}
+
+// len0: length of the sequence of this workgroup's first item, read once per launch (lengths do
+// not change during a launch).
 template <int HD>
-__device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, int layer, const bf16_t *q, GridBar &bar,
-                                  unsigned char *smem TRACE_ARG) {
-    constexpr int KD = HD / 32, DB = HD / 16, REC = HD + ATTF_STRIDE_PAD;
-    AttLds<HD> &L = *reinterpret_cast<AttLds<HD> *>(smem);
+__device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, int layer, const bf16_t *q, bf16_t *o,
+                                  int len0, GridBar &bar, unsigned char *smem, FusedShared &sh TRACE_ARG) {
+    constexpr int KD = HD / 32, DB = HD / 16, REC = HD + ATTF_STRIDE_PAD, MAXP = 8;
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     const int lane = tid & 63, wave = tid >> 6, g4 = lane >> 4, l15 = lane & 15;
-    const int G = gridDim.x, hq = a.hq, hkv = a.hkv, group = hq / hkv;
-    const int per_seq = a.n_splits * hkv;
-    const int items = per_seq * b.n_seqs;
-    AttStage<HD, FT> stage;
-    // keys below the sequence length were written by earlier calls: their loads may precede the barrier
+    const int G = gridDim.x, hq = a.hq, hkv = a.hkv, group = hq / hkv, P = a.att_parts;
+    floatx4 *o_s = reinterpret_cast<floatx4 *>(smem);                      // [wave][db][lane]
+    float *ml_s = reinterpret_cast<float *>(smem + FW * DB * 64 * 16);    // [wave][2][16]
+    const int n_work = a.att_blocks * P;
+    // K row fed to MFMA row rho of 16-key block h: key 8*(rho >> 2) + 4*h + (rho & 3)
+    const int krow = 8 * (l15 >> 2) + (l15 & 3);
+    bf16x8 kf[2][KD], vf[DB];
+    // coh: the tile holds keys written during this launch (by the QKV phase of this layer)
+    auto load_tile = [&](const SeqDesc &s, int kvh, int t, bool coh) {
+        const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);
+        const int t0 = t * FKT, page = kv_page(s, t0), tin = t0 % VF_TILE;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int kd = 0; kd < KD; ++kd) {
+                const bf16_t *kp = kv + kv_k_index(layer, s.n_pages, page, hkv, kvh, tin + krow + 4 * h, kd * 32 + g4 * 8, HD);
+                kf[h][kd] = coh ? __builtin_bit_cast(bf16x8, load_coherent16(kp)) : *reinterpret_cast<const bf16x8 *>(kp);
+            }
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+        {
+            const bf16_t *vp = kv + kv_v_index(layer, s.n_pages, page, hkv, kvh, tin + g4 * 8, db * 16 + l15, HD);
+            vf[db] = coh ? __builtin_bit_cast(bf16x8, load_coherent16(vp)) : *reinterpret_cast<const bf16x8 *>(vp);
+        }
+    };
+    auto tile_range = [&](const SeqDesc &s, const AttItem &it, int len, int &t_begin, int &t_end, int &kmax) {
+        kmax = min(len + s.nrows, s.capacity);  // keys 0..kmax-1 exist
+        const int blk_last = min(kmax - 1, len + min(s.nrows - 1, (it.qb * 16 + 15) / group));
+        const int tiles = blk_last / FKT + 1, tpp = (tiles + P - 1) / P;
+        t_begin = it.part * tpp;
+        t_end = min(tiles, t_begin + tpp);
+    };
+    // keys below the sequence length were written by earlier calls: a first tile made of them is
+    // loaded before the barrier wait
     bool preloaded = false;
-    if ((int)blockIdx.x < items) {
-        const int i = blockIdx.x;
-        const SeqDesc &s = b.s[i / per_seq];
-        const int split = i % a.n_splits, kvh = (i % per_seq) / a.n_splits;
-        const int len = s.state[0];
-        const int k_begin = split * ATT_KEYS;
-        if (k_begin + ATT_KEYS <= len) {
-            stage.load(s, layer, hkv, kvh, k_begin, len, tid);
+    if ((int)blockIdx.x < n_work) {
+        const AttItem it = att_item(a, b, blockIdx.x);
+        int t_begin, t_end, kmax;
+        tile_range(b.s[it.seq], it, len0, t_begin, t_end, kmax);
+        const int t = t_begin + wave;
+        if (t < t_end && (t + 1) * FKT <= len0) {
+            load_tile(b.s[it.seq], it.kvh, t, false);
             preloaded = true;
         }
     }
     TRACE(1);
     bar.wait();
     TRACE(2);
-    for (int i = blockIdx.x; i < items; i += G) {
-        const SeqDesc &s = b.s[i / per_seq];
-        const int split = i % a.n_splits, kvh = (i % per_seq) / a.n_splits;
+    for (int i = blockIdx.x; i < n_work; i += G) {
+        const AttItem it = att_item(a, b, i);
+        const SeqDesc &s = b.s[it.seq];
+        const int kvh = it.kvh, part = it.part;
         const int n_items = s.nrows * group;
-        const int len = s.state[0];
-        const int kmax = min(len + s.nrows, s.capacity);  // keys 0..kmax-1 exist
-        const int k_begin = split * ATT_KEYS;
-        if (k_begin >= kmax) continue;                    // the same for the whole workgroup
-        if (!preloaded) stage.load(s, layer, hkv, kvh, k_begin, kmax, tid);
-        const int nqb = (n_items + 15) >> 4;
-        // the first query block's fragments travel while the slice is written to LDS
-        bf16x8 qf[KD];
-        {
-            const int item = wave * 16 + l15;
-            const bool valid = wave < nqb && item < n_items;
-            const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
-#pragma unroll
-            for (int kd = 0; kd < KD; ++kd)
-                qf[kd] = *reinterpret_cast<const bf16x8 *>(q + ((size_t)(s.row0 + r) * hq + head) * HD + kd * 32 + g4 * 8);
-        }
-        if (i != (int)blockIdx.x) __syncthreads();  // previous slice consumed
-        stage.store(L, k_begin, preloaded ? len : kmax, tid);
-        preloaded = false;
-        __syncthreads();
-        for (int qb = wave; qb < nqb; qb += FW) {
-            const int item = qb * 16 + l15;
-            const bool valid = item < n_items;
-            const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
-            const int row = s.row0 + r;
-            const int last_key = valid ? len + r : -1;
-            const int blk_last = len + min(s.nrows - 1, (qb * 16 + 15) / group);
-            if (qb != wave) {
-#pragma unroll
-                for (int kd = 0; kd < KD; ++kd)
-                    qf[kd] = *reinterpret_cast<const bf16x8 *>(q + ((size_t)row * hq + head) * HD + kd * 32 + g4 * 8);
-            }
-            AttState<HD> st;
-#pragma unroll
-            for (int db = 0; db < DB; ++db) st.o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
-            st.m_run = -1e30f;
-            st.l_run = 0.f;
-            att_slice<HD>(st, qf, L, k_begin, last_key, blk_last, a.scale_log2e, lane);
-            if (valid) {
-                float *out = a.attn_part + (((size_t)row * hq + head) * a.n_splits + split) * REC;
-                if (g4 == 0) st_u32x2<true>(out, __builtin_bit_cast(u32x2, float2{st.m_run, st.l_run}));
-#pragma unroll
-                for (int db = 0; db < DB; ++db) st_f32x4<true>(out + ATTF_STRIDE_PAD + db * 16 + g4 * 4, st.o[db]);
-            }
-        }
-    }
-}
+        const int len = i == (int)blockIdx.x ? len0 : s.state[0];
+        int t_begin, t_end, kmax;
+        tile_range(s, it, len, t_begin, t_end, kmax);
+        const int item = it.qb * 16 + l15;
+        const bool valid = item < n_items;
+        const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
+        const int row = s.row0 + r;
+        const int last_key = valid ? len + r : -1;
 
-// ---- merge of the key slices by log-sum-exp: one wavefront per (row, head) ------------------------------
-template <int HD>
-__device__ __forceinline__ void combine_phase(const FusedArgs &a, const Batch &b, bf16_t *o) {
-    constexpr int REC = HD + ATTF_STRIDE_PAD, DPL = HD / 64;  // d values per lane
-    int tid = threadIdx.x;
-    asm volatile("" : "+v"(tid));
-    const int lane = tid & 63, wave = tid >> 6;
-    const int G = gridDim.x, hq = a.hq, n_splits = a.n_splits;
-    const int n_items = a.m * hq;
-    for (int i = blockIdx.x + G * wave; i < n_items; i += G * FW) {
-        const int row = i / hq, head = i % hq;
-        const SeqDesc &s = b.s[find_seq(b, row)];
-        const int kmax = min(s.state[0] + s.nrows, s.capacity);
-        const int used = min(n_splits, (kmax + ATT_KEYS - 1) / ATT_KEYS);  // slices that had keys
-        const float *p = a.attn_part + ((size_t)row * hq + head) * n_splits * REC;
-        // slice maxima and sums: lane j holds slices j and j + 64
-        float mv[2], lv[2];
+        bf16x8 qf[KD];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int j = lane + h * 64;
-            mv[h] = -1e30f;
-            lv[h] = 0.f;
-            if (j < used) {
-                const unsigned long long raw = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p + (size_t)j * REC),
-                                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const float2 ml = __builtin_bit_cast(float2, raw);
-                mv[h] = ml.x;
-                lv[h] = ml.y;
+        for (int kd = 0; kd < KD; ++kd)
+            qf[kd] = __builtin_bit_cast(bf16x8, ssa_load_16(q + ((size_t)row * hq + head) * HD + kd * 32 + g4 * 8));
+        AttState<HD> st;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) st.o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
+        st.m_run = -1e30f;
+        st.l_run = 0.f;
+#pragma unroll 1
+        for (int t = t_begin + wave; t < t_end; t += FW) {
+            const int t0 = t * FKT;
+            if (!preloaded) load_tile(s, kvh, t, (t + 1) * FKT > len);
+            preloaded = false;
+            floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kd = 0; kd < KD; ++kd) {
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][kd], qf[kd], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][kd], qf[kd], s1, 0, 0, 0);
+            }
+            // lane holds keys t0 + 8*g4 + j (s0) and t0 + 8*g4 + 4 + j (s1) of item l15
+            float p[8], tmax = -1e30f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                p[j] = (t0 + g4 * 8 + j <= last_key) ? s0[j] * a.scale_log2e : -1e30f;
+                p[4 + j] = (t0 + g4 * 8 + 4 + j <= last_key) ? s1[j] * a.scale_log2e : -1e30f;
+                tmax = fmaxf(tmax, fmaxf(p[j], p[4 + j]));
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float m_new = fmaxf(st.m_run, tmax);
+            const float corr = exp2f(st.m_run - m_new);
+            float psum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                p[j] = (t0 + g4 * 8 + j <= last_key) ? exp2f(p[j] - m_new) : 0.f;
+                psum += p[j];
+            }
+            psum += __shfl_xor(psum, 16, 64);
+            psum += __shfl_xor(psum, 32, 64);
+            st.l_run = st.l_run * corr + psum;
+            st.m_run = m_new;
+            // probabilities as a sum of two bfloat16 values (16 significant bits): the P * V
+            // product then carries no more rounding than its bfloat16 V operand
+            bf16x8 pf, pl;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                pf[j] = (bf16_t)p[j];
+                pl[j] = (bf16_t)(p[j] - (float)pf[j]);
+            }
+            // rows of the cache past the last key may hold anything: keep them out of the product
+            if (t0 + FKT > kmax) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (t0 + g4 * 8 + j >= kmax) vf[db][j] = (bf16_t)0.f;
+            }
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                st.o[db] = st.o[db] * corr;
+                st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pf, st.o[db], 0, 0, 0);
+                st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pl, st.o[db], 0, 0, 0);
             }
         }
-        float M = fmaxf(mv[0], mv[1]);
+        preloaded = false;
+        TRACE(20);
+        // ---- merge of the eight wavefronts through LDS ----
+        if (i != (int)blockIdx.x) lds_sync();  // the previous item's merge has been read
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
-        float wv[2];
+        for (int db = 0; db < DB; ++db) o_s[(wave * DB + db) * 64 + lane] = st.o[db];
+        if (g4 == 0) {
+            ml_s[(wave * 2 + 0) * 16 + l15] = st.m_run;
+            ml_s[(wave * 2 + 1) * 16 + l15] = st.l_run;
+        }
+        lds_sync();
+        // thread (db = wave, lane) owns O^T[d = 16*db + 4*g4 + j][item l15]; HD = 64 leaves waves 4..7 idle
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        float M = -1e30f, L = 0.f;
+        if (wave < DB) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) wv[h] = (lane + h * 64 < used) ? exp2f(mv[h] - M) : 0.f;
-        float Lsum = 0.f, acc[DPL];
+            for (int w = 0; w < FW; ++w) M = fmaxf(M, ml_s[(w * 2) * 16 + l15]);
 #pragma unroll
-        for (int j = 0; j < DPL; ++j) acc[j] = 0.f;
-        for (int j0 = 0; j0 < used; j0 += 8) {
-            float t[8][DPL], wj[8];
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) {
-                const int j = j0 + jj;
-                const int src = j & 63;
-                const float wlo = __shfl(wv[0], src, 64), whi = __shfl(wv[1], src, 64);
-                const float llo = __shfl(lv[0], src, 64), lhi = __shfl(lv[1], src, 64);
-                wj[jj] = j < used ? (j < 64 ? wlo : whi) : 0.f;
-                const float lj = j < used ? (j < 64 ? llo : lhi) : 0.f;
-                Lsum += lj * wj[jj];
-#pragma unroll
-                for (int e = 0; e < DPL; ++e) t[jj][e] = 0.f;
-                if (j < used) {
-                    const float *src_p = p + (size_t)j * REC + ATTF_STRIDE_PAD + lane * DPL;
-                    if (DPL == 2) {
-                        const unsigned long long raw = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(src_p),
-                                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        const float2 v = __builtin_bit_cast(float2, raw);
-                        t[jj][0] = v.x;
-                        t[jj][DPL - 1] = v.y;
-                    } else {
-                        t[jj][0] = load_coherent1(src_p);
+            for (int w = 0; w < FW; ++w) {
+                const float wt = exp2f(ml_s[(w * 2) * 16 + l15] - M);
+                L += ml_s[(w * 2 + 1) * 16 + l15] * wt;
+                acc += o_s[(w * DB + wave) * 64 + lane] * wt;
+            }
+        }
+        TRACE(21);
+        if (P > 1) {
+            // Merge across the parts of the block without a second grid-wide phase: every part
+            // leaves its record in memory and counts itself in; once all P have (all of them are
+            // resident and none has other work left, so the wait ends), part p merges the d-blocks
+            // p, p + P, ... of all records -- wavefront w takes d-block p + w * P -- and writes
+            // that slice of the output.
+            float *base = a.att_rec + ((size_t)layer * FUSED_G + (size_t)it.blk * P) * 16 * REC;
+            float *mine = base + (size_t)part * 16 * REC;
+            if (wave < DB) {
+                if (wave == 0 && g4 == 0) st_u32x2<true>(mine + l15 * REC, __builtin_bit_cast(u32x2, float2{M, L}));
+                st_f32x4<true>(mine + l15 * REC + ATTF_STRIDE_PAD + wave * 16 + g4 * 4, acc);
+            }
+            stores_done();
+            __syncthreads();
+            if (tid == 0) {
+                unsigned *cnt = a.bar + ATT_COUNTERS + it.blk;
+                __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned want = (unsigned)P * (unsigned)(layer + 1);
+                long long spins = 0;
+                while (!bar.dead && __hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
+                    __builtin_amdgcn_s_sleep(1);
+                    if (++spins > SPIN_LIMIT) {
+                        __hip_atomic_store(a.fail, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        bar.dead = true;
                     }
                 }
             }
+            lds_sync();
+            TRACE(22);
+            const int db = part + wave * P;
+            if (db < DB) {
+                // all records in flight at once (slots past P repeat the last part and weigh nothing);
+                // the records of a layer have a buffer of their own, so ordinary loads see them
+                float mp[MAXP], lp[MAXP];
+                floatx4 op[MAXP];
 #pragma unroll
-            for (int jj = 0; jj < 8; ++jj)
+                for (int pp = 0; pp < MAXP; ++pp) {
+                    const float *rec = base + ((size_t)min(pp, P - 1) * 16 + l15) * REC;
+                    const floatx4 hd4 = ssa_load_f4(rec);  // [max, sum, -, -]
+                    mp[pp] = hd4[0];
+                    lp[pp] = hd4[1];
+                    op[pp] = ssa_load_f4(rec + ATTF_STRIDE_PAD + db * 16 + g4 * 4);
+                }
+                float Mg = -1e30f;
 #pragma unroll
-                for (int e = 0; e < DPL; ++e) acc[e] += t[jj][e] * wj[jj];
-        }
-        bf16_t *dst = o + (size_t)row * hq * HD + head * HD + lane * DPL;
-        if (DPL == 2) {
-            st_u32<true>(dst, pack2_bf16(acc[0] / Lsum, acc[DPL - 1] / Lsum));
-        } else {
-            const bf16_t x = (bf16_t)(acc[0] / Lsum);
-            st_u16<true>(dst, __builtin_bit_cast(unsigned short, x));
+                for (int pp = 0; pp < MAXP; ++pp) Mg = fmaxf(Mg, mp[pp]);
+                float Lg = 0.f;
+                floatx4 og = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int pp = 0; pp < MAXP; ++pp) {
+                    const float wt = pp < P ? exp2f(mp[pp] - Mg) : 0.f;
+                    Lg += lp[pp] * wt;
+                    og += op[pp] * wt;
+                }
+                if (valid) {
+                    const float inv = 1.0f / Lg;
+                    st_u32x2<true>(o + (size_t)row * hq * HD + head * HD + db * 16 + g4 * 4,
+                                   pack4_bf16(og[0] * inv, og[1] * inv, og[2] * inv, og[3] * inv));
+                }
+            }
+        } else if (wave < DB && valid) {
+            const float inv = 1.0f / L;
+            st_u32x2<true>(o + (size_t)row * hq * HD + head * HD + wave * 16 + g4 * 4,
+                           pack4_bf16(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv));
         }
     }
 }
 
-template <int NB, int HD>
 #ifndef FUSED_MINW
 #define FUSED_MINW 2
 #endif
+template <int NB, int HD>
 __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs a, Batch b) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ FusedShared sh;
     GridBar bar{a.bar, a.fail, a.root0, gridDim.x / BAR_GROUP, false};
     const int d = a.d, F = a.F, hd = a.hd, nq = a.hq * hd, nkv = a.hkv * hd;
-#ifdef FUSED_ALIAS_PROBE
-    const size_t hstride = 0, sstride = 0;
-#else
     const size_t hstride = (size_t)FROWS * d, sstride = (size_t)(d / 16) * 64;
-#endif
 
 #ifdef FUSED_TRACE
     Trace trace{reinterpret_cast<unsigned long long *>(a.bar + 8192), 0};
 #endif
+    // length of the sequence of this workgroup's first attention item (lengths are constant during a launch)
+    int len0 = 0;
+    if ((int)blockIdx.x < a.att_blocks * a.att_parts) len0 = b.s[att_item(a, b, blockIdx.x).seq].state[0];
     TRACE(0);
     embed_phase(a, b);
     bar.arrive();
@@ -671,12 +828,7 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
         }
         bar.arrive();
         TRACE(10);
-        attn_phase<HD>(a, b, l, q, bar, smem TRACE_PASS);
-        bar.arrive();
-        TRACE(11);
-        bar.wait();
-        TRACE(12);
-        combine_phase<HD>(a, b, o);
+        attn_phase<HD>(a, b, l, q, o, len0, bar, smem, sh TRACE_PASS);
         bar.arrive();
         TRACE(13);
         {
@@ -776,6 +928,7 @@ size_t vf_fused_workspace_bytes(const vf_config &c) {
     add(L * FROWS * nq * 2);
     add(L * FROWS * nq * 2);
     add(L * FROWS * F * 2);
+    add(L * FUSED_G * 16 * ((size_t)c.head_dim + ATTF_STRIDE_PAD) * 4);
     add(65536);
     add(L * sizeof(FusedLayer));
     return n;
@@ -791,6 +944,7 @@ int vf_fused_init(vf_model *m, char *ws, hipStream_t st) {
     m->fz_q = take(L * FROWS * nq * 2);
     m->fz_o = take(L * FROWS * nq * 2);
     m->fz_a = take(L * FROWS * F * 2);
+    m->fz_att = (float *)take(L * FUSED_G * 16 * ((size_t)c.head_dim + ATTF_STRIDE_PAD) * 4);
     m->fz_bar = (unsigned *)take(65536);
     m->fz_layers = take(L * sizeof(FusedLayer));
     std::vector<FusedLayer> host(L);
@@ -851,8 +1005,15 @@ int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logi
     if (!plan_fused(m, b, a, &G)) return vf_fail(VF_ERR_UNSUPPORTED, "persistent kernel does not apply to this call");
     int max_keys = 0;
     for (int i = 0; i < b.n_seqs; ++i) max_keys = std::max(max_keys, b.s[i].len_ub + b.s[i].nrows);
-    const int n_splits = (max_keys + ATT_KEYS - 1) / ATT_KEYS;
-    if (n_splits > VF_ATTN_SPLIT_MAX) return vf_fail(VF_ERR_UNSUPPORTED, "context of %d keys", max_keys);
+    // attention: blocks of 16 query items per (sequence, kv head); as many key parts per block as
+    // fill the grid, but no more than give every wavefront of a part a tile of its own
+    const int group = c.n_q_heads / c.n_kv_heads;
+    int blocks = 0;
+    for (int i = 0; i < b.n_seqs; ++i) blocks += c.n_kv_heads * ((b.s[i].nrows * group + 15) / 16);
+    int parts = std::max(1, std::min(G / std::max(1, blocks), ((max_keys + FKT - 1) / FKT + FW - 1) / FW));
+    parts = std::min(parts, FUSED_MAXP);
+    if (blocks > VF_N_COUNTERS) return vf_fail(VF_ERR_UNSUPPORTED, "%d attention blocks", blocks);
+    if (blocks * parts > FUSED_G) parts = 1;  // records have room for one per workgroup
     a.layers = (const FusedLayer *)m->fz_layers;
     a.embed = (const bf16_t *)m->embed;
     a.lm_head = (const u32x4 *)m->lm_head;
@@ -865,7 +1026,7 @@ int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logi
     a.qv = (bf16_t *)m->fz_q;
     a.ov = (bf16_t *)m->fz_o;
     a.av = (bf16_t *)m->fz_a;
-    a.attn_part = m->attn_part;
+    a.att_rec = m->fz_att;
     a.part = m->part;
     a.counters = m->counters;
     a.bar = m->fz_bar;
@@ -879,13 +1040,14 @@ int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logi
     a.hd = c.head_dim;
     a.vocab = c.vocab;
     a.m = b.total_rows;
-    a.n_splits = n_splits;
+    a.att_blocks = blocks;
+    a.att_parts = parts;
     a.has_bias = c.qkv_bias;
     a.inv_d = 1.0f / (float)c.d_model;
     a.eps = c.rms_eps;
     a.scale_log2e = 1.4426950408889634f / sqrtf((float)c.head_dim);
     a.root0 = m->fz_epoch;
-    m->fz_epoch += (1u + 6u * (unsigned)c.n_layers) * (unsigned)(G / BAR_GROUP);  // barriers per launch x groups
+    m->fz_epoch += (1u + 5u * (unsigned)c.n_layers) * (unsigned)(G / BAR_GROUP);  // barriers per launch x groups
     const int rows = b.total_rows;
     ProfScope ps(m, VF_SITE_STEP, st);
     if (c.head_dim == 128) {

@@ -74,6 +74,7 @@ struct vf_model {
     float *part;                // split-K partial sums
     size_t part_floats;
     float *attn_part;           // [R*Hq, 16, hd+4]
+    size_t attn_part_floats;
     float *logits;              // [R, V]
     float *stat_max;            // [R, VF_STAT_CHUNKS]
     int32_t *stat_idx;          // [R, VF_STAT_CHUNKS]
@@ -86,7 +87,7 @@ struct vf_model {
     int fast_path;              // option: use the few-row kernels when they apply
     int persistent;             // option: use the persistent whole-pass kernel when it applies
     // persistent kernel: single-assignment activation buffers, barrier counters, layer table
-    float *fz_h, *fz_ss;
+    float *fz_h, *fz_ss, *fz_att;
     void *fz_q, *fz_o, *fz_a, *fz_layers;
     unsigned *fz_bar;
     char *fz_ws;                // their workspace

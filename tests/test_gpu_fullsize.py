@@ -124,14 +124,14 @@ def test_config3_full_size_stochastic_steps():
         tokens = i32(np.concatenate([[pending], drafts]))
         logits = torch.empty((m, cfg.vocab), dtype=torch.float32, device=DEV)
         vf.vf_seq_set_len(seq, ln)                       # teacher forcing: the oracle's state
-        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, 1)  # the same rows through the persistent kernel
+        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, 1)  # first through the persistent kernel (the default)
         vf.vf_verify(model, [seq], tokens, [0, m], logits)
         torch.cuda.synchronize()
         errs_p = rel_inf(logits.cpu().numpy(), z)
         print(f"1.5b full size: step {step} persistent kernel: row errors mean {errs_p.mean():.3e} max {errs_p.max():.3e}",
               flush=True)
         worst = max(worst, errs_p.max())
-        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, 0)
+        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, 0)  # then one kernel per GEMM; acceptance runs on these logits
         vf.vf_verify(model, [seq], tokens, [0, m], logits)
         torch.cuda.synchronize()
         zg = logits.cpu().numpy()
