@@ -31,8 +31,7 @@ constexpr int FT = FW * 64;      // threads per workgroup
 constexpr int FROWS = 48;        // most rows of a call
 constexpr int BAR_GROUP = 16;    // workgroups per first-level barrier counter
 constexpr int ATT_COUNTERS = 4096;  // arrival counters of the attention blocks inside the barrier block (uints)
-constexpr int LDS_SMALL = 76 * 1024;   // dynamic LDS with which two workgroups fit one CU (static part included)
-constexpr int LDS_BIG = 152 * 1024;    // one workgroup per CU
+constexpr int LDS_BYTES = 152 * 1024;  // dynamic LDS of the one workgroup a CU holds (160 KB less the static part)
 constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (seconds, not microseconds)
 
 // One workgroup of 8 wavefronts per CU: two wavefronts per SIMD, so each may use up to 256 vector
@@ -824,7 +823,7 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
             g.W = lp.wqkv; g.N = nq + 2 * nkv; g.KB = d / 32; g.Xh = h0; g.gain = lp.attn_norm; g.ss_in = ss0;
             g.bias = a.has_bias ? lp.bqkv : nullptr; g.layer = l; g.q = q;
             g.ks = a.ks_qkv; g.kbps = (g.KB + g.ks - 1) / g.ks;
-            gemm_phase<NB, 1, 8, EPI_QKV>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+            gemm_phase<NB, 1, 6, EPI_QKV>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
         }
         bar.arrive();
         TRACE(10);
@@ -835,7 +834,7 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
             FastGemm g = base;
             g.W = lp.wo; g.N = d; g.KB = nq / 32; g.X = o; g.h_in = h0; g.h = h1; g.ss_out = ss1;
             g.ks = a.ks_o; g.kbps = (g.KB + g.ks - 1) / g.ks;
-            gemm_phase<NB, 1, 8, EPI_RESID>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+            gemm_phase<NB, 1, 6, EPI_RESID>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
         }
         bar.arrive();
         TRACE(14);
@@ -851,7 +850,7 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
             FastGemm g = base;
             g.W = lp.wd; g.N = d; g.KB = F / 32; g.X = act; g.h_in = h1; g.h = h2; g.ss_out = ss2;
             g.ks = a.ks_down; g.kbps = (g.KB + g.ks - 1) / g.ks;
-            gemm_phase<NB, 2, 6, EPI_RESID>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+            gemm_phase<NB, 2, 5, EPI_RESID>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
         }
         bar.arrive();
         TRACE(16);
@@ -895,22 +894,19 @@ int pick_split(int G, int lds_total, int units, int KB, int rows, int nb, bool a
 template <int NB, int HD>
 int launch_fused(vf_model *m, FusedArgs &a, const Batch &b, int G, hipStream_t st) {
     auto kern = verify_fused_kernel<NB, HD>;
-    static int max_wgs[2] = {-1, -1};  // resident workgroups with LDS_SMALL / LDS_BIG
-    const int which = a.lds_total == LDS_BIG;
-    if (max_wgs[which] < 0) {
+    static int max_wgs = -1;  // workgroups that can be resident at once
+    if (max_wgs < 0) {
         VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   LDS_BIG));
+                                   LDS_BYTES));
         int per_cu = 0, dev = 0;
         hipDeviceProp_t prop;
         VF_HIP(hipGetDevice(&dev));
         VF_HIP(hipGetDeviceProperties(&prop, dev));
-        VF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kern), FT,
-                                                            a.lds_total));
-        max_wgs[which] = per_cu * prop.multiProcessorCount;
+        VF_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kern), FT, LDS_BYTES));
+        max_wgs = per_cu * prop.multiProcessorCount;
     }
-    if (G > max_wgs[which])
-        return vf_fail(VF_ERR_UNSUPPORTED, "persistent kernel: %d workgroups wanted, %d can be resident", G,
-                       max_wgs[which]);
+    if (G > max_wgs)
+        return vf_fail(VF_ERR_UNSUPPORTED, "persistent kernel: %d workgroups wanted, %d can be resident", G, max_wgs);
     hipLaunchKernelGGL(kern, dim3(G), dim3(FT), a.lds_total, st, a, b);
     VF_LAUNCH_CHECK("verify_fused");
     return VF_OK;
@@ -966,29 +962,26 @@ static bool plan_fused(const vf_model *m, const Batch &b, FusedArgs &a, int *G_o
     const int rows = b.total_rows, nb = (rows + 15) / 16;
     const int d = c.d_model, F = c.d_ffn, hd = c.head_dim, nq = c.n_q_heads * hd, nkv = c.n_kv_heads * hd;
     if (std::max((nq + 2 * nkv) / 16, F / 16) > VF_N_COUNTERS) return false;
-    for (int big = 0; big < 2; ++big) {
-        const int G = big ? 256 : FUSED_G, lds = big ? LDS_BIG : LDS_SMALL;
-        if (G % BAR_GROUP) continue;
-        a.ks_qkv = pick_split(G, lds, (nq + 2 * nkv) / 16, d / 32, rows, nb, false);
-        a.ks_o = pick_split(G, lds, d / 16, nq / 32, rows, nb, false);
-        a.ks_gu = pick_split(G, lds, F / 16, d / 32, rows, nb, false);
-        a.ks_down = pick_split(G, lds, (d / 16 + 1) / 2, F / 32, rows, nb, true);
-        const int ks_head = pick_split(G, lds, (c.vocab / 16 + 1) / 2, d / 32, rows, nb, false);
-        if (!a.ks_qkv || !a.ks_o || !a.ks_gu || !a.ks_down || ks_head != 1) continue;
-        // the gain slice of a normalising phase is staged where the partial sums go later
-        const int red_bytes = (FW / 2) * 2 * nb * 1024;
-        if ((d / 32 + a.ks_gu - 1) / a.ks_gu * 128 > red_bytes || (d / 32 + a.ks_qkv - 1) / a.ks_qkv * 128 > red_bytes ||
-            d / 32 * 128 > red_bytes)
-            continue;
-        // partial tiles of the split phases: units * ks tiles of UB * NB * 256 floats
-        const size_t tiles = std::max(std::max((nq + 2 * nkv) / 16 * a.ks_qkv, d / 16 * a.ks_o),
-                                      std::max(F / 16 * a.ks_gu, (d / 16 + 1) / 2 * a.ks_down));
-        if (tiles * 2 * nb * 256 > m->part_floats) continue;
-        a.lds_total = lds;
-        *G_out = G;
-        return true;
-    }
-    return false;
+    const int G = FUSED_G, lds = LDS_BYTES;
+    if (G % BAR_GROUP) return false;
+    a.ks_qkv = pick_split(G, lds, (nq + 2 * nkv) / 16, d / 32, rows, nb, false);
+    a.ks_o = pick_split(G, lds, d / 16, nq / 32, rows, nb, false);
+    a.ks_gu = pick_split(G, lds, F / 16, d / 32, rows, nb, false);
+    a.ks_down = pick_split(G, lds, (d / 16 + 1) / 2, F / 32, rows, nb, true);
+    const int ks_head = pick_split(G, lds, (c.vocab / 16 + 1) / 2, d / 32, rows, nb, false);
+    if (!a.ks_qkv || !a.ks_o || !a.ks_gu || !a.ks_down || ks_head != 1) return false;
+    // the gain slice of a normalising phase is staged where the partial sums go later
+    const int red_bytes = (FW / 2) * 2 * nb * 1024;
+    if ((d / 32 + a.ks_gu - 1) / a.ks_gu * 128 > red_bytes || (d / 32 + a.ks_qkv - 1) / a.ks_qkv * 128 > red_bytes ||
+        d / 32 * 128 > red_bytes)
+        return false;
+    // partial tiles of the split phases: units * ks tiles of UB * NB * 256 floats
+    const size_t tiles = std::max(std::max((nq + 2 * nkv) / 16 * a.ks_qkv, d / 16 * a.ks_o),
+                                  std::max(F / 16 * a.ks_gu, (d / 16 + 1) / 2 * a.ks_down));
+    if (tiles * 2 * nb * 256 > m->part_floats) return false;
+    a.lds_total = lds;
+    *G_out = G;
+    return true;
 }
 
 bool vf_fused_ok(const vf_model *m, const Batch &b) {
