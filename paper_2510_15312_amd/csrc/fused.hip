@@ -29,7 +29,9 @@ namespace {
 constexpr int FW = 8;            // wavefronts per workgroup
 constexpr int FT = FW * 64;      // threads per workgroup
 constexpr int FROWS = 48;        // most rows of a call
-constexpr int BAR_GROUP = 16;    // workgroups per first-level barrier counter
+#ifndef BAR_COUNTERS
+#define BAR_COUNTERS 32           // counters a barrier's arrivals are spread over
+#endif
 constexpr int ATT_COUNTERS = 4096;  // arrival counters of the attention blocks inside the barrier block (uints)
 constexpr int LDS_BYTES = 152 * 1024;  // dynamic LDS of the one workgroup a CU holds (160 KB less the static part)
 constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (seconds, not microseconds)
@@ -38,6 +40,9 @@ constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (s
 // registers (weight ring + staging loads in flight) without spilling.
 #ifndef FUSED_PREFETCH_EARLY
 #define FUSED_PREFETCH_EARLY 1   // first weight loads of a phase go out before the barrier wait
+#endif
+#ifndef FUSED_PD_DOWN
+#define FUSED_PD_DOWN 5            // ring depth of the down projection (nine fragments per wavefront at the 1.5B shape)
 #endif
 #ifndef FUSED_MAXP
 #define FUSED_MAXP 8              // most key parts per attention block (at most 8: the merge holds them all)
@@ -86,6 +91,10 @@ struct FusedArgs {
     float *logits;
     int n_layers, d, F, hq, hkv, hd, vocab, m, has_bias;
     int att_blocks, att_parts;  // (query block, kv head, sequence) blocks of the call; key parts per block
+    // First attention work item of every workgroup (-1: none).  Workgroup w runs on compute die w % 8;
+    // the map puts the query blocks that read the same keys (same sequence, kv head and key part) on one
+    // die, so that its L2 serves all but the first of those reads.
+    short att_first[FUSED_G];
     float inv_d, eps, scale_log2e;
     unsigned root0;   // value of the barrier's root counter when this launch starts
     int ks_qkv, ks_o, ks_gu, ks_down;
@@ -106,28 +115,31 @@ __device__ __forceinline__ void lds_sync() {
     asm volatile("" ::: "memory");
 }
 
-// Two-level counting barrier, split into arrive and wait.  Counters only ever grow: every barrier
-// adds one to the root counter per group of BAR_GROUP workgroups, so barrier number e of a launch is
-// complete when the root counter reaches its value at launch start + e * groups.
+// Counting barrier, split into arrive and wait.  The workgroups are spread over BAR_COUNTERS counters
+// (each in a memory channel of its own, so that the increments of a barrier are not all serialised
+// at one address); an arrival is one increment that returns nothing, and a barrier is complete when
+// every counter has grown by the number of workgroups mapped to it.  Counters only ever grow:
+// barrier number e of a launch waits for the counters' value at launch start + e * (G / BAR_COUNTERS).
+// Lanes 0..BAR_COUNTERS-1 of the first wavefront poll one counter each.
 struct GridBar {
     unsigned *mem, *fail;
-    unsigned target, ng;
+    unsigned target, per;  // per: workgroups per counter
     bool dead;
     __device__ __forceinline__ void arrive() {
-stores_done();  // this wavefront's write-through stores have reached memory
+        stores_done();  // this wavefront's write-through stores have reached memory
         __syncthreads();
-        target += ng;
-        if (threadIdx.x == 0) {
-            unsigned *gc = mem + 64 + (blockIdx.x % ng) * 64;
-            const unsigned old = __hip_atomic_fetch_add(gc, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (((old + 1u) & (BAR_GROUP - 1)) == 0u)
-                __hip_atomic_fetch_add(mem, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        target += per;
+        if (threadIdx.x == 0)
+            __hip_atomic_fetch_add(mem + (blockIdx.x % BAR_COUNTERS) * 64, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __device__ __forceinline__ void wait() {
-        if (threadIdx.x == 0 && !dead) {
+        if (threadIdx.x < 64 && !dead) {
+            const int lane = threadIdx.x;
+            const unsigned *mine = mem + min(lane, BAR_COUNTERS - 1) * 64;
             long long spins = 0;
-            while ((int)(__hip_atomic_load(mem, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+            for (;;) {
+                const bool done = (int)(__hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) >= 0;
+                if (__all(done)) break;
                 __builtin_amdgcn_s_sleep(1);
                 ++spins;
                 if (spins > SPIN_LIMIT ||
@@ -137,14 +149,8 @@ stores_done();  // this wavefront's write-through stores have reached memory
                     break;
                 }
             }
-#ifdef FUSED_POST_WAIT_SLEEP
-            for (int i = 0; i < FUSED_POST_WAIT_SLEEP; ++i) __builtin_amdgcn_s_sleep(127);
-#endif
         }
         lds_sync();
-#ifdef FUSED_ACQ_AGENT
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-#endif
     }
 };
 
@@ -587,8 +593,9 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
     // keys below the sequence length were written by earlier calls: a first tile made of them is
     // loaded before the barrier wait
     bool preloaded = false;
-    if ((int)blockIdx.x < n_work) {
-        const AttItem it = att_item(a, b, blockIdx.x);
+    const int i_first = a.att_first[blockIdx.x];
+    if (i_first >= 0) {
+        const AttItem it = att_item(a, b, i_first);
         int t_begin, t_end, kmax;
         tile_range(b.s[it.seq], it, len0, t_begin, t_end, kmax);
         const int t = t_begin + wave;
@@ -600,12 +607,13 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
     TRACE(1);
     bar.wait();
     TRACE(2);
-    for (int i = blockIdx.x; i < n_work; i += G) {
+    // further items (more work than workgroups; then there is one part per block) follow in steps of G
+    for (int i = i_first; i >= 0 && i < n_work; i += G) {
         const AttItem it = att_item(a, b, i);
         const SeqDesc &s = b.s[it.seq];
         const int kvh = it.kvh, part = it.part;
         const int n_items = s.nrows * group;
-        const int len = i == (int)blockIdx.x ? len0 : s.state[0];
+        const int len = i == i_first ? len0 : s.state[0];
         int t_begin, t_end, kmax;
         tile_range(s, it, len, t_begin, t_end, kmax);
         const int item = it.qb * 16 + l15;
@@ -682,7 +690,7 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
         preloaded = false;
         TRACE(20);
         // ---- merge of the eight wavefronts through LDS ----
-        if (i != (int)blockIdx.x) lds_sync();  // the previous item's merge has been read
+        if (i != i_first) lds_sync();  // the previous item's merge has been read
 #pragma unroll
         for (int db = 0; db < DB; ++db) o_s[(wave * DB + db) * 64 + lane] = st.o[db];
         if (g4 == 0) {
@@ -779,7 +787,7 @@ template <int NB, int HD>
 __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs a, Batch b) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ FusedShared sh;
-    GridBar bar{a.bar, a.fail, a.root0, gridDim.x / BAR_GROUP, false};
+    GridBar bar{a.bar, a.fail, a.root0, gridDim.x / BAR_COUNTERS, false};
     const int d = a.d, F = a.F, hd = a.hd, nq = a.hq * hd, nkv = a.hkv * hd;
     const size_t hstride = (size_t)FROWS * d, sstride = (size_t)(d / 16) * 64;
 
@@ -788,7 +796,7 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
 #endif
     // length of the sequence of this workgroup's first attention item (lengths are constant during a launch)
     int len0 = 0;
-    if ((int)blockIdx.x < a.att_blocks * a.att_parts) len0 = b.s[att_item(a, b, blockIdx.x).seq].state[0];
+    if (a.att_first[blockIdx.x] >= 0) len0 = b.s[att_item(a, b, a.att_first[blockIdx.x]).seq].state[0];
     TRACE(0);
     embed_phase(a, b);
     bar.arrive();
@@ -850,7 +858,7 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
             FastGemm g = base;
             g.W = lp.wd; g.N = d; g.KB = F / 32; g.X = act; g.h_in = h1; g.h = h2; g.ss_out = ss2;
             g.ks = a.ks_down; g.kbps = (g.KB + g.ks - 1) / g.ks;
-            gemm_phase<NB, 2, 5, EPI_RESID>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+            gemm_phase<NB, 2, FUSED_PD_DOWN, EPI_RESID>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
         }
         bar.arrive();
         TRACE(16);
@@ -963,7 +971,7 @@ static bool plan_fused(const vf_model *m, const Batch &b, FusedArgs &a, int *G_o
     const int d = c.d_model, F = c.d_ffn, hd = c.head_dim, nq = c.n_q_heads * hd, nkv = c.n_kv_heads * hd;
     if (std::max((nq + 2 * nkv) / 16, F / 16) > VF_N_COUNTERS) return false;
     const int G = FUSED_G, lds = LDS_BYTES;
-    if (G % BAR_GROUP) return false;
+    if (G % BAR_COUNTERS) return false;
     a.ks_qkv = pick_split(G, lds, (nq + 2 * nkv) / 16, d / 32, rows, nb, false);
     a.ks_o = pick_split(G, lds, d / 16, nq / 32, rows, nb, false);
     a.ks_gu = pick_split(G, lds, F / 16, d / 32, rows, nb, false);
@@ -1035,12 +1043,36 @@ int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logi
     a.m = b.total_rows;
     a.att_blocks = blocks;
     a.att_parts = parts;
+    {
+        // item = part * blocks + block, block = (sequence, kv head, query block) in that order
+        const int n_work = blocks * parts;
+        for (int w = 0; w < FUSED_G; ++w) a.att_first[w] = (short)(w < n_work && n_work > G ? w : -1);
+        if (n_work <= G) {
+            int next[8], die = 0;
+            for (int x = 0; x < 8; ++x) next[x] = x;
+            int blk0 = 0;
+            for (int sq = 0; sq < b.n_seqs; ++sq) {
+                const int nqb = (b.s[sq].nrows * group + 15) / 16;
+                for (int kvh = 0; kvh < c.n_kv_heads; ++kvh)
+                    for (int p = 0; p < parts; ++p) {
+                        for (int qb = 0; qb < nqb; ++qb) {
+                            int x = die;
+                            for (int tries = 0; tries < 8 && next[x] >= G; ++tries) x = (x + 1) % 8;  // that die is full
+                            a.att_first[next[x]] = (short)(p * blocks + blk0 + kvh * nqb + qb);
+                            next[x] += 8;
+                        }
+                        die = (die + 1) % 8;
+                    }
+                blk0 += c.n_kv_heads * nqb;
+            }
+        }
+    }
     a.has_bias = c.qkv_bias;
     a.inv_d = 1.0f / (float)c.d_model;
     a.eps = c.rms_eps;
     a.scale_log2e = 1.4426950408889634f / sqrtf((float)c.head_dim);
     a.root0 = m->fz_epoch;
-    m->fz_epoch += (1u + 5u * (unsigned)c.n_layers) * (unsigned)(G / BAR_GROUP);  // barriers per launch x groups
+    m->fz_epoch += (1u + 5u * (unsigned)c.n_layers) * (unsigned)(G / BAR_COUNTERS);  // barriers per launch x arrivals per counter
     const int rows = b.total_rows;
     ProfScope ps(m, VF_SITE_STEP, st);
     if (c.head_dim == 128) {
