@@ -24,11 +24,12 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the gate/up GEMM kernel from hardware counters (FETCH_SIZE + WRITE_SIZE,
-# each scaled by what the same counter reads for a plain 1 GiB copy); see
-# profiles/gateup_gemm_1.5b_k16_pmc.md.  Set to None whenever that kernel changes.
-GATEUP_TRAFFIC_BYTES = 56_474_000
-# The same for one launch of the persistent whole-pass kernel (None: not measured since it last changed).
-FUSED_TRAFFIC_BYTES = None
+# each scaled by what the same counter reads for a plain 1 GiB copy); 56,474,000 when last taken, see
+# profiles/gateup_gemm_1.5b_k16_pmc.md.  None: the kernel's source has changed since.
+GATEUP_TRAFFIC_BYTES = None
+# The same for one launch of the persistent whole-pass kernel (profiles/verify_fused_1.5b_k16_pmc.md); set to
+# None whenever that kernel changes.
+FUSED_TRAFFIC_BYTES = 3_534_300_000
 
 
 def log(*a):

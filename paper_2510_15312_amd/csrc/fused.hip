@@ -1,25 +1,29 @@
 // The whole verify forward pass (paper Sec. 3 / Sec. 4.3: rows [T, x_1..x_k] of every sequence of
 // the batch through all decoder layers and the output head) as ONE persistent kernel.
 //
-// The grid is sized so that every workgroup is resident at once; the phases of the pass
-//   embed | per layer: QKV, attention, merge, O, gate/up, down | output head
+// The grid is sized so that every workgroup is resident at once (one workgroup of eight
+// wavefronts per CU); the phases of the pass
+//   embed | per layer: QKV, attention, O, gate/up, down | output head
 // are separated by grid-wide barriers instead of kernel boundaries.  What this buys over a chain
-// of kernels: no launch gap and no ramp-up per phase, and the weight stream never stops -- a
-// workgroup issues the first loads of its next phase (weights do not depend on the previous
-// phase) between arriving at a barrier and waiting on it, and inside a phase it refills its
-// register ring with the next work item's fragments while the current item is reduced.
+// of kernels: no launch gap and no ramp-up per phase, and the weight stream pauses only for the
+// hand-over of the activations -- a workgroup issues the first loads of its next phase (weights
+// do not depend on the previous phase) between arriving at a barrier and waiting on it, and
+// inside a phase it refills its register ring with the next work item's fragments during the
+// current item's last round.
 //
 // Memory protocol between workgroups (different compute dies have separate L2 caches):
 //   * everything one workgroup writes and another reads later in the launch is stored through
-//     to memory (agent-scope stores) and the barrier waits for those stores to complete;
+//     to memory (agent-scope stores), and a workgroup waits until its stores have completed
+//     before it signals anything (a barrier arrival, a counter) to other workgroups;
 //   * bulk data is read with ordinary loads from single-assignment buffers -- one version of
-//     the residual stream per half layer, one q / attention output / SwiGLU buffer per layer --
-//     so no cache can hold a stale line of it: a line is never read before its only write in a
-//     launch, and caches start clean at every launch;
-//   * data in reused buffers (split-K partial tiles, attention partials, counters) is read with
-//     agent-scope loads.
+//     the residual stream per half layer, one q / attention output / SwiGLU buffer and one set
+//     of attention records per layer -- so no cache can hold a stale line of it: a line is never
+//     read before its only write in a launch, and caches start clean at every launch;
+//   * data in reused buffers (split-K partial tiles, counters) is read with agent-scope loads.
 // The KV cache is written (new rows) and read (all rows) once per layer and launch, in that
-// order, so it follows the single-assignment rule as well.
+// order; tiles that hold new rows are read with agent-scope loads.
+//
+// Results do not depend on timing: every sum has a fixed order.
 #include "fast_common.h"
 
 #include <type_traits>
@@ -36,8 +40,6 @@ constexpr int ATT_COUNTERS = 4096;  // arrival counters of the attention blocks 
 constexpr int LDS_BYTES = 152 * 1024;  // dynamic LDS of the one workgroup a CU holds (160 KB less the static part)
 constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (seconds, not microseconds)
 
-// One workgroup of 8 wavefronts per CU: two wavefronts per SIMD, so each may use up to 256 vector
-// registers (weight ring + staging loads in flight) without spilling.
 #ifndef FUSED_PREFETCH_EARLY
 #define FUSED_PREFETCH_EARLY 1   // first weight loads of a phase go out before the barrier wait
 #endif
@@ -47,6 +49,8 @@ constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (s
 #ifndef FUSED_MAXP
 #define FUSED_MAXP 8              // most key parts per attention block (at most 8: the merge holds them all)
 #endif
+// One workgroup of 8 wavefronts per CU: two wavefronts per SIMD, so each may use up to 256 vector
+// registers (weight ring + staging loads in flight) without spilling.
 #ifndef FUSED_G
 #define FUSED_G 256
 #endif
@@ -106,10 +110,6 @@ struct FusedArgs {
 // its LDS operations; the empty asm statements keep the compiler from moving memory accesses
 // across it.
 __device__ __forceinline__ void lds_sync() {
-#ifdef FUSED_SYNC_FULL
-    __syncthreads();
-    return;
-#endif
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
