@@ -273,6 +273,18 @@ def main():
                      "avg_launch_us": round(avg_us, 2), "bytes_per_launch": int(k_bytes)},
         "sites_us_per_step": {n: site_tbl[n]["us_per_step"] for n in site_tbl},
     }
+    # yardstick: how fast this GPU reads the same weights with nothing else to do
+    for _ in range(3):
+        nbytes = vf.vf_stream_read(model)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        vf.vf_stream_read(model)
+    e1.record()
+    torch.cuda.synchronize()
+    stream_gbs = nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    res["stream_read"] = {"GB/s": round(stream_gbs, 1), "bytes": nbytes, "frac_of_peak": round(stream_gbs / HBM_PEAK_GBS, 4),
+                          "step_vs_stream_read": round(gbs / stream_gbs, 4)}
     # determinism: the timed replay must have walked the recorded trajectory
     assert ln_end == lens[K], (ln_end, lens[K])
     if args.pmc_calibration:

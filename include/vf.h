@@ -245,6 +245,11 @@ int vf_profile(vf_model *m, int enable);
  * site into ms_host[VF_N_SITES] / count_host[VF_N_SITES], and clears the record. */
 int vf_profile_read(vf_model *m, float *ms_host, int32_t *count_host);
 
+/* Yardstick for the roofline: one kernel that reads every packed weight of the model (what a verify
+ * step must stream at least) and does nothing else.  Returns the number of bytes it reads in
+ * *bytes_host; the caller times it with events on `stream`.  Writes 4 bytes of workspace. */
+int vf_stream_read(vf_model *m, size_t *bytes_host, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ EXPORTS = [
     "vf_last_error", "vf_model_packed_bytes", "vf_model_create", "vf_model_destroy",
     "vf_seq_state_bytes", "vf_kv_bytes", "vf_seq_create", "vf_seq_destroy", "vf_seq_set_len",
     "vf_seq_set_pending", "vf_seq_get_state", "vf_kv_read", "vf_kv_write", "vf_prefill_chunk", "vf_verify",
-    "vf_accept", "vf_profile", "vf_profile_read", "vf_set_option",
+    "vf_accept", "vf_profile", "vf_profile_read", "vf_set_option", "vf_stream_read",
 ]
 SITES = ["qkv", "o", "gateup", "down", "head", "attn", "small", "accept", "step"]
 
@@ -83,6 +83,7 @@ def _load():
                                 vp, vp, vp, vp, vp]),
         "vf_set_option": (C.c_int, [vp, C.c_int, C.c_int]),
         "vf_profile": (C.c_int, [vp, C.c_int]),
+        "vf_stream_read": (C.c_int, [vp, C.POINTER(sz), vp]),
         "vf_profile_read": (C.c_int, [vp, C.POINTER(C.c_float), C.POINTER(i32)]),
     }
     for name, (res, args) in sig.items():
@@ -257,6 +258,13 @@ def vf_profile_read(model):
     cnt = (C.c_int32 * len(SITES))()
     _check(lib.vf_profile_read(model.handle, ms, cnt))
     return {s: (ms[i], cnt[i]) for i, s in enumerate(SITES)}
+
+
+def vf_stream_read(model):
+    """Launches the read-every-weight yardstick kernel; returns the bytes it reads."""
+    n = C.c_size_t(0)
+    _check(lib.vf_stream_read(model.handle, C.byref(n), _stream()))
+    return n.value
 
 
 def vf_set_option(model, option, value):

@@ -497,6 +497,11 @@ int vf_set_option(vf_model *m, int option, int value) {
     return vf_fail(VF_ERR_ARG, "vf_set_option: unknown option %d", option);
 }
 
+int vf_stream_read(vf_model *m, size_t *bytes_host, void *stream) {
+    if (!m || !bytes_host) return vf_fail(VF_ERR_ARG, "vf_stream_read: NULL argument");
+    return vf_launch_stream_read(m, bytes_host, (hipStream_t)stream);
+}
+
 int vf_profile(vf_model *m, int enable) {
     if (!m) return vf_fail(VF_ERR_ARG, "vf_profile: NULL");
     m->prof_on = enable != 0;

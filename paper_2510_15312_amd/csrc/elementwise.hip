@@ -329,6 +329,35 @@ int vf_launch_state_add(int32_t *state, int idx, int32_t delta, hipStream_t st) 
     return VF_OK;
 }
 
+namespace {
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// Every thread streams 16-byte pieces at a stride of the whole grid; the xor of what it read goes to a
+// word nobody reads unless it is a magic value (so the loads cannot be dropped).
+__global__ __launch_bounds__(512) void stream_read_kernel(const u32x4_t *__restrict__ p, size_t n, int32_t *sink) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    u32x4_t acc = {0u, 0u, 0u, 0u};
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 7 * stride < n; i += 8 * stride) {
+        u32x4_t v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(p + i + j * stride);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc ^= v[j];
+    }
+    for (; i < n; i += stride) acc ^= __builtin_nontemporal_load(p + i);
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9e3779b9u) *sink = 1;
+}
+}  // namespace
+
+int vf_launch_stream_read(const vf_model *m, size_t *bytes, hipStream_t st) {
+    // the packed weights sit at the start of the model's buffer, up to the rotary tables
+    const size_t n = ((const char *)m->rope_cos - (const char *)m->base) / 16;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(1024), dim3(512), 0, st, (const u32x4_t *)m->base, n, m->scratch_i32 + 63);
+    VF_LAUNCH_CHECK("stream_read");
+    *bytes = n * 16;
+    return VF_OK;
+}
+
 int vf_launch_kv_write(const vf_model *m, const SeqDesc &s, int layer, int t0, int n, const float *k_in,
                        const float *v_in, hipStream_t st) {
     const vf_config &c = m->cfg;

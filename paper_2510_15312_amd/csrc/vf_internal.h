@@ -222,6 +222,7 @@ int vf_launch_state_set(int32_t *state, int idx, int32_t value, hipStream_t st);
 int vf_launch_state_add(int32_t *state, int idx, int32_t delta, hipStream_t st);
 int vf_launch_kv_read(const vf_model *m, const SeqDesc &s, int layer, int t0, int n, float *k_out,
                       float *v_out, hipStream_t st);
+int vf_launch_stream_read(const vf_model *m, size_t *bytes, hipStream_t st);
 int vf_launch_kv_write(const vf_model *m, const SeqDesc &s, int layer, int t0, int n, const float *k_in,
                        const float *v_in, hipStream_t st);
 int vf_launch_accept(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,

@@ -76,6 +76,7 @@ def test_null_handles_are_errors_not_crashes():
     assert L.vf_seq_get_state(None, None, None, None) == vf.VF_ERR_ARG
     assert L.vf_kv_read(None, None, 0, 0, 0, None, None, None) == vf.VF_ERR_ARG
     assert L.vf_kv_write(None, None, 0, 0, 0, None, None, None) == vf.VF_ERR_ARG
+    assert L.vf_stream_read(None, None, None) == vf.VF_ERR_ARG
     assert L.vf_prefill_chunk(None, None, None, 1, 0, None, 0, None, 0.0, None) == vf.VF_ERR_ARG
     assert L.vf_verify(None, None, 1, None, None, None, None) == vf.VF_ERR_ARG
     assert L.vf_accept(None, None, 1, None, None, None, None, None, None, None, None) == vf.VF_ERR_ARG
