@@ -162,6 +162,10 @@ def main():
     prefill_ms = (time.time() - t0) * 1e3
     len0, pending0 = vf.vf_seq_get_state(seq)
     assert len0 == cfg.ctx
+    # flops of the chunked prefill: every layer weight twice per token, plus Q K^T and P V over the causal context
+    layer_params = (cfg.weight_bytes() - V * cfg.d_model * 2) // 2
+    prefill_flops = 2.0 * cfg.ctx * layer_params + \
+        4.0 * cfg.n_layers * cfg.n_q_heads * cfg.head_dim * (cfg.ctx * (cfg.ctx + 1) / 2)
     log(f"[bench] prefill of {cfg.ctx} tokens: {prefill_ms:.1f} ms")
 
     # ---- trajectory pre-pass: generates every step's inputs, leaves them in HBM ----------------
@@ -267,6 +271,9 @@ def main():
         "accepted_drafts_per_step": round(float(np.mean(acc_ref[:K])), 3),
         "us_per_emitted_token": round(ms_per_step * 1e3 / (1 + float(np.mean(acc_ref[:K]))), 1),
         "prefill_ms": round(prefill_ms, 1),
+        "prefill": {"tokens": cfg.ctx, "chunk": cfg.chunk, "ms": round(prefill_ms, 1),
+                    "TFLOP/s": round(prefill_flops / (prefill_ms * 1e-3) / 1e12, 1),
+                    "frac_of_bf16_mfma_peak": round(prefill_flops / (prefill_ms * 1e-3) / 2.5e15, 4)},
         "roofline": {"bound": "hbm", "kernel": kern,
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,

@@ -323,53 +323,92 @@ __global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, cons
     }
 }
 
-// Many rows (a prefill chunk, or a large batch): one workgroup per (64 query items, kv head,
-// sequence) walks all key slices its items can see; each wavefront owns one block of 16 items for
-// the whole walk, so no partial results leave the workgroup.  Output in the bf16 activation
-// (MFMA B-operand) layout the general GEMM reads.
+// Many rows (a prefill chunk, or a large batch): one workgroup of eight wavefronts per (32 query
+// items = two blocks of 16, kv head, sequence).  The wavefronts take the 32-key tiles its items can
+// see in turn (tile t goes to wavefront t mod 8); a tile's K and V^T fragments go from the cache
+// straight into registers, once, and serve both item blocks.  Each wavefront keeps an online
+// softmax state per item block; the eight states are merged through LDS at the end, so nothing
+// partial leaves the workgroup.  Output in the bf16 activation (MFMA B-operand) layout the
+// general GEMM reads.
+constexpr int ROWS_QB = 2, ROWS_WAVES = 8;
+
 template <int HD>
-__global__ __launch_bounds__(256) void attn_rows_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
-                                                        bf16_t *__restrict__ o, int hq, int hkv, int ncb,
-                                                        float scale_log2e) {
+__global__ __launch_bounds__(ROWS_WAVES * 64) void attn_rows_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
+                                                                   bf16_t *__restrict__ o, int hq, int hkv, int ncb,
+                                                                   float scale_log2e) {
     constexpr int KD = HD / 32, DB = HD / 16;
-    __shared__ __align__(16) AttLds<HD> L;
+    extern __shared__ __align__(16) unsigned char rows_smem[];
+    floatx4 *o_s = reinterpret_cast<floatx4 *>(rows_smem);                            // [wave][db][lane]
+    float *ml_s = reinterpret_cast<float *>(rows_smem + ROWS_WAVES * DB * 64 * 16);  // [wave][2][16]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g4 = lane >> 4, l15 = lane & 15;
     const int kvh = blockIdx.y;
     const SeqDesc &s = b.s[blockIdx.z];
     const int group = hq / hkv, n_items = s.nrows * group;
-    const int item0 = blockIdx.x * 64;
+    const int item0 = blockIdx.x * (16 * ROWS_QB);
     if (item0 >= n_items) return;
     const int len = s.state[0];
     const int kmax = min(len + s.nrows, s.capacity);
-    const int item = item0 + wave * 16 + l15;
-    const bool valid = item < n_items;
-    const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
-    const int row = s.row0 + r;
-    const int last_key = valid ? len + r : -1;
-    const int blk_last = len + min(s.nrows - 1, (item0 + wave * 16 + 15) / group);
-    const int wg_last = min(kmax - 1, len + min(s.nrows - 1, (item0 + 63) / group));
-    bf16x8 qf[KD];
+    bf16x8 qf[ROWS_QB][KD];
+    AttState<HD> st[ROWS_QB];
+    int last_key[ROWS_QB], blk_last[ROWS_QB], row[ROWS_QB], head[ROWS_QB];
+    bool valid[ROWS_QB];
 #pragma unroll
-    for (int kd = 0; kd < KD; ++kd)
-        qf[kd] = *reinterpret_cast<const bf16x8 *>(q + ((size_t)row * hq + head) * HD + kd * 32 + g4 * 8);
-    AttState<HD> st;
+    for (int c = 0; c < ROWS_QB; ++c) {
+        const int item = item0 + c * 16 + l15;
+        valid[c] = item < n_items;
+        const int r = valid[c] ? item / group : 0;
+        head[c] = kvh * group + (valid[c] ? item % group : 0);
+        row[c] = s.row0 + r;
+        last_key[c] = valid[c] ? len + r : -1;
+        blk_last[c] = min(kmax - 1, len + min(s.nrows - 1, (item0 + c * 16 + 15) / group));
 #pragma unroll
-    for (int db = 0; db < DB; ++db) st.o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
-    st.m_run = -1e30f;
-    st.l_run = 0.f;
-    for (int k_begin = 0; k_begin <= wg_last; k_begin += ATT_KEYS) {
-        __syncthreads();  // previous slice consumed
-        att_stage<HD>(s, layer, hkv, kvh, k_begin, kmax, L, tid);
-        __syncthreads();
-        att_slice<HD>(st, qf, L, k_begin, last_key, blk_last, scale_log2e, lane);
+        for (int kd = 0; kd < KD; ++kd)
+            qf[c][kd] = *reinterpret_cast<const bf16x8 *>(q + ((size_t)row[c] * hq + head[c]) * HD + kd * 32 + g4 * 8);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) st[c].o[db] = floatx4{0.f, 0.f, 0.f, 0.f};
+        st[c].m_run = -1e30f;
+        st[c].l_run = 0.f;
     }
-    if (valid) {
-        const float inv = 1.0f / st.l_run;
+    const int tiles = blk_last[ROWS_QB - 1] / ATT_TILE + 1;  // the last block sees the most keys
+    AttTile<HD> tile;
+#pragma unroll 1
+    for (int t = wave; t < tiles; t += ROWS_WAVES) {
+        const int t0 = t * ATT_TILE;
+        tile.load(s, layer, hkv, kvh, t, false, lane);
+        tile.mask_values(t0, kmax, lane);
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            const int k = head * HD + db * 16 + g4 * 4;
-            *reinterpret_cast<u32x2 *>(o + xfrag_index(row, k, ncb)) =
-                pack4_bf16(st.o[db][0] * inv, st.o[db][1] * inv, st.o[db][2] * inv, st.o[db][3] * inv);
+        for (int c = 0; c < ROWS_QB; ++c)
+            if (t0 <= blk_last[c]) att_tile_update<HD>(st[c], qf[c], tile, t0, last_key[c], scale_log2e, lane);
+    }
+    // merge of the eight wavefronts, one item block at a time: thread (db = wave, lane) owns
+    // O^T[d = 16*db + 4*g4 + j][item l15]; HD = 64 leaves wavefronts 4..7 idle here
+#pragma unroll
+    for (int c = 0; c < ROWS_QB; ++c) {
+        if (c) lds_sync();
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o_s[(wave * DB + db) * 64 + lane] = st[c].o[db];
+        if (g4 == 0) {
+            ml_s[(wave * 2 + 0) * 16 + l15] = st[c].m_run;
+            ml_s[(wave * 2 + 1) * 16 + l15] = st[c].l_run;
+        }
+        lds_sync();
+        if (wave < DB) {
+            float M = -1e30f, L = 0.f;
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < ROWS_WAVES; ++w) M = fmaxf(M, ml_s[(w * 2) * 16 + l15]);
+#pragma unroll
+            for (int w = 0; w < ROWS_WAVES; ++w) {
+                const float wt = exp2f(ml_s[(w * 2) * 16 + l15] - M);
+                L += ml_s[(w * 2 + 1) * 16 + l15] * wt;
+                acc += o_s[(w * DB + wave) * 64 + lane] * wt;
+            }
+            if (valid[c]) {
+                const float inv = 1.0f / L;
+                const int k = head[c] * HD + wave * 16 + g4 * 4;
+                *reinterpret_cast<u32x2 *>(o + xfrag_index(row[c], k, ncb)) =
+                    pack4_bf16(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+            }
         }
     }
 }
@@ -552,14 +591,21 @@ int vf_launch_attention_rows(const vf_model *m, const Batch &b, int layer, hipSt
     const int group = c.n_q_heads / c.n_kv_heads;
     int max_items = 0;
     for (int i = 0; i < b.n_seqs; ++i) max_items = max(max_items, b.s[i].nrows * group);
-    const dim3 grid((max_items + 63) / 64, c.n_kv_heads, b.n_seqs);
+    const dim3 grid((max_items + 16 * ROWS_QB - 1) / (16 * ROWS_QB), c.n_kv_heads, b.n_seqs);
     const int ncb = (b.total_rows + 15) >> 4;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)c.head_dim);
+    const int lds = ROWS_WAVES * (c.head_dim / 16) * 64 * 16 + ROWS_WAVES * 2 * 16 * 4;
+    static bool attr_done = false;
+    if (!attr_done) {
+        VF_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(attn_rows_kernel<128>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, ROWS_WAVES * 8 * 64 * 16 + 1024));
+        attr_done = true;
+    }
     if (c.head_dim == 128)
-        hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(256), 0, st, b, layer, (const bf16_t *)m->q,
+        hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(ROWS_WAVES * 64), lds, st, b, layer, (const bf16_t *)m->q,
                            (bf16_t *)m->o, c.n_q_heads, c.n_kv_heads, ncb, scale_log2e);
     else
-        hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(256), 0, st, b, layer, (const bf16_t *)m->q,
+        hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(ROWS_WAVES * 64), lds, st, b, layer, (const bf16_t *)m->q,
                            (bf16_t *)m->o, c.n_q_heads, c.n_kv_heads, ncb, scale_log2e);
     VF_LAUNCH_CHECK("attn_rows");
     return VF_OK;

@@ -358,4 +358,106 @@ __device__ inline void att_slice(AttState<HD> &st, const bf16x8 (&qf)[HD / 32], 
     }
 }
 
+
+// ---- register-fed attention tiles -----------------------------------------------------------------
+// A tile is 32 keys of one kv head.  K rows are fed to the first MFMA in the order
+// 8*(rho >> 2) + (rho & 3) (+ 4 for the second 16-key block), which makes the score tile
+// S^T[key, item] = K Q^T come out with eight consecutive keys per lane: the B-operand layout of
+// O^T[d, item] += V^T[d, key] P[key, item]; the matching V^T fragment is one 16-byte load.
+constexpr int ATT_TILE = 32;
+
+template <int HD> struct AttTile {
+    bf16x8 kf[2][HD / 32], vf[HD / 16];
+    // coh: the tile holds keys written during this launch by other workgroups
+    __device__ __forceinline__ void load(const SeqDesc &s, int layer, int hkv, int kvh, int t, bool coh, int lane) {
+        const int g4 = lane >> 4, l15 = lane & 15;
+        const int krow = 8 * (l15 >> 2) + (l15 & 3);
+        const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);
+        const int t0 = t * ATT_TILE, page = kv_page(s, t0), tin = t0 % VF_TILE;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int kd = 0; kd < HD / 32; ++kd) {
+                const bf16_t *kp = kv + kv_k_index(layer, s.n_pages, page, hkv, kvh, tin + krow + 4 * h, kd * 32 + g4 * 8, HD);
+                kf[h][kd] = coh ? __builtin_bit_cast(bf16x8, load_coherent16(kp)) : *reinterpret_cast<const bf16x8 *>(kp);
+            }
+#pragma unroll
+        for (int db = 0; db < HD / 16; ++db) {
+            const bf16_t *vp = kv + kv_v_index(layer, s.n_pages, page, hkv, kvh, tin + g4 * 8, db * 16 + l15, HD);
+            vf[db] = coh ? __builtin_bit_cast(bf16x8, load_coherent16(vp)) : *reinterpret_cast<const bf16x8 *>(vp);
+        }
+    }
+    // rows of the cache at or past kmax may hold anything: keep them out of the P V product
+    __device__ __forceinline__ void mask_values(int t0, int kmax, int lane) {
+        if (t0 + ATT_TILE > kmax) {
+            const int g4 = lane >> 4;
+#pragma unroll
+            for (int db = 0; db < HD / 16; ++db)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (t0 + g4 * 8 + j >= kmax) vf[db][j] = (bf16_t)0.f;
+        }
+    }
+};
+
+// One tile for one block of 16 query items: masked online softmax update of st.
+// last_key: last visible key of this lane's item (-1: none).
+template <int HD>
+__device__ __forceinline__ void att_tile_update(AttState<HD> &st, const bf16x8 (&qf)[HD / 32], const AttTile<HD> &T, int t0,
+                                                int last_key, float scale_log2e, int lane) {
+    constexpr int KD = HD / 32, DB = HD / 16;
+    const int g4 = lane >> 4;
+    floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kd = 0; kd < KD; ++kd) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T.kf[0][kd], qf[kd], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T.kf[1][kd], qf[kd], s1, 0, 0, 0);
+    }
+    // lane holds keys t0 + 8*g4 + j (s0) and t0 + 8*g4 + 4 + j (s1) of item (lane & 15)
+    float p[8], tmax = -1e30f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        p[j] = (t0 + g4 * 8 + j <= last_key) ? s0[j] * scale_log2e : -1e30f;
+        p[4 + j] = (t0 + g4 * 8 + 4 + j <= last_key) ? s1[j] * scale_log2e : -1e30f;
+        tmax = fmaxf(tmax, fmaxf(p[j], p[4 + j]));
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(st.m_run, tmax);
+    const float corr = exp2f(st.m_run - m_new);
+    float psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        p[j] = (t0 + g4 * 8 + j <= last_key) ? exp2f(p[j] - m_new) : 0.f;
+        psum += p[j];
+    }
+    psum += __shfl_xor(psum, 16, 64);
+    psum += __shfl_xor(psum, 32, 64);
+    st.l_run = st.l_run * corr + psum;
+    st.m_run = m_new;
+    // probabilities as a sum of two bfloat16 values (16 significant bits): the P * V product
+    // then carries no more rounding than its bfloat16 V operand
+    bf16x8 pf, pl;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        pf[j] = (bf16_t)p[j];
+        pl[j] = (bf16_t)(p[j] - (float)pf[j]);
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+        st.o[db] = st.o[db] * corr;
+        st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T.vf[db], pf, st.o[db], 0, 0, 0);
+        st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T.vf[db], pl, st.o[db], 0, 0, 0);
+    }
+}
+
+// Workgroup barrier for data exchanged through LDS only.  Unlike __syncthreads() it does not wait
+// for this wavefront's global loads in flight, only for its LDS operations; the empty asm
+// statements keep the compiler from moving memory accesses across it.
+__device__ __forceinline__ void lds_sync() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 }  // namespace

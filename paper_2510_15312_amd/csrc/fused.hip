@@ -105,16 +105,6 @@ struct FusedArgs {
     int lds_total;    // dynamic LDS bytes of this launch
 };
 
-// Workgroup barrier for data exchanged through LDS only.  Unlike __syncthreads() it does not wait
-// for this wavefront's global loads in flight (the weight fragments prefetched for later), only for
-// its LDS operations; the empty asm statements keep the compiler from moving memory accesses
-// across it.
-__device__ __forceinline__ void lds_sync() {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 // Counting barrier, split into arrive and wait.  The workgroups are spread over BAR_COUNTERS counters
 // (each in a memory channel of its own, so that the increments of a barrier are not all serialised
 // at one address); an arrival is one increment that returns nothing, and a barrier is complete when
@@ -526,7 +516,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 // Wavefront results (running max, sum, O^T) are merged through LDS; with several parts the
 // merged partials go to memory and the last workgroup to arrive merges the parts.  No second
 // grid-wide phase is needed for the merge.
-constexpr int FKT = 32;  // keys per tile
+constexpr int FKT = ATT_TILE;  // keys per tile
 
 // (sequence, kv head, query block, key part) of attention work item i
 struct AttItem { int seq, kvh, qb, part, blk; };
@@ -562,27 +552,7 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
     floatx4 *o_s = reinterpret_cast<floatx4 *>(smem);                      // [wave][db][lane]
     float *ml_s = reinterpret_cast<float *>(smem + FW * DB * 64 * 16);    // [wave][2][16]
     const int n_work = a.att_blocks * P;
-    // K row fed to MFMA row rho of 16-key block h: key 8*(rho >> 2) + 4*h + (rho & 3)
-    const int krow = 8 * (l15 >> 2) + (l15 & 3);
-    bf16x8 kf[2][KD], vf[DB];
-    // coh: the tile holds keys written during this launch (by the QKV phase of this layer)
-    auto load_tile = [&](const SeqDesc &s, int kvh, int t, bool coh) {
-        const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);
-        const int t0 = t * FKT, page = kv_page(s, t0), tin = t0 % VF_TILE;
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int kd = 0; kd < KD; ++kd) {
-                const bf16_t *kp = kv + kv_k_index(layer, s.n_pages, page, hkv, kvh, tin + krow + 4 * h, kd * 32 + g4 * 8, HD);
-                kf[h][kd] = coh ? __builtin_bit_cast(bf16x8, load_coherent16(kp)) : *reinterpret_cast<const bf16x8 *>(kp);
-            }
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-        {
-            const bf16_t *vp = kv + kv_v_index(layer, s.n_pages, page, hkv, kvh, tin + g4 * 8, db * 16 + l15, HD);
-            vf[db] = coh ? __builtin_bit_cast(bf16x8, load_coherent16(vp)) : *reinterpret_cast<const bf16x8 *>(vp);
-        }
-    };
+    AttTile<HD> tile;
     auto tile_range = [&](const SeqDesc &s, const AttItem &it, int len, int &t_begin, int &t_end, int &kmax) {
         kmax = min(len + s.nrows, s.capacity);  // keys 0..kmax-1 exist
         const int blk_last = min(kmax - 1, len + min(s.nrows - 1, (it.qb * 16 + 15) / group));
@@ -600,7 +570,7 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
         tile_range(b.s[it.seq], it, len0, t_begin, t_end, kmax);
         const int t = t_begin + wave;
         if (t < t_end && (t + 1) * FKT <= len0) {
-            load_tile(b.s[it.seq], it.kvh, t, false);
+            tile.load(b.s[it.seq], layer, hkv, it.kvh, t, false, lane);
             preloaded = true;
         }
     }
@@ -634,58 +604,10 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
 #pragma unroll 1
         for (int t = t_begin + wave; t < t_end; t += FW) {
             const int t0 = t * FKT;
-            if (!preloaded) load_tile(s, kvh, t, (t + 1) * FKT > len);
+            if (!preloaded) tile.load(s, layer, hkv, kvh, t, (t + 1) * FKT > len, lane);
             preloaded = false;
-            floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kd = 0; kd < KD; ++kd) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][kd], qf[kd], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][kd], qf[kd], s1, 0, 0, 0);
-            }
-            // lane holds keys t0 + 8*g4 + j (s0) and t0 + 8*g4 + 4 + j (s1) of item l15
-            float p[8], tmax = -1e30f;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                p[j] = (t0 + g4 * 8 + j <= last_key) ? s0[j] * a.scale_log2e : -1e30f;
-                p[4 + j] = (t0 + g4 * 8 + 4 + j <= last_key) ? s1[j] * a.scale_log2e : -1e30f;
-                tmax = fmaxf(tmax, fmaxf(p[j], p[4 + j]));
-            }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float m_new = fmaxf(st.m_run, tmax);
-            const float corr = exp2f(st.m_run - m_new);
-            float psum = 0.f;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                p[j] = (t0 + g4 * 8 + j <= last_key) ? exp2f(p[j] - m_new) : 0.f;
-                psum += p[j];
-            }
-            psum += __shfl_xor(psum, 16, 64);
-            psum += __shfl_xor(psum, 32, 64);
-            st.l_run = st.l_run * corr + psum;
-            st.m_run = m_new;
-            // probabilities as a sum of two bfloat16 values (16 significant bits): the P * V
-            // product then carries no more rounding than its bfloat16 V operand
-            bf16x8 pf, pl;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                pf[j] = (bf16_t)p[j];
-                pl[j] = (bf16_t)(p[j] - (float)pf[j]);
-            }
-            // rows of the cache past the last key may hold anything: keep them out of the product
-            if (t0 + FKT > kmax) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (t0 + g4 * 8 + j >= kmax) vf[db][j] = (bf16_t)0.f;
-            }
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                st.o[db] = st.o[db] * corr;
-                st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pf, st.o[db], 0, 0, 0);
-                st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pl, st.o[db], 0, 0, 0);
-            }
+            tile.mask_values(t0, kmax, lane);
+            att_tile_update<HD>(st, qf, tile, t0, last_key, a.scale_log2e, lane);
         }
         preloaded = false;
         TRACE(20);
