@@ -451,13 +451,4 @@ __device__ __forceinline__ void att_tile_update(AttState<HD> &st, const bf16x8 (
     }
 }
 
-// Workgroup barrier for data exchanged through LDS only.  Unlike __syncthreads() it does not wait
-// for this wavefront's global loads in flight, only for its LDS operations; the empty asm
-// statements keep the compiler from moving memory accesses across it.
-__device__ __forceinline__ void lds_sync() {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 }  // namespace

@@ -112,14 +112,17 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_bf16_kernel(
 
 // Many rows (a prefill chunk): workgroup tile = 16*MB rows x TNB weight blocks, four wavefronts
 // of 4*MB rows each.  Per K step of KSTEP 32-wide k-blocks the weight and activation fragments go
-// through a double-buffered LDS stage (one barrier per step, the next step's global loads in
-// flight during the MFMAs).
+// through a double-buffered LDS stage, one barrier per step.  Global loads run two steps ahead of
+// the MFMAs through two register sets; they are never predicated (addresses past the end are
+// clamped and what they fetch is not used), so the compiler waits for exactly the set it stores,
+// and the barrier orders LDS traffic only.
 template <int TNB, int MB, int KSTEP>
 __global__ __launch_bounds__(256) void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp,
                                                         float *__restrict__ part, int N, int KB, int ncb, int row_lo,
                                                         int row_hi, int ld_rows, int kb_per_split) {
     constexpr int NF = TNB + MB;               // fragments per 32-wide k-block
-    constexpr int NL = (KSTEP * NF * 64 + 255) / 256;  // 16-byte loads per thread and stage
+    constexpr int NL = KSTEP * NF * 64 / 256;  // 16-byte loads per thread and stage
+    static_assert(KSTEP * NF * 64 % 256 == 0, "a stage is a whole number of loads per thread");
     constexpr int WC = MB / 4;                 // activation blocks per wavefront
     __shared__ u32x4 lds[2][KSTEP * NF * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -132,34 +135,32 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(const u32x4 *__restrict_
     for (int n = 0; n < TNB; ++n)
 #pragma unroll
         for (int c = 0; c < WC; ++c) acc[n][c] = floatx4{0.f, 0.f, 0.f, 0.f};
-    u32x4 r[NL];
-    auto fetch = [&](int kb) {
+    if (kb_begin >= kb_end) return;
+    // where this thread's pieces of a stage come from: piece i is fragment f of k-block `half`
+    const u32x4 *src[NL];
+    size_t kstride[NL];
+    int half_of[NL];
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int idx = tid + i * 256, half = idx / (NF * 64), rem = idx % (NF * 64), f = rem >> 6, l = rem & 63;
-            const int k = kb + half;
-            r[i] = u32x4{0u, 0u, 0u, 0u};
-            if (half < KSTEP && k < kb_end) {
-                if (f < TNB) {
-                    const int nb = min(nb0 + f, NBt - 1);
-                    r[i] = __builtin_nontemporal_load(Wp + ((size_t)nb * KB + k) * 64 + l);
-                } else {
-                    const int cb = cb0 + f - TNB;
-                    if (cb < ncb) r[i] = Xp[((size_t)k * ncb + cb) * 64 + l];
-                }
-            }
+    for (int i = 0; i < NL; ++i) {
+        const int idx = tid + i * 256, rem = idx % (NF * 64), f = rem >> 6, l = rem & 63;
+        half_of[i] = idx / (NF * 64);
+        if (f < TNB) {
+            src[i] = Wp + (size_t)min(nb0 + f, NBt - 1) * KB * 64 + l;   // rows past N: a valid block, result dropped
+            kstride[i] = 64;
+        } else {
+            src[i] = Xp + (size_t)min(cb0 + f - TNB, ncb - 1) * 64 + l;  // rows past the call: likewise
+            kstride[i] = (size_t)ncb * 64;
         }
+    }
+    auto fetch = [&](u32x4 (&r)[NL], int kb) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) r[i] = src[i][(size_t)min(kb + half_of[i], kb_end - 1) * kstride[i]];
     };
-    if (kb_begin < kb_end) fetch(kb_begin);
-    int buf = 0;
-    for (int kb = kb_begin; kb < kb_end; kb += KSTEP, buf ^= 1) {
+    auto stage = [&](const u32x4 (&r)[NL], int buf) {
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int idx = tid + i * 256;
-            if (idx < KSTEP * NF * 64) lds[buf][idx] = r[i];
-        }
-        __syncthreads();
-        if (kb + KSTEP < kb_end) fetch(kb + KSTEP);
+        for (int i = 0; i < NL; ++i) lds[buf][tid + i * 256] = r[i];
+    };
+    auto multiply = [&](int buf, int kb) {
 #pragma unroll
         for (int half = 0; half < KSTEP; ++half) {
             if (kb + half < kb_end) {
@@ -176,6 +177,22 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(const u32x4 *__restrict_
                 }
             }
         }
+    };
+    u32x4 ra[NL], rb[NL];
+    fetch(ra, kb_begin);
+    fetch(rb, kb_begin + KSTEP);
+    // a buffer is written again two steps later, behind the barrier of the step in between, which
+    // every wavefront reaches only after its MFMAs on that buffer
+    for (int kb = kb_begin; kb < kb_end; kb += 2 * KSTEP) {
+        stage(ra, 0);
+        lds_sync();
+        fetch(ra, kb + 2 * KSTEP);
+        multiply(0, kb);
+        if (kb + KSTEP >= kb_end) break;
+        stage(rb, 1);
+        lds_sync();
+        fetch(rb, kb + 3 * KSTEP);
+        multiply(1, kb + KSTEP);
     }
     float *out = part + (size_t)blockIdx.y * ld_rows * N;
 #pragma unroll

@@ -188,6 +188,15 @@ template <typename T> __device__ inline T from_f32(float v);
 template <> __device__ inline float from_f32<float>(float v) { return v; }
 template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // round-to-nearest-even
 
+// Workgroup barrier for data exchanged through LDS only.  Unlike __syncthreads() it does not wait
+// for this wavefront's global loads in flight, only for its LDS operations; the empty asm
+// statements keep the compiler from moving memory accesses across it.
+__device__ __forceinline__ void lds_sync() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 __device__ inline int find_seq(const Batch &b, int row) {
     int i = 0;
     while (i + 1 < b.n_seqs && row >= b.s[i + 1].row0) ++i;
