@@ -145,11 +145,19 @@ int run_layers(vf_model *m, const Batch &b, const int32_t *tokens, int *tail_par
           if ((rc = vf_launch_gemm(m, lp.wo, m->o, m->part, d, nq, rows, 0, rows, R, p, st))) return rc; }
         { ProfScope ps(m, VF_SITE_SMALL, st);
           if ((rc = vf_launch_norm(m, lp.ffn_norm, m->x, m->part, p.ks, rows, R, st))) return rc; }
+        // many rows: one K range per workgroup, and the activation function is the GEMM's epilogue
         p = vf_gemm_plan(m, 2 * F, d, rows, 0);
+        if (p.tnb) {
+            p = vf_gemm_plan(m, 2 * F, d, rows, 1);
+            p.swiglu = 1;
+        }
         { ProfScope ps(m, VF_SITE_GATEUP, st);
-          if ((rc = vf_launch_gemm(m, lp.wgu, m->x, m->part, 2 * F, d, rows, 0, rows, R, p, st))) return rc; }
-        { ProfScope ps(m, VF_SITE_SMALL, st);
-          if ((rc = vf_launch_swiglu(m, m->part, p.ks, rows, R, st))) return rc; }
+          if ((rc = vf_launch_gemm(m, lp.wgu, m->x, p.swiglu ? (float *)m->a : m->part, 2 * F, d, rows, 0, rows, R, p,
+                                   st))) return rc; }
+        if (!p.swiglu) {
+            ProfScope ps(m, VF_SITE_SMALL, st);
+            if ((rc = vf_launch_swiglu(m, m->part, p.ks, rows, R, st))) return rc;
+        }
         p = vf_gemm_plan(m, d, F, rows, 0);
         { ProfScope ps(m, VF_SITE_DOWN, st);
           if ((rc = vf_launch_gemm(m, lp.wd, m->a, m->part, d, F, rows, 0, rows, R, p, st))) return rc; }

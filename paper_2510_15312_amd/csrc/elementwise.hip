@@ -4,6 +4,7 @@
 // fixed order.
 #include "vf_internal.h"
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 namespace {
 
 // ---- model creation -----------------------------------------------------------------------------
@@ -99,6 +100,65 @@ __global__ __launch_bounds__(256) void norm_kernel(float *__restrict__ h, const 
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
     for (int k = threadIdx.x; k < d; k += 256)
         x[act_index<T>(row, k, d, ncb)] = from_f32<T>(h[(size_t)row * d + k] * inv * gain[k]);
+}
+
+// The same for bf16 activations with d a multiple of 8: a thread owns runs of eight consecutive
+// elements (one 16-byte piece of an activation fragment), keeps them in registers between the
+// sum of squares and the scaling, and stores the piece whole.
+template <int VPT>
+__global__ __launch_bounds__(256) void norm_bf16_vec_kernel(float *__restrict__ h, const float *__restrict__ part,
+                                                            int nparts, int ld_rows, const float *__restrict__ gain,
+                                                            u32x4_t *__restrict__ x, int d, int ncb, float eps) {
+    __shared__ float red[4];
+    const int row = blockIdx.x;
+    float v[VPT][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int k0 = (threadIdx.x + i * 256) * 8;
+        if (k0 < d) {
+            float *hp = h + (size_t)row * d + k0;
+            const float4 a = *reinterpret_cast<const float4 *>(hp), b = *reinterpret_cast<const float4 *>(hp + 4);
+            v[i][0] = a.x; v[i][1] = a.y; v[i][2] = a.z; v[i][3] = a.w;
+            v[i][4] = b.x; v[i][5] = b.y; v[i][6] = b.z; v[i][7] = b.w;
+            for (int p = 0; p < nparts; ++p) {
+                const float *pp = part + ((size_t)p * ld_rows + row) * d + k0;
+                const float4 c = *reinterpret_cast<const float4 *>(pp), e = *reinterpret_cast<const float4 *>(pp + 4);
+                v[i][0] += c.x; v[i][1] += c.y; v[i][2] += c.z; v[i][3] += c.w;
+                v[i][4] += e.x; v[i][5] += e.y; v[i][6] += e.z; v[i][7] += e.w;
+            }
+            if (nparts) {
+                *reinterpret_cast<float4 *>(hp) = float4{v[i][0], v[i][1], v[i][2], v[i][3]};
+                *reinterpret_cast<float4 *>(hp + 4) = float4{v[i][4], v[i][5], v[i][6], v[i][7]};
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[i][j] = 0.f;
+        }
+    }
+    // the sum runs over k in the order of the scalar kernel's threads only up to rounding; both
+    // are sums of d squares in float32
+#pragma unroll
+    for (int i = 0; i < VPT; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ss += v[i][j] * v[i][j];
+    ss = block_sum(ss, red);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int k0 = (threadIdx.x + i * 256) * 8;
+        if (k0 >= d) continue;
+        const float4 ga = *reinterpret_cast<const float4 *>(gain + k0), gb = *reinterpret_cast<const float4 *>(gain + k0 + 4);
+        const float gv[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
+        u32x4_t out;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bf16_t lo = (bf16_t)(v[i][2 * j] * inv * gv[2 * j]), hi = (bf16_t)(v[i][2 * j + 1] * inv * gv[2 * j + 1]);
+            out[j] = (unsigned)__builtin_bit_cast(unsigned short, lo) | ((unsigned)__builtin_bit_cast(unsigned short, hi) << 16);
+        }
+        const int kb = k0 >> 5, lane = (((k0 >> 3) & 3) << 4) | (row & 15);
+        x[((size_t)kb * ncb + (row >> 4)) * 64 + lane] = out;
+    }
 }
 
 // QKV epilogue: one thread per (row, head, rotary pair).  Heads 0..Hq-1 are q, then Hkv k heads,
@@ -268,7 +328,14 @@ int vf_launch_embed(const vf_model *m, const Batch &b, const int32_t *tokens, hi
 int vf_launch_norm(const vf_model *m, const float *gain, void *x_out, const float *part, int nparts, int rows,
                    int ld_rows, hipStream_t st) {
     const int ncb = (rows + 15) >> 4;
-    if (m->cfg.dtype == VF_BF16)
+    const int d = m->cfg.d_model;
+    if (m->cfg.dtype == VF_BF16 && d % 8 == 0 && d <= 2048)
+        hipLaunchKernelGGL(norm_bf16_vec_kernel<1>, dim3(rows), dim3(256), 0, st, m->h, part, nparts, ld_rows, gain,
+                           (u32x4_t *)x_out, d, ncb, m->cfg.rms_eps);
+    else if (m->cfg.dtype == VF_BF16 && d % 8 == 0 && d <= 4096)
+        hipLaunchKernelGGL(norm_bf16_vec_kernel<2>, dim3(rows), dim3(256), 0, st, m->h, part, nparts, ld_rows, gain,
+                           (u32x4_t *)x_out, d, ncb, m->cfg.rms_eps);
+    else if (m->cfg.dtype == VF_BF16)
         hipLaunchKernelGGL(norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, m->h, part, nparts, ld_rows, gain,
                            (bf16_t *)x_out, m->cfg.d_model, ncb, m->cfg.rms_eps);
     else
@@ -330,7 +397,6 @@ int vf_launch_state_add(int32_t *state, int idx, int32_t delta, hipStream_t st) 
 }
 
 namespace {
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 // Every thread streams 16-byte pieces at a stride of the whole grid; the xor of what it read goes to a
 // word nobody reads unless it is a magic value (so the loads cannot be dropped).
 __global__ __launch_bounds__(512) void stream_read_kernel(const u32x4_t *__restrict__ p, size_t n, int32_t *sink) {

@@ -12,6 +12,7 @@
 namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int GEMM_WAVES = 4;
 constexpr int PREFETCH = 4;   // weight fragments in flight per stream and wavefront
@@ -116,10 +117,15 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_bf16_kernel(
 // the MFMAs through two register sets; they are never predicated (addresses past the end are
 // clamped and what they fetch is not used), so the compiler waits for exactly the set it stores,
 // and the barrier orders LDS traffic only.
-template <int TNB, int MB, int KSTEP>
+//
+// SWIGLU (gate/up matrix, no K split): instead of partial sums the kernel writes
+// a = bf16(silu(gate) * up) in activation layout.  Weight block 2j holds gate columns 16j.. and
+// block 2j+1 the matching up columns, so a pair of accumulators of one lane holds both factors.
+template <int TNB, int MB, int KSTEP, bool SWIGLU>
 __global__ __launch_bounds__(256) void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp,
                                                         float *__restrict__ part, int N, int KB, int ncb, int row_lo,
                                                         int row_hi, int ld_rows, int kb_per_split) {
+    static_assert(!SWIGLU || TNB % 2 == 0, "gate and up blocks come in pairs");
     constexpr int NF = TNB + MB;               // fragments per 32-wide k-block
     constexpr int NL = KSTEP * NF * 64 / 256;  // 16-byte loads per thread and stage
     static_assert(KSTEP * NF * 64 % 256 == 0, "a stage is a whole number of loads per thread");
@@ -194,15 +200,43 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(const u32x4 *__restrict_
         fetch(rb, kb + 3 * KSTEP);
         multiply(1, kb + KSTEP);
     }
-    float *out = part + (size_t)blockIdx.y * ld_rows * N;
+    if constexpr (SWIGLU) {
+        u32x2 *a_out = reinterpret_cast<u32x2 *>(part);  // [kb][cb][lane] fragments of 16 bytes, two halves each
+        const int g4 = lane >> 4;
 #pragma unroll
-    for (int n = 0; n < TNB; ++n) {
-        if (nb0 + n >= NBt) break;
+        for (int n = 0; n < TNB; n += 2) {
+            if (nb0 + n + 1 >= NBt) break;
+            const int fb = (nb0 + n) >> 1;  // 16-wide block of a: columns 16*fb + 4*g4 + j
+            const int lane_out = ((((fb & 1) << 1) | (g4 >> 1)) << 4) | (lane & 15);
 #pragma unroll
-        for (int c = 0; c < WC; ++c) {
-            const int row = (cb0 + wave * WC + c) * 16 + (lane & 15);
-            if (row >= row_lo && row < row_hi)
-                *reinterpret_cast<floatx4 *>(out + (size_t)row * N + (nb0 + n) * 16 + (lane >> 4) * 4) = acc[n][c];
+            for (int c = 0; c < WC; ++c) {
+                const int cb = cb0 + wave * WC + c, row = cb * 16 + (lane & 15);
+                if (row < row_lo || row >= row_hi) continue;
+                float o[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float gt = acc[n][c][j], up = acc[n + 1][c][j];
+                    o[j] = gt / (1.0f + expf(-gt)) * up;
+                }
+                u32x2 packed;
+                packed[0] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)o[0]) |
+                            ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)o[1]) << 16);
+                packed[1] = (unsigned)__builtin_bit_cast(unsigned short, (bf16_t)o[2]) |
+                            ((unsigned)__builtin_bit_cast(unsigned short, (bf16_t)o[3]) << 16);
+                a_out[((((size_t)(fb >> 1) * ncb + cb) * 64 + lane_out) << 1) | (g4 & 1)] = packed;
+            }
+        }
+    } else {
+        float *out = part + (size_t)blockIdx.y * ld_rows * N;
+#pragma unroll
+        for (int n = 0; n < TNB; ++n) {
+            if (nb0 + n >= NBt) break;
+#pragma unroll
+            for (int c = 0; c < WC; ++c) {
+                const int row = (cb0 + wave * WC + c) * 16 + (lane & 15);
+                if (row >= row_lo && row < row_hi)
+                    *reinterpret_cast<floatx4 *>(out + (size_t)row * N + (nb0 + n) * 16 + (lane >> 4) * 4) = acc[n][c];
+            }
         }
     }
 }
@@ -257,7 +291,7 @@ int launch_bf16(const vf_model *m, const void *W, const void *X, float *part, in
 }  // namespace
 
 GemmPlan vf_gemm_plan(const vf_model *m, int N, int K, int rows, int force_single) {
-    GemmPlan p{1, 1, 0};
+    GemmPlan p{1, 1, 0, 0};
     if (m->cfg.dtype == VF_F32) return p;
     const int NBt = N >> 4, KB = K >> 5;
     if (rows > 64 && m->fast_path) {
@@ -293,12 +327,19 @@ int vf_launch_gemm(const vf_model *m, const void *W, const void *X, float *part,
         const int cbs = ((row_hi + 15) >> 4) - (row_lo >> 4);
         const int mb = plan.tnb == 8 ? 16 : 8;
         dim3 grid((NBt + plan.tnb - 1) / plan.tnb, plan.ks, (cbs + mb - 1) / mb);
-        if (plan.tnb == 8)
-            hipLaunchKernelGGL((gemm_rows_kernel<8, 16, 1>), grid, dim3(256), 0, st, (const u32x4 *)W, (const u32x4 *)X,
-                               part, N, KB, ncb, row_lo, row_hi, ld_rows, kbps);
-        else
-            hipLaunchKernelGGL((gemm_rows_kernel<4, 8, 2>), grid, dim3(256), 0, st, (const u32x4 *)W, (const u32x4 *)X,
-                               part, N, KB, ncb, row_lo, row_hi, ld_rows, kbps);
+        auto go = [&](auto kern) {
+            hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, (const u32x4 *)W, (const u32x4 *)X, part, N, KB, ncb,
+                               row_lo, row_hi, ld_rows, kbps);
+        };
+        if (plan.swiglu) {
+            if (plan.ks != 1) return vf_fail(VF_ERR_ARG, "the fused SwiGLU epilogue takes no K split");
+            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, 1, true>);
+            else go(gemm_rows_kernel<4, 8, 2, true>);
+        } else if (plan.tnb == 8) {
+            go(gemm_rows_kernel<8, 16, 1, false>);
+        } else {
+            go(gemm_rows_kernel<4, 8, 2, false>);
+        }
         VF_LAUNCH_CHECK("gemm_rows");
         return VF_OK;
     }

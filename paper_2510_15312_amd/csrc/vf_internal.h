@@ -208,6 +208,7 @@ struct GemmPlan {
     int ks;        // K splits (partials)
     int nbw;       // n-blocks per wavefront
     int tnb;       // > 0: many-row kernel with this many weight blocks per workgroup
+    int swiglu;    // many-row kernel only: write bf16(silu(gate) * up) in activation layout, not partials
 };
 GemmPlan vf_gemm_plan(const vf_model *m, int N, int K, int rows, int force_single);
 // Y partials [ks][R][N] (R = ld_rows) for rows [row_lo, row_hi) of X.
