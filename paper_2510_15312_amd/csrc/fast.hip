@@ -25,7 +25,7 @@ namespace {
 // NB: 16-row activation blocks (rows <= 16*NB); UB: weight blocks per unit; PD: fragments in flight
 // per weight stream and wavefront; NW: wavefronts per workgroup.
 template <int NB, int UB, int PD, int EPI, int NW>
-__global__ __launch_bounds__(NW * 64) void gemm_fast_kernel(FastGemm g, Batch b) {
+__global__ __launch_bounds__(NW * 64) VF_MFMA_KERNEL void gemm_fast_kernel(FastGemm g, Batch b) {
     constexpr int FAST_THREADS = NW * 64, FAST_WAVES = NW;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     u32x4 *xs = reinterpret_cast<u32x4 *>(smem_raw);
@@ -280,7 +280,7 @@ __global__ __launch_bounds__(256) void embed_fast_kernel(const bf16_t *__restric
 // ---- attention ----------------------------------------------------------------------------------
 // Few rows: one workgroup per (key slice, kv head, sequence); partial results per slice.
 template <int HD>
-__global__ __launch_bounds__(256) void attn_fast_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
+__global__ __launch_bounds__(256) VF_MFMA_KERNEL void attn_fast_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
                                                         float *__restrict__ part, int hq, int hkv, int n_splits,
                                                         float scale_log2e) {
     constexpr int KD = HD / 32, DB = HD / 16, REC = HD + ATTF_STRIDE_PAD;

@@ -23,7 +23,7 @@ __device__ inline u32x4 load_stream(const u32x4 *p) { return __builtin_nontempor
 
 // NB: 16-row activation blocks handled per pass; NBW: weight n-blocks per wavefront.
 template <int NB, int NBW>
-__global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_bf16_kernel(
+__global__ __launch_bounds__(GEMM_WAVES * 64) VF_MFMA_KERNEL void gemm_bf16_kernel(
     const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp, float *__restrict__ part, int N,
     int KB, int ncb, int row_lo, int row_hi, int ld_rows, int kb_per_split) {
     constexpr int KC = Chunk<NB>::KC;
@@ -111,25 +111,42 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) void gemm_bf16_kernel(
     }
 }
 
-// Many rows (a prefill chunk): workgroup tile = 16*MB rows x TNB weight blocks, four wavefronts
-// of 4*MB rows each.  Per K step of KSTEP 32-wide k-blocks the weight and activation fragments go
-// through a double-buffered LDS stage, one barrier per step.  Global loads run two steps ahead of
-// the MFMAs through two register sets; they are never predicated (addresses past the end are
-// clamped and what they fetch is not used), so the compiler waits for exactly the set it stores,
-// and the barrier orders LDS traffic only.
+// Many rows (a prefill chunk): workgroup tile = 16*MB rows x TNB weight blocks, NW wavefronts
+// of 16*MB/NW rows each.  Per K step of KSTEP 32-wide k-blocks the weight and activation fragments
+// go through a double-buffered LDS stage, one barrier per step.  What bounds this kernel is the
+// number of bytes a compute unit has in flight, so global loads run NSETS steps ahead of the MFMAs
+// through NSETS register sets; they are never predicated (addresses past the end are clamped and
+// what they fetch is not used), so the wait before a set's LDS stores leaves the other sets' loads
+// in flight, and the barrier orders LDS traffic only.
 //
 // SWIGLU (gate/up matrix, no K split): instead of partial sums the kernel writes
 // a = bf16(silu(gate) * up) in activation layout.  Weight block 2j holds gate columns 16j.. and
 // block 2j+1 the matching up columns, so a pair of accumulators of one lane holds both factors.
-template <int TNB, int MB, int KSTEP, bool SWIGLU>
-__global__ __launch_bounds__(256) void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp,
-                                                        float *__restrict__ part, int N, int KB, int ncb, int row_lo,
-                                                        int row_hi, int ld_rows, int kb_per_split) {
+// wavefronts per workgroup and register sets of the two tile shapes
+#ifndef ROWS_NW_WIDE
+#define ROWS_NW_WIDE 8
+#endif
+#ifndef ROWS_SETS_WIDE
+#define ROWS_SETS_WIDE 4
+#endif
+#ifndef ROWS_NW_NARROW
+#define ROWS_NW_NARROW 4
+#endif
+#ifndef ROWS_SETS_NARROW
+#define ROWS_SETS_NARROW 2
+#endif
+template <int TNB, int MB, int KSTEP, int NW, int NSETS, bool SWIGLU>
+__global__ __launch_bounds__(NW * 64) VF_MFMA_KERNEL
+void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp, float *__restrict__ part, int N,
+                      int KB, int ncb, int row_lo, int row_hi, int ld_rows, int kb_per_split) {
     static_assert(!SWIGLU || TNB % 2 == 0, "gate and up blocks come in pairs");
-    constexpr int NF = TNB + MB;               // fragments per 32-wide k-block
-    constexpr int NL = KSTEP * NF * 64 / 256;  // 16-byte loads per thread and stage
-    static_assert(KSTEP * NF * 64 % 256 == 0, "a stage is a whole number of loads per thread");
-    constexpr int WC = MB / 4;                 // activation blocks per wavefront
+    static_assert(NSETS % 2 == 0, "set s is staged in LDS buffer s & 1");
+    constexpr int NT = NW * 64;
+    constexpr int NF = TNB + MB;              // fragments per 32-wide k-block
+    constexpr int NL = KSTEP * NF * 64 / NT;  // 16-byte loads per thread and stage
+    static_assert(KSTEP * NF * 64 % NT == 0, "a stage is a whole number of loads per thread");
+    static_assert(MB % NW == 0, "whole activation blocks per wavefront");
+    constexpr int WC = MB / NW;               // activation blocks per wavefront
     __shared__ u32x4 lds[2][KSTEP * NF * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int NBt = N >> 4;
@@ -148,7 +165,7 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(const u32x4 *__restrict_
     int half_of[NL];
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-        const int idx = tid + i * 256, rem = idx % (NF * 64), f = rem >> 6, l = rem & 63;
+        const int idx = tid + i * NT, rem = idx % (NF * 64), f = rem >> 6, l = rem & 63;
         half_of[i] = idx / (NF * 64);
         if (f < TNB) {
             src[i] = Wp + (size_t)min(nb0 + f, NBt - 1) * KB * 64 + l;   // rows past N: a valid block, result dropped
@@ -164,41 +181,58 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(const u32x4 *__restrict_
     };
     auto stage = [&](const u32x4 (&r)[NL], int buf) {
 #pragma unroll
-        for (int i = 0; i < NL; ++i) lds[buf][tid + i * 256] = r[i];
+        for (int i = 0; i < NL; ++i) lds[buf][tid + i * NT] = r[i];
     };
-    auto multiply = [&](int buf, int kb) {
+    // kb_limit: k-blocks from here on do not exist (what was fetched for them came from a clamped
+    // address); the main loop passes a limit no step reaches, which leaves no test in its code
+    auto multiply = [&](int buf, int kb, int kb_limit) {
 #pragma unroll
         for (int half = 0; half < KSTEP; ++half) {
-            if (kb + half < kb_end) {
-                const u32x4 *st = lds[buf] + half * NF * 64;
-                bf16x8 bfr[WC];
+            if (kb + half >= kb_limit) continue;
+            const u32x4 *st = lds[buf] + half * NF * 64;
+            bf16x8 bfr[WC];
 #pragma unroll
-                for (int c = 0; c < WC; ++c) bfr[c] = __builtin_bit_cast(bf16x8, st[(TNB + wave * WC + c) * 64 + lane]);
+            for (int c = 0; c < WC; ++c) bfr[c] = __builtin_bit_cast(bf16x8, st[(TNB + wave * WC + c) * 64 + lane]);
 #pragma unroll
-                for (int n = 0; n < TNB; ++n) {
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, st[n * 64 + lane]);
+            for (int n = 0; n < TNB; ++n) {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, st[n * 64 + lane]);
 #pragma unroll
-                    for (int c = 0; c < WC; ++c)
-                        acc[n][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bfr[c], acc[n][c], 0, 0, 0);
-                }
+                for (int c = 0; c < WC; ++c)
+                    acc[n][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bfr[c], acc[n][c], 0, 0, 0);
             }
         }
     };
-    u32x4 ra[NL], rb[NL];
-    fetch(ra, kb_begin);
-    fetch(rb, kb_begin + KSTEP);
-    // a buffer is written again two steps later, behind the barrier of the step in between, which
-    // every wavefront reaches only after its MFMAs on that buffer
-    for (int kb = kb_begin; kb < kb_end; kb += 2 * KSTEP) {
-        stage(ra, 0);
-        lds_sync();
-        fetch(ra, kb + 2 * KSTEP);
-        multiply(0, kb);
-        if (kb + KSTEP >= kb_end) break;
-        stage(rb, 1);
-        lds_sync();
-        fetch(rb, kb + 3 * KSTEP);
-        multiply(1, kb + KSTEP);
+    u32x4 r[NSETS][NL];
+#pragma unroll
+    for (int s = 0; s < NSETS; ++s) fetch(r[s], kb_begin + s * KSTEP);
+    // Whole groups of NSETS steps first.  An LDS buffer is written again two steps later, behind
+    // the barrier of the step in between, which every wavefront reaches only after its MFMAs on
+    // that buffer.  The scheduling barriers keep each step's order: stores of its set (the only
+    // wait for loads), barrier, the set's next loads, then the MFMAs that hide them.
+    constexpr int NEVER = 0x7fffffff;
+    const int ngroups = (kb_end - kb_begin) / (NSETS * KSTEP);
+    int kb = kb_begin;
+    for (int g = 0; g < ngroups; ++g) {
+#pragma unroll
+        for (int s = 0; s < NSETS; ++s) {
+            stage(r[s], s & 1);
+            lds_sync();
+            fetch(r[s], kb + NSETS * KSTEP);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(s & 1, 0, NEVER);
+            __builtin_amdgcn_sched_barrier(0);
+            kb += KSTEP;
+        }
+    }
+    // the remaining k-blocks (less than a group) are already in the register sets
+#pragma unroll
+    for (int s = 0; s < NSETS; ++s) {
+        if (kb < kb_end) {
+            stage(r[s], s & 1);
+            lds_sync();
+            multiply(s & 1, kb, kb_end);
+            kb += KSTEP;
+        }
     }
     if constexpr (SWIGLU) {
         u32x2 *a_out = reinterpret_cast<u32x2 *>(part);  // [kb][cb][lane] fragments of 16 bytes, two halves each
@@ -327,18 +361,18 @@ int vf_launch_gemm(const vf_model *m, const void *W, const void *X, float *part,
         const int cbs = ((row_hi + 15) >> 4) - (row_lo >> 4);
         const int mb = plan.tnb == 8 ? 16 : 8;
         dim3 grid((NBt + plan.tnb - 1) / plan.tnb, plan.ks, (cbs + mb - 1) / mb);
-        auto go = [&](auto kern) {
-            hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, (const u32x4 *)W, (const u32x4 *)X, part, N, KB, ncb,
+        auto go = [&](auto kern, int nw) {
+            hipLaunchKernelGGL(kern, grid, dim3(nw * 64), 0, st, (const u32x4 *)W, (const u32x4 *)X, part, N, KB, ncb,
                                row_lo, row_hi, ld_rows, kbps);
         };
         if (plan.swiglu) {
             if (plan.ks != 1) return vf_fail(VF_ERR_ARG, "the fused SwiGLU epilogue takes no K split");
-            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, 1, true>);
-            else go(gemm_rows_kernel<4, 8, 2, true>);
+            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, 1, ROWS_NW_WIDE, ROWS_SETS_WIDE, true>, ROWS_NW_WIDE);
+            else go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, true>, ROWS_NW_NARROW);
         } else if (plan.tnb == 8) {
-            go(gemm_rows_kernel<8, 16, 1, false>);
+            go(gemm_rows_kernel<8, 16, 1, ROWS_NW_WIDE, ROWS_SETS_WIDE, false>, ROWS_NW_WIDE);
         } else {
-            go(gemm_rows_kernel<4, 8, 2, false>);
+            go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, false>, ROWS_NW_NARROW);
         }
         VF_LAUNCH_CHECK("gemm_rows");
         return VF_OK;

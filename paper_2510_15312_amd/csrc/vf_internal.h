@@ -188,6 +188,12 @@ template <typename T> __device__ inline T from_f32(float v);
 template <> __device__ inline float from_f32<float>(float v) { return v; }
 template <> __device__ inline bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // round-to-nearest-even
 
+// Kernels that keep MFMA accumulators live across a loop ask for at least two wavefronts per SIMD:
+// within that register budget (256 per lane) the compiler places accumulators in ordinary vector
+// registers and updates them in place; with the whole file at its disposal it moves them to and
+// from accumulation registers around every MFMA.
+#define VF_MFMA_KERNEL __attribute__((amdgpu_waves_per_eu(2)))
+
 // Workgroup barrier for data exchanged through LDS only.  Unlike __syncthreads() it does not wait
 // for this wavefront's global loads in flight, only for its LDS operations; the empty asm
 // statements keep the compiler from moving memory accesses across it.
