@@ -12,6 +12,8 @@ Paper anchors (section / table):
     the first mismatch are discarded"  -- Sec. 3, "NPU-only decoding ..."
   * x = [T, x_1..x_n], predictions y = [y_1..y_{n+1}], accepted prefix
     x_1..x_{e-1}, y_e                       -- Sec. 4.3, empirical analysis
+  * reuse of rejected draft tokens: longest run after the rejection on which
+    draft and prediction agree              -- Sec. 4.3, Eq. (reuse), Table "cases"
   * fixed-size chunked prefill              -- Sec. 2 / Sec. 4.1
   * "executing the short graph several times equals one long execution"
                                             -- Sec. 4.1 (equivalence insight)
@@ -23,8 +25,9 @@ cross-check; none is "parity unpinned".
 from .numfmt import round_bf16
 from .transformer import ModelSpec, Weights, KVCache, forward, prefill, verify
 from .acceptance import greedy_accept, stochastic_accept, first_token
+from .reuse import reuse_segment, ReusePool
 
 __all__ = [
     "round_bf16", "ModelSpec", "Weights", "KVCache", "forward", "prefill",
-    "verify", "greedy_accept", "stochastic_accept", "first_token",
+    "verify", "greedy_accept", "stochastic_accept", "first_token", "reuse_segment", "ReusePool",
 ]
