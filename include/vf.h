@@ -204,6 +204,43 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
               const float *logits_dev, int32_t *n_accept_dev, int32_t *out_tokens_dev,
               int32_t *y_dev, void *stream);
 
+/* ---- reuse of rejected draft tokens (next to the three operations) --------------------------- */
+
+/* The segment of a rejected draft worth keeping (paper Sec. 4.3, "Reuse strategy", Eq. (reuse)):
+ * per sequence b with drafts x_1..x_k = tokens_dev[row_off[b]+1 ..], predictions
+ * y_i = y_dev[row_off[b] + i - 1] (what vf_accept wrote) and a_b = n_accept_dev[b] accepted
+ * drafts, i.e. a rejection at e = a_b + 1, finds the longest run of positions i in (e, k] with
+ * x_i == y_i, the earliest among runs of equal length, and writes
+ *   seg_dev[2b] = its first position (1-based draft index), seg_dev[2b+1] = its length;
+ * both 0 when a_b == k or no position agrees.  All pointers but row_off_host are device
+ * memory (int32); nothing else is read or written; asynchronous on `stream`. */
+int vf_reuse_select(int n_seqs, const int32_t *tokens_dev, const int32_t *row_off_host,
+                    const int32_t *y_dev, const int32_t *n_accept_dev, int32_t *seg_dev, void *stream);
+
+/* The segment held between steps (paper Sec. 4.3: kept for at least one step, dropped once its
+ * lifetime or the total draft length passes a limit; the limit on the length is 32, Sec. 5.1).
+ * Plain host memory owned by the caller; the functions touch no device.  One segment is held:
+ * a newly found one replaces it only if it is longer, and then starts a new lifetime. */
+typedef struct {
+    int32_t tokens[VF_MAX_DRAFTS];
+    int32_t len;        /* tokens held (0 = none)                          */
+    int32_t age;        /* verify steps since the held segment was found   */
+    int32_t max_age;    /* the segment is dropped when age exceeds this    */
+    int32_t cap;        /* largest total number of drafts of a step        */
+} vf_reuse_pool;
+
+/* 0 <= max_age, 1 <= cap <= VF_MAX_DRAFTS. */
+int vf_reuse_pool_init(vf_reuse_pool *p, int max_age, int cap);
+/* After a verify step whose drafts were drafts_host[0..n_drafts) and whose segment
+ * (seg_start, seg_len) came from vf_reuse_select: ages the held segment by one step, drops it
+ * past max_age, then takes the new one if it is longer. */
+int vf_reuse_pool_update(vf_reuse_pool *p, const int32_t *drafts_host, int n_drafts, int seg_start,
+                         int seg_len);
+/* Appends the held segment to the n_fresh drafts in drafts_host (room for cap entries) if the
+ * total stays within cap; a segment that does not fit is dropped, not cut.  Returns the new
+ * number of drafts (>= n_fresh), or a negative VF_ERR_* code. */
+int vf_reuse_pool_extend(vf_reuse_pool *p, int32_t *drafts_host, int n_fresh);
+
 /* ---- options ---------------------------------------------------------------------------------- */
 
 /* VF_OPT_FAST_PATH (default 1): vf_verify on a bfloat16 model with at most 48 rows in total runs

@@ -26,6 +26,7 @@ EXPORTS = [
     "vf_seq_state_bytes", "vf_kv_bytes", "vf_seq_create", "vf_seq_destroy", "vf_seq_set_len",
     "vf_seq_set_pending", "vf_seq_get_state", "vf_kv_read", "vf_kv_write", "vf_prefill_chunk", "vf_verify",
     "vf_accept", "vf_profile", "vf_profile_read", "vf_set_option", "vf_stream_read",
+    "vf_reuse_select", "vf_reuse_pool_init", "vf_reuse_pool_update", "vf_reuse_pool_extend",
 ]
 SITES = ["qkv", "o", "gateup", "down", "head", "attn", "small", "accept", "step"]
 
@@ -58,6 +59,11 @@ class vf_accept_params(C.Structure):
                 ("u_dev", C.c_void_p)]
 
 
+class vf_reuse_pool(C.Structure):
+    _fields_ = [("tokens", C.c_int32 * VF_MAX_DRAFTS)] + \
+               [(n, C.c_int32) for n in ("len", "age", "max_age", "cap")]
+
+
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2510_15312_amd.build)")
@@ -85,6 +91,10 @@ def _load():
         "vf_profile": (C.c_int, [vp, C.c_int]),
         "vf_stream_read": (C.c_int, [vp, C.POINTER(sz), vp]),
         "vf_profile_read": (C.c_int, [vp, C.POINTER(C.c_float), C.POINTER(i32)]),
+        "vf_reuse_select": (C.c_int, [C.c_int, vp, C.POINTER(i32), vp, vp, vp, vp]),
+        "vf_reuse_pool_init": (C.c_int, [C.POINTER(vf_reuse_pool), C.c_int, C.c_int]),
+        "vf_reuse_pool_update": (C.c_int, [C.POINTER(vf_reuse_pool), C.POINTER(i32), C.c_int, C.c_int, C.c_int]),
+        "vf_reuse_pool_extend": (C.c_int, [C.POINTER(vf_reuse_pool), C.POINTER(i32), C.c_int]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -246,6 +256,33 @@ def vf_accept(model, seqs, tokens, row_off, params, n_accept, out_tokens, y, log
                                  u.data_ptr() if u is not None else None)
     _check(lib.vf_accept(model.handle, hs, len(seqs), _ptr(tokens), ro, ps, _ptr(logits), _ptr(n_accept),
                          _ptr(out_tokens), _ptr(y), _stream()))
+
+
+def vf_reuse_select(tokens, row_off, y, n_accept, seg):
+    """tokens, y int32[total_rows], n_accept int32[n_seqs], seg int32[2 * n_seqs]: device tensors."""
+    ro = (C.c_int32 * len(row_off))(*[int(r) for r in row_off])
+    _check(lib.vf_reuse_select(len(row_off) - 1, _ptr(tokens), ro, _ptr(y), _ptr(n_accept), _ptr(seg), _stream()))
+
+
+def vf_reuse_pool_init(max_age, cap=VF_MAX_DRAFTS):
+    pool = vf_reuse_pool()
+    _check(lib.vf_reuse_pool_init(C.byref(pool), int(max_age), int(cap)))
+    return pool
+
+
+def vf_reuse_pool_update(pool, drafts, seg_start, seg_len):
+    """drafts: host ints, the drafts of the step the segment was found in."""
+    arr = (C.c_int32 * max(1, len(drafts)))(*[int(t) for t in drafts])
+    _check(lib.vf_reuse_pool_update(C.byref(pool), arr, len(drafts), int(seg_start), int(seg_len)))
+
+
+def vf_reuse_pool_extend(pool, fresh):
+    """Returns the drafts of the next step: the fresh ones, then the held segment if it fits."""
+    arr = (C.c_int32 * VF_MAX_DRAFTS)(*[int(t) for t in fresh])
+    n = lib.vf_reuse_pool_extend(C.byref(pool), arr, len(fresh))
+    if n < 0:
+        _check(n)
+    return list(arr[:n])
 
 
 def vf_profile(model, enable):
