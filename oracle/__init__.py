@@ -14,6 +14,8 @@ Paper anchors (section / table):
     x_1..x_{e-1}, y_e                       -- Sec. 4.3, empirical analysis
   * reuse of rejected draft tokens: longest run after the rejection on which
     draft and prediction agree              -- Sec. 4.3, Eq. (reuse), Table "cases"
+  * "tree-structured drafts" verified in one pass (mechanics: tree.py)
+                                            -- Sec. 4, workflow
   * fixed-size chunked prefill              -- Sec. 2 / Sec. 4.1
   * "executing the short graph several times equals one long execution"
                                             -- Sec. 4.1 (equivalence insight)
@@ -26,8 +28,10 @@ from .numfmt import round_bf16
 from .transformer import ModelSpec, Weights, KVCache, forward, prefill, verify
 from .acceptance import greedy_accept, stochastic_accept, first_token
 from .reuse import reuse_segment, ReusePool
+from .tree import verify_tree, tree_greedy_accept, tree_stochastic_accept, compact
 
 __all__ = [
     "round_bf16", "ModelSpec", "Weights", "KVCache", "forward", "prefill",
     "verify", "greedy_accept", "stochastic_accept", "first_token", "reuse_segment", "ReusePool",
+    "verify_tree", "tree_greedy_accept", "tree_stochastic_accept", "compact",
 ]

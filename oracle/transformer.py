@@ -115,12 +115,30 @@ def silu(a):
     return a / (1.0 + np.exp(-a))
 
 
-def forward(spec: ModelSpec, w: Weights, cache: KVCache, tokens, dt=np.float64):
+def tree_depths(parents):
+    """Depth of every node of a draft tree given as parent row indices: parents[0] = -1 (the root,
+    the pending token), 0 <= parents[i] < i for the others."""
+    parents = [int(p) for p in parents]
+    if not parents or parents[0] != -1 or any(not 0 <= p < i for i, p in enumerate(parents) if i):
+        raise ValueError("parents must start with -1 and point to earlier rows")
+    depth = [0] * len(parents)
+    for i in range(1, len(parents)):
+        depth[i] = depth[parents[i]] + 1
+    return depth
+
+
+def forward(spec: ModelSpec, w: Weights, cache: KVCache, tokens, dt=np.float64, parents=None):
     """Run `tokens` (ids) at positions cache.len.. through the model.
 
     Appends their K/V rows to the cache and returns the logits [n, V] (dtype
     `dt`): row r is the model's prediction for the token after position
     cache.len + r.  `w` must already hold arrays of dtype `dt`.
+
+    parents (tree-structured drafts, Sec. 4 "tree-structured drafts"): row r is
+    a node of a token tree rooted at row 0.  It stands at the position of its
+    depth, cache.len + depth[r], sees the whole cache and, of the rows of this
+    call, only its ancestors and itself; its K/V go to cache row cache.len + r.
+    Row r then predicts the token after the root-to-r path.
     """
     tokens = np.asarray(tokens, dtype=np.int64)
     n = tokens.shape[0]
@@ -130,12 +148,24 @@ def forward(spec: ModelSpec, w: Weights, cache: KVCache, tokens, dt=np.float64):
     act = (lambda a: round_bf16(a)) if spec.dtype == "bf16" else (lambda a: a)
     hq, hkv, hd = spec.n_q_heads, spec.n_kv_heads, spec.head_dim
     group = hq // hkv
-    pos = p0 + np.arange(n)
+    if parents is None:
+        pos = p0 + np.arange(n)
+        # key t is visible to row r iff t <= pos[r]
+        visible = np.arange(p0 + n)[None, :] <= pos[:, None]
+    else:
+        if len(parents) != n:
+            raise ValueError("one parent per row")
+        pos = p0 + np.asarray(tree_depths(parents))
+        visible = np.zeros((n, p0 + n), dtype=bool)
+        visible[:, :p0] = True
+        for r in range(n):
+            a = r
+            while a >= 0:
+                visible[r, p0 + a] = True
+                a = int(parents[a])
     cos, sin = rope_tables(pos, hd, spec.rope_theta)
     cos, sin = cos.astype(dt), sin.astype(dt)
     scale = 1.0 / np.sqrt(np.float64(hd))
-    # key t is visible to row r iff t <= pos[r]
-    visible = np.arange(p0 + n)[None, :] <= pos[:, None]
 
     h = w.embed[tokens].astype(dt)
     for l, lw in enumerate(w.layers):
