@@ -113,6 +113,13 @@ def cpu_baseline(cfg, wd, ctx_len, k, temperature):
                       f"({times[0] * 1e3:.1f} ms), extrapolated linearly to {cfg.n_layers} layers"}
 
 
+def wl_depths(parents):
+    d = [0] * len(parents)
+    for i in range(1, len(parents)):
+        d[i] = d[parents[i]] + 1
+    return d
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -294,6 +301,29 @@ def main():
                           "step_vs_stream_read": round(gbs / stream_gbs, 4)}
     # determinism: the timed replay must have walked the recorded trajectory
     assert ln_end == lens[K], (ln_end, lens[K])
+    # the same step on tree-structured drafts: m rows as a random tree (chains with side branches),
+    # greedy acceptance with compaction of the accepted path; the length is put back before each step
+    trng = np.random.default_rng(15312)
+    parents = [-1] + [i - 1 if trng.random() > 0.5 else int(trng.integers(0, i)) for i in range(1, m)]
+    ttok = torch.as_tensor(trng.integers(0, V, m).astype(np.int32), device="cuda:0")
+    path_t = torch.zeros(m, dtype=torch.int32, device="cuda:0")
+    tparams = [(vf.VF_GREEDY, 0.0, None, None)]
+    reset()
+
+    def tree_step():
+        vf.vf_seq_set_len(seq, len0)
+        vf.vf_verify_tree(model, [seq], ttok, [0, m], parents)
+        vf.vf_accept_tree(model, [seq], ttok, [0, m], parents, tparams, n_acc, out_t, y_t, path_t)
+
+    for _ in range(3):
+        tree_step()
+    e0.record()
+    for _ in range(10):
+        tree_step()
+    e1.record()
+    torch.cuda.synchronize()
+    res["tree_verify"] = {"us_per_step": round(e0.elapsed_time(e1) * 100.0, 1), "rows": m,
+                          "depth": int(max(wl_depths(parents))), "acceptance": "greedy, path compacted"}
     if args.pmc_calibration:
         a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")
         b = torch.empty_like(a)

@@ -204,6 +204,43 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
               const float *logits_dev, int32_t *n_accept_dev, int32_t *out_tokens_dev,
               int32_t *y_dev, void *stream);
 
+/* ---- tree-structured drafts (next to the three operations) ---------------------------------- */
+
+/* Verify forward for drafts that form a token tree per sequence (paper Sec. 4, workflow:
+ * "iteratively constructs tree-structured drafts and verifies them").  Arguments as vf_verify,
+ * plus parent_host[total_rows] (HOST, int32): -1 for a sequence's first row (the pending token,
+ * root of its tree), otherwise the row, counted within the sequence, of the node's parent, which
+ * must be smaller than the node's own row.  Row r stands at position len + depth(r) (rotary
+ * angle), sees the whole cache and, of the call's rows, only its ancestors and itself, and
+ * predicts the token after its root path.  Its K/V go to cache row len + r; vf_accept_tree
+ * moves the accepted path into place.  A chain (parent r-1 for every r) is exactly vf_verify.
+ * VF_ERR_ARG for a malformed parent table; otherwise errors as vf_verify. */
+int vf_verify_tree(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+                   const int32_t *row_off_host, const int32_t *parent_host, float *logits_out_dev,
+                   void *stream);
+
+/* Acceptance over the tree, for the same seqs / tokens_dev / row_off_host / parent_host.  From the
+ * root, the walk moves to a child while one is accepted and emits one more token at the node
+ * where it stops:
+ *   VF_GREEDY      the child whose token equals the arg-max at the current node (the lowest row
+ *                  among children with equal tokens); the emitted token is that arg-max;
+ *   VF_STOCHASTIC  deterministic drafter only (q_dev must be NULL, else VF_ERR_UNSUPPORTED): the
+ *                  children are tried in row order against the residual r of the node's target
+ *                  distribution (r = p at first): child c with token x is kept when
+ *                  u[c-1] * sum(r) < r(x); a refused child's token is struck from r; the emitted
+ *                  token is drawn from r by inverse CDF with u[m_b + node].  For a chain this is
+ *                  vf_accept with a deterministic drafter.
+ * Outputs as vf_accept (n_accept_dev[b] = a_b accepted drafts, out_tokens_dev = their tokens then
+ * the emitted one, y_dev = arg-max of every row), plus
+ *   path_dev[row_off[b] + j] = row of the j-th node of the accepted path, j = 0..a_b (path[0] = 0),
+ *                              -1 beyond.
+ * On the device: the K/V rows of the path move to cache rows len_b + 1 .. len_b + a_b,
+ * len_b += 1 + a_b, pending_b = the emitted token. */
+int vf_accept_tree(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+                   const int32_t *row_off_host, const int32_t *parent_host,
+                   const vf_accept_params *params_host, const float *logits_dev, int32_t *n_accept_dev,
+                   int32_t *out_tokens_dev, int32_t *y_dev, int32_t *path_dev, void *stream);
+
 /* ---- reuse of rejected draft tokens (next to the three operations) --------------------------- */
 
 /* The segment of a rejected draft worth keeping (paper Sec. 4.3, "Reuse strategy", Eq. (reuse)):

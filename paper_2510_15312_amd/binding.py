@@ -27,6 +27,7 @@ EXPORTS = [
     "vf_seq_set_pending", "vf_seq_get_state", "vf_kv_read", "vf_kv_write", "vf_prefill_chunk", "vf_verify",
     "vf_accept", "vf_profile", "vf_profile_read", "vf_set_option", "vf_stream_read",
     "vf_reuse_select", "vf_reuse_pool_init", "vf_reuse_pool_update", "vf_reuse_pool_extend",
+    "vf_verify_tree", "vf_accept_tree",
 ]
 SITES = ["qkv", "o", "gateup", "down", "head", "attn", "small", "accept", "step"]
 
@@ -91,6 +92,9 @@ def _load():
         "vf_profile": (C.c_int, [vp, C.c_int]),
         "vf_stream_read": (C.c_int, [vp, C.POINTER(sz), vp]),
         "vf_profile_read": (C.c_int, [vp, C.POINTER(C.c_float), C.POINTER(i32)]),
+        "vf_verify_tree": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(i32), vp, vp]),
+        "vf_accept_tree": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(i32),
+                                     C.POINTER(vf_accept_params), vp, vp, vp, vp, vp, vp]),
         "vf_reuse_select": (C.c_int, [C.c_int, vp, C.POINTER(i32), vp, vp, vp, vp]),
         "vf_reuse_pool_init": (C.c_int, [C.POINTER(vf_reuse_pool), C.c_int, C.c_int]),
         "vf_reuse_pool_update": (C.c_int, [C.POINTER(vf_reuse_pool), C.POINTER(i32), C.c_int, C.c_int, C.c_int]),
@@ -256,6 +260,26 @@ def vf_accept(model, seqs, tokens, row_off, params, n_accept, out_tokens, y, log
                                  u.data_ptr() if u is not None else None)
     _check(lib.vf_accept(model.handle, hs, len(seqs), _ptr(tokens), ro, ps, _ptr(logits), _ptr(n_accept),
                          _ptr(out_tokens), _ptr(y), _stream()))
+
+
+def vf_verify_tree(model, seqs, tokens, row_off, parents, logits_out=None):
+    """As vf_verify; parents: host ints [total_rows], -1 for each sequence's first row, else the
+    parent's row within the sequence."""
+    hs, ro = _batch(seqs, row_off)
+    par = (C.c_int32 * len(parents))(*[int(p) for p in parents])
+    _check(lib.vf_verify_tree(model.handle, hs, len(seqs), _ptr(tokens), ro, par, _ptr(logits_out), _stream()))
+
+
+def vf_accept_tree(model, seqs, tokens, row_off, parents, params, n_accept, out_tokens, y, path, logits=None):
+    """As vf_accept, plus path int32[total_rows] (device): the rows of the accepted path."""
+    hs, ro = _batch(seqs, row_off)
+    par = (C.c_int32 * len(parents))(*[int(p) for p in parents])
+    ps = (vf_accept_params * len(seqs))()
+    for i, (mode, temp, q, u) in enumerate(params):
+        ps[i] = vf_accept_params(mode, temp, q.data_ptr() if q is not None else None,
+                                 u.data_ptr() if u is not None else None)
+    _check(lib.vf_accept_tree(model.handle, hs, len(seqs), _ptr(tokens), ro, par, ps, _ptr(logits), _ptr(n_accept),
+                              _ptr(out_tokens), _ptr(y), _ptr(path), _stream()))
 
 
 def vf_reuse_select(tokens, row_off, y, n_accept, seg):

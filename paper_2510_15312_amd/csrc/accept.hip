@@ -135,6 +135,7 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
         d.row = s.row0 + acc;
         d.q = (acc < k && a.q) ? a.q + (size_t)acc * V : nullptr;
         d.x_excl = (acc < k && !a.q) ? drafts[acc] : -1;
+        d.n_excl = 0;
         d.u = d.active ? (double)a.u[m + acc] : 0.0;
         d.t = t;
         draw[blockIdx.x] = d;
@@ -145,14 +146,119 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
     }
 }
 
+// Tree-structured drafts: the same row statistics, then one thread walks down from the root.
+// Greedy: move to the first child (in row order) whose token is the arg-max at the current node.
+// Stochastic, deterministic drafter: the children are tried in row order against the residual of
+// the node's target distribution p: child with token x is kept when u * (1 - struck mass) < r(x),
+// r(x) = p(x) unless an earlier refused sibling carried the same token; a refused child's token is
+// struck.  The walk ends at the node none of whose children is kept; the token emitted there is the
+// arg-max (greedy) or a draw from the residual (emit kernel, via the exclusion list).
+__global__ __launch_bounds__(256) void accept_tree_decide_kernel(
+    const float *__restrict__ logits, int V, Batch b, AcceptBatch ab, TreeDesc tree,
+    const int32_t *__restrict__ tokens, const float *__restrict__ smax, const int32_t *__restrict__ sidx,
+    const double *__restrict__ ssum, int32_t *__restrict__ n_accept, int32_t *__restrict__ out_tokens,
+    int32_t *__restrict__ y, int32_t *__restrict__ path_out, DrawDesc *__restrict__ draw) {
+    __shared__ double row_S[VF_MAX_DRAFTS + 1];
+    __shared__ float row_max[VF_MAX_DRAFTS + 1];
+    __shared__ int row_arg[VF_MAX_DRAFTS + 1];
+    __shared__ double px[VF_MAX_DRAFTS + 1];   // p of the parent node at this node's token
+    __shared__ int path[VF_MAX_DRAFTS + 1];
+    const SeqDesc &s = b.s[blockIdx.x];
+    const AcceptDesc &a = ab.a[blockIdx.x];
+    const int8_t *par = tree.parent[blockIdx.x];
+    const int m = s.nrows;
+    const double t = (double)a.temperature;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int r = wave; r < m; r += 4) {
+        const size_t o = (size_t)(s.row0 + r) * VF_STAT_CHUNKS + lane;  // one chunk per lane
+        const MaxIdx mine{smax[o], sidx[o]};
+        const MaxIdx best = wave_best(mine);
+        double S = 0.0;
+        if (a.mode == VF_STOCHASTIC) {
+            const double sm = ssum[o];
+            S = wave_sum(sm != 0.0 ? sm * exp(((double)mine.v - (double)best.v) / t) : 0.0);
+        }
+        if (lane == 0) {
+            row_S[r] = S;
+            row_max[r] = best.v;
+            row_arg[r] = best.i;
+            y[s.row0 + r] = best.i;
+        }
+    }
+    __syncthreads();
+    const int c = threadIdx.x;
+    if (c >= 1 && c < m) {
+        double v = 0.0;
+        const int x = tokens[s.row0 + c], pr = par[c];
+        if (a.mode == VF_STOCHASTIC && x >= 0 && x < V)
+            v = exp(((double)logits[(size_t)(s.row0 + pr) * V + x] - (double)row_max[pr]) / t) / row_S[pr];
+        px[c] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    DrawDesc &d = draw[blockIdx.x];
+    int acc = 0, cur = 0, n_excl = 0;
+    path[0] = 0;
+    while (true) {
+        int kept = -1;
+        n_excl = 0;
+        double struck = 0.0;
+        for (int ch = cur + 1; ch < m; ++ch) {
+            if (par[ch] != cur) continue;
+            const int x = tokens[s.row0 + ch];
+            if (a.mode == VF_GREEDY) {
+                if (x == row_arg[cur]) { kept = ch; break; }
+                continue;
+            }
+            bool dup = false;
+            for (int i = 0; i < n_excl; ++i) dup = dup || d.excl[i] == x;
+            const double rx = dup ? 0.0 : px[ch];
+            if ((double)a.u[ch - 1] * (1.0 - struck) < rx) { kept = ch; break; }
+            if (!dup && x >= 0 && x < V) {
+                d.excl[n_excl++] = x;
+                struck += px[ch];
+            }
+        }
+        if (kept < 0) break;
+        path[++acc] = kept;
+        cur = kept;
+    }
+    for (int j = 0; j < m; ++j) {
+        int v = -1;
+        if (j < acc) v = tokens[s.row0 + path[j + 1]];
+        else if (j == acc && a.mode == VF_GREEDY) v = row_arg[cur];
+        out_tokens[s.row0 + j] = v;
+        path_out[s.row0 + j] = j <= acc ? path[j] : -1;
+    }
+    n_accept[blockIdx.x] = acc;
+    d.zmax = (double)row_max[cur];
+    d.S = row_S[cur];
+    d.active = a.mode == VF_STOCHASTIC;
+    d.acc = acc;
+    d.row = s.row0 + cur;
+    d.q = nullptr;
+    d.x_excl = -1;
+    d.n_excl = n_excl;
+    d.u = d.active ? (double)a.u[m + cur] : 0.0;
+    d.t = t;
+    if (a.mode == VF_GREEDY) {
+        s.state[0] += 1 + acc;
+        s.state[1] = row_arg[cur];
+    }
+}
+
 // weight of id v in the draw at the deciding row:
-//   max(0, p_v - q_v)  (dense draft distribution),  p_v with p_x = 0  (one-hot drafter),
+//   max(0, p_v - q_v)  (dense draft distribution),  p_v with p_x = 0  (one-hot drafter; for a tree
+//   every refused child's token x),
 //   p_v  (bonus token / first token / every residual weight zero),  p_v = exp((z_v - zmax)/T) / S.
 __device__ inline double draw_weight(const float *__restrict__ z, const DrawDesc &d, int v, bool plain) {
     const double p = exp(((double)z[v] - d.zmax) / d.t) / d.S;
     if (plain) return p;
     if (d.q) return fmax(p - (double)d.q[v], 0.0);
-    return v == d.x_excl ? 0.0 : p;
+    if (v == d.x_excl) return 0.0;
+    for (int i = 0; i < d.n_excl; ++i)
+        if (v == d.excl[i]) return 0.0;
+    return p;
 }
 
 __device__ inline double chunk_weight_sum(const float *__restrict__ z, const DrawDesc &d, int v0, int v1,
@@ -170,7 +276,7 @@ __global__ __launch_bounds__(256) void draw_sums_kernel(const float *__restrict_
                                                         const DrawDesc *__restrict__ draw,
                                                         double *__restrict__ wsum) {
     __shared__ double rs[4];
-    const DrawDesc d = draw[blockIdx.y];
+    const DrawDesc &d = draw[blockIdx.y];
     if (!d.active) return;
     const int per = (V + VF_STAT_CHUNKS - 1) / VF_STAT_CHUNKS;
     const int v0 = min(V, (int)blockIdx.x * per), v1 = min(V, v0 + per);
@@ -186,7 +292,7 @@ __global__ __launch_bounds__(256) void accept_emit_kernel(const float *__restric
     __shared__ double seg[256];
     __shared__ double rs[4];
     __shared__ int result;
-    const DrawDesc d = draw[blockIdx.x];
+    const DrawDesc &d = draw[blockIdx.x];
     if (!d.active) return;
     const SeqDesc &s = b.s[blockIdx.x];
     const float *z = logits + (size_t)d.row * V;
@@ -274,6 +380,28 @@ int launch_all(const vf_model *m, const Batch &b, const AcceptBatch &ab, const i
 int vf_launch_accept(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
                      const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y, hipStream_t st) {
     return launch_all(m, b, ab, tokens, logits, n_accept, out_tokens, y, 1, st);
+}
+
+int vf_launch_accept_tree(const vf_model *m, const Batch &b, const AcceptBatch &ab, const TreeDesc &tree,
+                          const int32_t *tokens, const float *logits, int32_t *n_accept, int32_t *out_tokens,
+                          int32_t *y, int32_t *path, hipStream_t st) {
+    const int V = m->cfg.vocab;
+    hipLaunchKernelGGL(row_stats_kernel, dim3(VF_STAT_CHUNKS, b.total_rows), dim3(256), 0, st, logits, V, b, ab,
+                       m->stat_max, m->stat_idx, m->stat_sum);
+    VF_LAUNCH_CHECK("row_stats");
+    hipLaunchKernelGGL(accept_tree_decide_kernel, dim3(b.n_seqs), dim3(256), 0, st, logits, V, b, ab, tree, tokens,
+                       m->stat_max, m->stat_idx, m->stat_sum, n_accept, out_tokens, y, path, m->draw);
+    VF_LAUNCH_CHECK("accept_tree_decide");
+    bool any = false;
+    for (int i = 0; i < b.n_seqs; ++i) any = any || ab.a[i].mode == VF_STOCHASTIC;
+    if (!any) return VF_OK;
+    hipLaunchKernelGGL(draw_sums_kernel, dim3(VF_STAT_CHUNKS, b.n_seqs), dim3(256), 0, st, logits, V, m->draw,
+                       m->draw_sums);
+    VF_LAUNCH_CHECK("draw_sums");
+    hipLaunchKernelGGL(accept_emit_kernel, dim3(b.n_seqs), dim3(256), 0, st, logits, V, b, m->draw, m->draw_sums,
+                       out_tokens, 1);
+    VF_LAUNCH_CHECK("accept_emit");
+    return VF_OK;
 }
 
 // First generated token from one row of logits: arg-max (temperature 0) or a draw from

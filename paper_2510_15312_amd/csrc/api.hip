@@ -101,6 +101,8 @@ size_t carve_model(vf_model *m, char *base) {
     m->scratch_i32 = (int32_t *)cv.take(64 * 4);
     m->ss = (float *)cv.take((d / 16) * 64 * 4);
     m->counters = (int32_t *)cv.take(VF_N_COUNTERS * 4);
+    m->tree_anc = (tree_mask_t *)cv.take((size_t)R * 8);
+    m->tree_depth = (int32_t *)cv.take((size_t)R * 4);
     m->fz_ws = (char *)cv.take(vf_fused_workspace_bytes(c));
     return (cv.off + 255) & ~(size_t)255;
 }
@@ -122,7 +124,8 @@ SeqDesc describe(const vf_seq *s, int row0, int nrows) {
 // One pass of the decoder stack over the rows of `b`; leaves the residual stream in m->h with
 // the last down-projection still in (part, nparts) form: *tail_parts tells the caller how many
 // partial sums the final norm must add.
-int run_layers(vf_model *m, const Batch &b, const int32_t *tokens, int *tail_parts, hipStream_t st) {
+int run_layers(vf_model *m, const Batch &b, const int32_t *tokens, int *tail_parts, hipStream_t st,
+               bool tree = false) {
     const vf_config &c = m->cfg;
     const int rows = b.total_rows, R = rows;  // partials are laid out with ld = rows of this call
     const int d = c.d_model, F = c.d_ffn, nq = c.n_q_heads * c.head_dim, nkv = c.n_kv_heads * c.head_dim;
@@ -137,9 +140,9 @@ int run_layers(vf_model *m, const Batch &b, const int32_t *tokens, int *tail_par
         { ProfScope ps(m, VF_SITE_QKV, st);
           if ((rc = vf_launch_gemm(m, lp.wqkv, m->x, m->part, nq + 2 * nkv, d, rows, 0, rows, R, p, st))) return rc; }
         { ProfScope ps(m, VF_SITE_SMALL, st);
-          if ((rc = vf_launch_qkv_finish(m, b, l, m->part, p.ks, R, st))) return rc; }
+          if ((rc = vf_launch_qkv_finish(m, b, l, m->part, p.ks, R, tree ? m->tree_depth : nullptr, st))) return rc; }
         { ProfScope ps(m, VF_SITE_ATTN, st);
-          if ((rc = vf_launch_attention(m, b, l, st))) return rc; }
+          if ((rc = vf_launch_attention(m, b, l, tree ? m->tree_anc : nullptr, st))) return rc; }
         p = vf_gemm_plan(m, d, nq, rows, 0);
         { ProfScope ps(m, VF_SITE_O, st);
           if ((rc = vf_launch_gemm(m, lp.wo, m->o, m->part, d, nq, rows, 0, rows, R, p, st))) return rc; }
@@ -435,25 +438,48 @@ static int build_batch(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32
     return VF_OK;
 }
 
-int vf_verify(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
-              const int32_t *row_off_host, float *logits_out_dev, void *stream) {
+// parent_host (one entry per row of the call): -1 for the first row of a sequence, else the row,
+// counted within the sequence, of the parent node, which must come earlier.
+static int build_tree(const Batch &b, const int32_t *parent_host, TreeDesc *tree, const char *who) {
+    if (!parent_host) return vf_fail(VF_ERR_ARG, "%s: parent_host is NULL", who);
+    memset(tree, 0, sizeof(*tree));
+    for (int i = 0; i < b.n_seqs; ++i)
+        for (int r = 0; r < b.s[i].nrows; ++r) {
+            const int p = parent_host[b.s[i].row0 + r];
+            if (r == 0 ? p != -1 : (p < 0 || p >= r))
+                return vf_fail(VF_ERR_ARG, "%s: sequence %d row %d has parent %d", who, i, r, p);
+            tree->parent[i][r] = (int8_t)p;
+        }
+    return VF_OK;
+}
+
+static int verify_impl(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+                       const int32_t *row_off_host, const int32_t *parent_host, bool tree, float *logits_out_dev,
+                       void *stream, const char *who) {
     Batch b;
-    int rc = build_batch(m, seqs, n_seqs, row_off_host, &b, "vf_verify");
+    int rc = build_batch(m, seqs, n_seqs, row_off_host, &b, who);
     if (rc) return rc;
-    if (!tokens_dev) return vf_fail(VF_ERR_ARG, "vf_verify: tokens_dev is NULL");
+    if (!tokens_dev) return vf_fail(VF_ERR_ARG, "%s: tokens_dev is NULL", who);
     for (int i = 0; i < n_seqs; ++i)
         if (seqs[i]->len_ub + b.s[i].nrows > seqs[i]->capacity)
-            return vf_fail(VF_ERR_CAP, "vf_verify: sequence %d: %d + %d > capacity %d", i, seqs[i]->len_ub,
+            return vf_fail(VF_ERR_CAP, "%s: sequence %d: %d + %d > capacity %d", who, i, seqs[i]->len_ub,
                            b.s[i].nrows, seqs[i]->capacity);
     hipStream_t st = (hipStream_t)stream;
+    if (tree) {
+        TreeDesc td;
+        if ((rc = build_tree(b, parent_host, &td, who))) return rc;
+        if (m->cfg.head_dim != 64 && m->cfg.head_dim != 128)
+            return vf_fail(VF_ERR_UNSUPPORTED, "%s: head_dim %d (built for 64 and 128)", who, m->cfg.head_dim);
+        if ((rc = vf_launch_tree_prep(m, b, td, st))) return rc;
+    }
     float *dst = logits_out_dev ? logits_out_dev : m->logits;
     if (m->fast_path && m->persistent && vf_fused_ok(m, b)) {
-        if ((rc = vf_run_fused(m, b, tokens_dev, dst, st))) return rc;
-    } else if (m->fast_path && vf_fast_path_ok(m, b.total_rows)) {
+        if ((rc = vf_run_fused(m, b, tokens_dev, dst, tree, st))) return rc;
+    } else if (!tree && m->fast_path && vf_fast_path_ok(m, b.total_rows)) {
         if ((rc = vf_run_fast(m, b, tokens_dev, dst, st))) return rc;
     } else {
         int tail = 0;
-        if ((rc = run_layers(m, b, tokens_dev, &tail, st))) return rc;
+        if ((rc = run_layers(m, b, tokens_dev, &tail, st, tree))) return rc;
         if ((rc = run_head(m, b.total_rows, tail, 0, b.total_rows, dst, st))) return rc;
     }
     m->last_logits = dst;
@@ -461,28 +487,44 @@ int vf_verify(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
     return VF_OK;
 }
 
-int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
-              const int32_t *row_off_host, const vf_accept_params *params_host, const float *logits_dev,
-              int32_t *n_accept_dev, int32_t *out_tokens_dev, int32_t *y_dev, void *stream) {
+int vf_verify(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+              const int32_t *row_off_host, float *logits_out_dev, void *stream) {
+    return verify_impl(m, seqs, n_seqs, tokens_dev, row_off_host, nullptr, false, logits_out_dev, stream, "vf_verify");
+}
+
+int vf_verify_tree(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+                   const int32_t *row_off_host, const int32_t *parent_host, float *logits_out_dev, void *stream) {
+    return verify_impl(m, seqs, n_seqs, tokens_dev, row_off_host, parent_host, true, logits_out_dev, stream,
+                       "vf_verify_tree");
+}
+
+static int accept_impl(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+                       const int32_t *row_off_host, const int32_t *parent_host, bool tree,
+                       const vf_accept_params *params_host, const float *logits_dev, int32_t *n_accept_dev,
+                       int32_t *out_tokens_dev, int32_t *y_dev, int32_t *path_dev, void *stream, const char *who) {
     Batch b;
-    int rc = build_batch(m, seqs, n_seqs, row_off_host, &b, "vf_accept");
+    int rc = build_batch(m, seqs, n_seqs, row_off_host, &b, who);
     if (rc) return rc;
-    if (!tokens_dev || !params_host || !n_accept_dev || !out_tokens_dev || !y_dev)
-        return vf_fail(VF_ERR_ARG, "vf_accept: NULL argument");
+    if (!tokens_dev || !params_host || !n_accept_dev || !out_tokens_dev || !y_dev || (tree && !path_dev))
+        return vf_fail(VF_ERR_ARG, "%s: NULL argument", who);
     const float *logits = logits_dev ? logits_dev : m->last_logits;
-    if (!logits) return vf_fail(VF_ERR_ARG, "vf_accept: no logits (run vf_verify first or pass logits_dev)");
+    if (!logits) return vf_fail(VF_ERR_ARG, "%s: no logits (run the verify first or pass logits_dev)", who);
     if (!logits_dev && m->last_rows != b.total_rows)
-        return vf_fail(VF_ERR_ARG, "vf_accept: %d rows but the last verify had %d", b.total_rows, m->last_rows);
+        return vf_fail(VF_ERR_ARG, "%s: %d rows but the last verify had %d", who, b.total_rows, m->last_rows);
+    TreeDesc td;
+    if (tree && (rc = build_tree(b, parent_host, &td, who))) return rc;
     AcceptBatch ab;
     for (int i = 0; i < n_seqs; ++i) {
         const vf_accept_params &p = params_host[i];
-        if (p.mode != VF_GREEDY && p.mode != VF_STOCHASTIC) return vf_fail(VF_ERR_ARG, "vf_accept: mode %d", p.mode);
+        if (p.mode != VF_GREEDY && p.mode != VF_STOCHASTIC) return vf_fail(VF_ERR_ARG, "%s: mode %d", who, p.mode);
         if (p.mode == VF_STOCHASTIC) {
-            if (!(p.temperature > 0.f)) return vf_fail(VF_ERR_ARG, "vf_accept: temperature must be > 0");
-            if (!p.u_dev) return vf_fail(VF_ERR_ARG, "vf_accept: u_dev is NULL");
+            if (!(p.temperature > 0.f)) return vf_fail(VF_ERR_ARG, "%s: temperature must be > 0", who);
+            if (!p.u_dev) return vf_fail(VF_ERR_ARG, "%s: u_dev is NULL", who);
+            if (tree && p.q_dev)
+                return vf_fail(VF_ERR_UNSUPPORTED, "%s: tree drafts take a deterministic drafter (q_dev NULL)", who);
         }
         if (seqs[i]->len_ub + b.s[i].nrows > seqs[i]->capacity)
-            return vf_fail(VF_ERR_CAP, "vf_accept: sequence %d would exceed its capacity", i);
+            return vf_fail(VF_ERR_CAP, "%s: sequence %d would exceed its capacity", who, i);
         ab.a[i].q = p.q_dev;
         ab.a[i].u = p.u_dev;
         ab.a[i].temperature = p.mode == VF_STOCHASTIC ? p.temperature : 1.f;
@@ -490,12 +532,33 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
     }
     {
         ProfScope ps(m, VF_SITE_ACCEPT, (hipStream_t)stream);
-        if ((rc = vf_launch_accept(m, b, ab, tokens_dev, logits, n_accept_dev, out_tokens_dev, y_dev,
-                                   (hipStream_t)stream)))
+        if (tree) {
+            if ((rc = vf_launch_accept_tree(m, b, ab, td, tokens_dev, logits, n_accept_dev, out_tokens_dev, y_dev,
+                                            path_dev, (hipStream_t)stream)))
+                return rc;
+            if ((rc = vf_launch_kv_compact(m, b, n_accept_dev, path_dev, (hipStream_t)stream))) return rc;
+        } else if ((rc = vf_launch_accept(m, b, ab, tokens_dev, logits, n_accept_dev, out_tokens_dev, y_dev,
+                                          (hipStream_t)stream))) {
             return rc;
+        }
     }
     for (int i = 0; i < n_seqs; ++i) seqs[i]->len_ub += b.s[i].nrows;
     return VF_OK;
+}
+
+int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+              const int32_t *row_off_host, const vf_accept_params *params_host, const float *logits_dev,
+              int32_t *n_accept_dev, int32_t *out_tokens_dev, int32_t *y_dev, void *stream) {
+    return accept_impl(m, seqs, n_seqs, tokens_dev, row_off_host, nullptr, false, params_host, logits_dev,
+                       n_accept_dev, out_tokens_dev, y_dev, nullptr, stream, "vf_accept");
+}
+
+int vf_accept_tree(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+                   const int32_t *row_off_host, const int32_t *parent_host, const vf_accept_params *params_host,
+                   const float *logits_dev, int32_t *n_accept_dev, int32_t *out_tokens_dev, int32_t *y_dev,
+                   int32_t *path_dev, void *stream) {
+    return accept_impl(m, seqs, n_seqs, tokens_dev, row_off_host, parent_host, true, params_host, logits_dev,
+                       n_accept_dev, out_tokens_dev, y_dev, path_dev, stream, "vf_accept_tree");
 }
 
 int vf_set_option(vf_model *m, int option, int value) {

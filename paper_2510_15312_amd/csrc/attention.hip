@@ -14,7 +14,7 @@ constexpr int ATT_TK = 32;        // keys staged in LDS at a time
 template <typename T, int HD>
 __global__ __launch_bounds__(ATT_THREADS) void attn_partial_kernel(
     Batch b, int layer, const T *__restrict__ q, float *__restrict__ part, int hq, int hkv, int n_splits,
-    int chunk, float scale) {
+    int chunk, float scale, const tree_mask_t *__restrict__ anc) {
     __shared__ float ks[ATT_TK][HD];
     __shared__ float vs[ATT_TK][HD];
     const int group = hq / hkv;
@@ -30,6 +30,8 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_partial_kernel(
     const int head = kvh * group + jg;
     const int row = s.row0 + r;
     const int last_key = len + r;  // inclusive
+    // tree-structured drafts: of the call's own rows (keys len..) only the ancestors are visible
+    const tree_mask_t visible_rows = anc && valid ? anc[row] : ~(tree_mask_t)0;
     const int r_max = min(s.nrows - 1, (item0 + ATT_THREADS - 1) / group);
     const int split = blockIdx.y;
     const int k_begin = split * chunk;
@@ -60,6 +62,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_partial_kernel(
         if (!valid) continue;
         for (int t = 0; t < nt; ++t) {
             if (t0 + t > last_key) break;
+            if (anc && t0 + t >= len && !((visible_rows >> (t0 + t - len)) & 1)) continue;
             float sc = 0.f;
 #pragma unroll
             for (int d = 0; d < HD; ++d) sc = fmaf(qv[d], ks[t][d], sc);
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(const float *__restric
 }
 
 template <typename T, int HD>
-int launch(const vf_model *m, const Batch &b, int layer, hipStream_t st) {
+int launch(const vf_model *m, const Batch &b, int layer, const tree_mask_t *anc, hipStream_t st) {
     const vf_config &c = m->cfg;
     const int group = c.n_q_heads / c.n_kv_heads;
     int max_items = 0, max_keys = 0;
@@ -120,7 +123,7 @@ int launch(const vf_model *m, const Batch &b, int layer, hipStream_t st) {
     const float scale = 1.0f / sqrtf((float)HD);
     hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(tiles, n_splits, b.n_seqs * c.n_kv_heads),
                        dim3(ATT_THREADS), 0, st, b, layer, (const T *)m->q, m->attn_part, c.n_q_heads,
-                       c.n_kv_heads, n_splits, chunk, scale);
+                       c.n_kv_heads, n_splits, chunk, scale, anc);
     VF_LAUNCH_CHECK("attn_partial");
     const int ncb = (b.total_rows + 15) >> 4;
     hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(b.total_rows * c.n_q_heads), dim3(HD), 0, st,
@@ -131,15 +134,15 @@ int launch(const vf_model *m, const Batch &b, int layer, hipStream_t st) {
 
 }  // namespace
 
-int vf_launch_attention(const vf_model *m, const Batch &b, int layer, hipStream_t st) {
+int vf_launch_attention(const vf_model *m, const Batch &b, int layer, const tree_mask_t *anc, hipStream_t st) {
     const vf_config &c = m->cfg;
     if (c.dtype == VF_BF16) {
-        if (m->fast_path) return vf_launch_attention_rows(m, b, layer, st);  // MFMA kernel
-        if (c.head_dim == 64) return launch<bf16_t, 64>(m, b, layer, st);
-        if (c.head_dim == 128) return launch<bf16_t, 128>(m, b, layer, st);
+        if (m->fast_path && !anc) return vf_launch_attention_rows(m, b, layer, st);  // MFMA kernel
+        if (c.head_dim == 64) return launch<bf16_t, 64>(m, b, layer, anc, st);
+        if (c.head_dim == 128) return launch<bf16_t, 128>(m, b, layer, anc, st);
     } else {
-        if (c.head_dim == 64) return launch<float, 64>(m, b, layer, st);
-        if (c.head_dim == 128) return launch<float, 128>(m, b, layer, st);
+        if (c.head_dim == 64) return launch<float, 64>(m, b, layer, anc, st);
+        if (c.head_dim == 128) return launch<float, 128>(m, b, layer, anc, st);
     }
     return vf_fail(VF_ERR_UNSUPPORTED, "head_dim %d (built for 64 and 128)", c.head_dim);
 }

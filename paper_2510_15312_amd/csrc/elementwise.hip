@@ -167,7 +167,8 @@ __global__ __launch_bounds__(256) void norm_bf16_vec_kernel(float *__restrict__ 
 template <typename T>
 __global__ void qkv_finish_kernel(const float *__restrict__ part, int nparts, int ld_rows, Batch b, int layer,
                                   const float *__restrict__ bias, const float *__restrict__ cosv,
-                                  const float *__restrict__ sinv, T *__restrict__ q, int hq, int hkv, int hd) {
+                                  const float *__restrict__ sinv, T *__restrict__ q, int hq, int hkv, int hd,
+                                  const int32_t *__restrict__ depth) {
     const int half = hd >> 1;
     const int heads = hq + 2 * hkv;
     const int per_row = heads * half;
@@ -186,8 +187,11 @@ __global__ void qkv_finish_kernel(const float *__restrict__ part, int nparts, in
     }
     if (bias) { v0 += bias[n0]; v1 += bias[n1]; }
     const SeqDesc &s = b.s[find_seq(b, row)];
-    const int pos = s.state[0] + (row - s.row0);
-    if (pos < 0 || pos >= s.capacity) return;
+    // the rotary angle is that of the token's position; the cache row is the call's row (the two
+    // differ for tree-structured drafts, where a node stands at the position of its depth)
+    const int slot = s.state[0] + (row - s.row0);
+    const int pos = depth ? s.state[0] + depth[row] : slot;
+    if (slot < 0 || slot >= s.capacity) return;
     if (rot) {
         const float c = cosv[(size_t)pos * half + i], sn = sinv[(size_t)pos * half + i];
         const float r0 = v0 * c - v1 * sn, r1 = v1 * c + v0 * sn;
@@ -200,7 +204,7 @@ __global__ void qkv_finish_kernel(const float *__restrict__ part, int nparts, in
         return;
     }
     T *kv = reinterpret_cast<T *>(s.kv);
-    const int page = kv_page(s, pos), tin = pos % VF_TILE;
+    const int page = kv_page(s, slot), tin = slot % VF_TILE;
     if (head < hq + hkv) {
         const int kh = head - hq;
         kv[kv_k_index(layer, s.n_pages, page, hkv, kh, tin, i, hd)] = from_f32<T>(v0);
@@ -277,6 +281,54 @@ __global__ void pack_vec_kernel(const float *__restrict__ src, float *__restrict
     if (i < n) dst[i] = src[pack_src_row(i, perm_hd)];
 }
 
+// Tree-structured drafts: lane r of the sequence's wavefront walks from row r to the root and
+// collects the ancestor mask (bit j = row j lies on the path, r itself included) and the depth.
+// The host has checked 0 <= parent < r, so the walk ends after at most r steps.
+__global__ __launch_bounds__(64) void tree_prep_kernel(Batch b, TreeDesc tree, tree_mask_t *__restrict__ anc,
+                                                       int32_t *__restrict__ depth) {
+    const SeqDesc &s = b.s[blockIdx.x];
+    const int r = threadIdx.x;
+    if (r >= s.nrows) return;
+    tree_mask_t mask = 0;
+    int d = 0;
+    for (int a = r, steps = 0; a >= 0 && steps <= VF_MAX_DRAFTS; ++steps) {
+        mask |= (tree_mask_t)1 << a;
+        const int p = a > 0 ? tree.parent[blockIdx.x][a] : -1;
+        if (p >= 0) ++d;
+        a = p;
+    }
+    anc[s.row0 + r] = mask;
+    depth[s.row0 + r] = d;
+}
+
+// After a tree verify: cache rows of the accepted path go to len_old + 1 .. len_old + a in path
+// order (row len_old, the root, stays).  Path rows increase and path[j] >= j, so a destination row
+// j can be the source only of an earlier step (path[j'] = j with j' < j).  One thread per (layer,
+// kv head, element) copies its element for j = 1, 2, ... in turn: it has read row path[j'] before
+// it overwrites that row at step j.
+template <typename T>
+__global__ void kv_compact_kernel(Batch b, const int32_t *__restrict__ n_accept, const int32_t *__restrict__ path,
+                                  int n_layers, int hkv, int hd) {
+    const SeqDesc &s = b.s[blockIdx.y];
+    const int a = n_accept[blockIdx.y];
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_layers * hkv * hd || a <= 0 || a >= s.nrows) return;
+    const int layer = idx / (hkv * hd), head = (idx / hd) % hkv, d = idx % hd;
+    const int len_old = s.state[0] - 1 - a;  // the acceptance kernels have already advanced the length
+    T *kv = reinterpret_cast<T *>(s.kv);
+    for (int j = 1; j <= a; ++j) {
+        const int r = path[s.row0 + j];
+        if (r == j || r < j || r >= s.nrows) continue;
+        const int src = len_old + r, dst = len_old + j;
+        if (src >= s.capacity) continue;
+        const int ps = kv_page(s, src), pd = kv_page(s, dst);
+        kv[kv_k_index(layer, s.n_pages, pd, hkv, head, dst % VF_TILE, d, hd)] =
+            kv[kv_k_index(layer, s.n_pages, ps, hkv, head, src % VF_TILE, d, hd)];
+        kv[kv_v_index(layer, s.n_pages, pd, hkv, head, dst % VF_TILE, d, hd)] =
+            kv[kv_v_index(layer, s.n_pages, ps, hkv, head, src % VF_TILE, d, hd)];
+    }
+}
+
 }  // namespace
 
 int vf_launch_pack_vec(const float *src, float *dst, int n, int perm_hd, hipStream_t st) {
@@ -346,18 +398,18 @@ int vf_launch_norm(const vf_model *m, const float *gain, void *x_out, const floa
 }
 
 int vf_launch_qkv_finish(const vf_model *m, const Batch &b, int layer, const float *part, int nparts,
-                         int ld_rows, hipStream_t st) {
+                         int ld_rows, const int32_t *depth, hipStream_t st) {
     const vf_config &c = m->cfg;
     const int total = b.total_rows * (c.n_q_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
     const float *bias = c.qkv_bias ? m->layers[layer].bqkv : nullptr;
     if (c.dtype == VF_BF16)
         hipLaunchKernelGGL(qkv_finish_kernel<bf16_t>, dim3(nblocks(total, 256)), dim3(256), 0, st, part, nparts,
                            ld_rows, b, layer, bias, m->rope_cos, m->rope_sin, (bf16_t *)m->q, c.n_q_heads,
-                           c.n_kv_heads, c.head_dim);
+                           c.n_kv_heads, c.head_dim, depth);
     else
         hipLaunchKernelGGL(qkv_finish_kernel<float>, dim3(nblocks(total, 256)), dim3(256), 0, st, part, nparts,
                            ld_rows, b, layer, bias, m->rope_cos, m->rope_sin, (float *)m->q, c.n_q_heads,
-                           c.n_kv_heads, c.head_dim);
+                           c.n_kv_heads, c.head_dim, depth);
     VF_LAUNCH_CHECK("qkv_finish");
     return VF_OK;
 }
@@ -451,5 +503,25 @@ int vf_launch_kv_read(const vf_model *m, const SeqDesc &s, int layer, int t0, in
         hipLaunchKernelGGL(kv_read_kernel<float>, dim3(nblocks(total, 256)), dim3(256), 0, st, s, layer, t0, n,
                            c.n_kv_heads, c.head_dim, k_out, v_out);
     VF_LAUNCH_CHECK("kv_read");
+    return VF_OK;
+}
+
+int vf_launch_tree_prep(const vf_model *m, const Batch &b, const TreeDesc &tree, hipStream_t st) {
+    hipLaunchKernelGGL(tree_prep_kernel, dim3(b.n_seqs), dim3(64), 0, st, b, tree, m->tree_anc, m->tree_depth);
+    VF_LAUNCH_CHECK("tree_prep");
+    return VF_OK;
+}
+
+int vf_launch_kv_compact(const vf_model *m, const Batch &b, const int32_t *n_accept, const int32_t *path,
+                         hipStream_t st) {
+    const vf_config &c = m->cfg;
+    const int total = c.n_layers * c.n_kv_heads * c.head_dim;
+    if (c.dtype == VF_BF16)
+        hipLaunchKernelGGL(kv_compact_kernel<bf16_t>, dim3(nblocks(total, 256), b.n_seqs), dim3(256), 0, st, b,
+                           n_accept, path, c.n_layers, c.n_kv_heads, c.head_dim);
+    else
+        hipLaunchKernelGGL(kv_compact_kernel<float>, dim3(nblocks(total, 256), b.n_seqs), dim3(256), 0, st, b,
+                           n_accept, path, c.n_layers, c.n_kv_heads, c.head_dim);
+    VF_LAUNCH_CHECK("kv_compact");
     return VF_OK;
 }

@@ -378,7 +378,7 @@ __global__ __launch_bounds__(ROWS_WAVES * 64) void attn_rows_kernel(Batch b, int
         tile.mask_values(t0, kmax, lane);
 #pragma unroll
         for (int c = 0; c < ROWS_QB; ++c)
-            if (t0 <= blk_last[c]) att_tile_update<HD>(st[c], qf[c], tile, t0, last_key[c], scale_log2e, lane);
+            if (t0 <= blk_last[c]) att_tile_update<HD>(st[c], qf[c], tile, t0, last_key[c], ATT_NO_TREE, 0, scale_log2e, lane);
     }
     // merge of the eight wavefronts, one item block at a time: thread (db = wave, lane) owns
     // O^T[d = 16*db + 4*g4 + j][item l15]; HD = 64 leaves wavefronts 4..7 idle here

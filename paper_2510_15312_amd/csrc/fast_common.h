@@ -39,6 +39,7 @@ struct FastGemm {
     const float *bias, *cosv, *sinv;
     bf16_t *q;
     int layer, hq, hkv, hd;
+    const int32_t *depth;  // tree-structured drafts: depth of every row (NULL: row r of a sequence has depth r)
 };
 
 __device__ inline u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
@@ -129,8 +130,11 @@ __device__ inline void epi_qkv(const FastGemm &g, const Batch &b, int row, int n
     if (g.bias)
         for (int i = 0; i < 4; ++i) v[i] += g.bias[n0 + i];
     const SeqDesc &s = b.s[find_seq(b, row)];
-    const int pos = s.state[0] + (row - s.row0);
-    if (pos < 0 || pos >= s.capacity) return;
+    // slot: the cache row the call's row is written to; pos: the position whose rotary angle it
+    // takes (its depth below the pending token when the drafts form a tree)
+    const int slot = s.state[0] + (row - s.row0);
+    const int pos = g.depth ? s.state[0] + g.depth[row] : slot;
+    if (slot < 0 || slot >= s.capacity) return;
     const int head = n0 / hd, p0 = n0 % hd;
     bf16_t *kv = reinterpret_cast<bf16_t *>(s.kv);
     if (head < g.hq + g.hkv) {
@@ -143,14 +147,14 @@ __device__ inline void epi_qkv(const FastGemm &g, const Batch &b, int row, int n
         if (head < g.hq) {
             dst = g.q + ((size_t)row * g.hq + head) * hd;
         } else {
-            const int page = kv_page(s, pos), tin = pos % VF_TILE;
+            const int page = kv_page(s, slot), tin = slot % VF_TILE;
             dst = kv + kv_k_index(g.layer, s.n_pages, page, g.hkv, head - g.hq, tin, 0, hd);
         }
         st_u32<COH>(dst + i0, pack2_bf16(a0, a1));          // i0 is even: 4-byte aligned
         st_u32<COH>(dst + i0 + half, pack2_bf16(b0, b1));
     } else {
         const int vh = head - g.hq - g.hkv;
-        const int page = kv_page(s, pos), tin = pos % VF_TILE;
+        const int page = kv_page(s, slot), tin = slot % VF_TILE;
         for (int i = 0; i < 4; ++i) {
             const bf16_t x = (bf16_t)v[i];
             st_u16<COH>(kv + kv_v_index(g.layer, s.n_pages, page, g.hkv, vh, tin, p0 + i, hd),
@@ -401,10 +405,14 @@ template <int HD> struct AttTile {
 };
 
 // One tile for one block of 16 query items: masked online softmax update of st.
-// last_key: last visible key of this lane's item (-1: none).
+// last_key: last visible key of this lane's item (-1: none).  Tree-structured drafts: of the keys
+// from own_base on (the rows of the same call) only those whose bit is set in own_mask are
+// visible; a plain causal call passes ATT_NO_TREE as own_base.
+constexpr int ATT_NO_TREE = 0x7fffffff;
 template <int HD>
 __device__ __forceinline__ void att_tile_update(AttState<HD> &st, const bf16x8 (&qf)[HD / 32], const AttTile<HD> &T, int t0,
-                                                int last_key, float scale_log2e, int lane) {
+                                                int last_key, int own_base, tree_mask_t own_mask,
+                                                float scale_log2e, int lane) {
     constexpr int KD = HD / 32, DB = HD / 16;
     const int g4 = lane >> 4;
     floatx4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -415,10 +423,21 @@ __device__ __forceinline__ void att_tile_update(AttState<HD> &st, const bf16x8 (
     }
     // lane holds keys t0 + 8*g4 + j (s0) and t0 + 8*g4 + 4 + j (s1) of item (lane & 15)
     float p[8], tmax = -1e30f;
+    bool vis[8];
+    if (own_base == ATT_NO_TREE) {  // the same for every lane: a scalar branch, the causal test alone
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vis[j] = t0 + g4 * 8 + j <= last_key;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int key = t0 + g4 * 8 + j;
+            vis[j] = key <= last_key && (key < own_base || ((own_mask >> ((unsigned)(key - own_base) & 63u)) & 1));
+        }
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        p[j] = (t0 + g4 * 8 + j <= last_key) ? s0[j] * scale_log2e : -1e30f;
-        p[4 + j] = (t0 + g4 * 8 + 4 + j <= last_key) ? s1[j] * scale_log2e : -1e30f;
+        p[j] = vis[j] ? s0[j] * scale_log2e : -1e30f;
+        p[4 + j] = vis[4 + j] ? s1[j] * scale_log2e : -1e30f;
         tmax = fmaxf(tmax, fmaxf(p[j], p[4 + j]));
     }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
@@ -428,7 +447,7 @@ __device__ __forceinline__ void att_tile_update(AttState<HD> &st, const bf16x8 (
     float psum = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        p[j] = (t0 + g4 * 8 + j <= last_key) ? exp2f(p[j] - m_new) : 0.f;
+        p[j] = vis[j] ? exp2f(p[j] - m_new) : 0.f;
         psum += p[j];
     }
     psum += __shfl_xor(psum, 16, 64);

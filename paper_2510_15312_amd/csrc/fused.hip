@@ -84,6 +84,8 @@ struct FusedArgs {
     const bf16_t *embed;
     const u32x4 *lm_head;
     const float *final_norm, *cosv, *sinv;
+    const int32_t *tree_depth;      // tree-structured drafts (else NULL): depth and ancestor mask of every row
+    const tree_mask_t *tree_anc;
     const int32_t *tokens;
     float *hv;        // residual stream, [2L+1][FROWS][d]
     float *ssv;       // sums of squares of its rows per 16 columns, [2L+1][d/16][64]
@@ -591,6 +593,9 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
         const int r = valid ? item / group : 0, head = kvh * group + (valid ? item % group : 0);
         const int row = s.row0 + r;
         const int last_key = valid ? len + r : -1;
+        // a value every lane shares (kernel argument and the item's sequence length)
+        const int own_base = a.tree_anc ? __builtin_amdgcn_readfirstlane(len) : ATT_NO_TREE;
+        const tree_mask_t own_mask = a.tree_anc && valid ? a.tree_anc[row] : 0;
 
         bf16x8 qf[KD];
 #pragma unroll
@@ -607,7 +612,7 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
             if (!preloaded) tile.load(s, layer, hkv, kvh, t, (t + 1) * FKT > len, lane);
             preloaded = false;
             tile.mask_values(t0, kmax, lane);
-            att_tile_update<HD>(st, qf, tile, t0, last_key, a.scale_log2e, lane);
+            att_tile_update<HD>(st, qf, tile, t0, last_key, own_base, own_mask, a.scale_log2e, lane);
         }
         preloaded = false;
         TRACE(20);
@@ -733,6 +738,7 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
     base.F = F;
     base.cosv = a.cosv;
     base.sinv = a.sinv;
+    base.depth = a.tree_depth;
     base.hq = a.hq;
     base.hkv = a.hkv;
     base.hd = hd;
@@ -920,7 +926,7 @@ bool vf_fused_ok(const vf_model *m, const Batch &b) {
     return plan_fused(m, b, a, &G);
 }
 
-int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, hipStream_t st) {
+int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, bool tree, hipStream_t st) {
     const vf_config &c = m->cfg;
     FusedArgs a;
     memset(&a, 0, sizeof a);
@@ -943,6 +949,8 @@ int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logi
     a.final_norm = m->final_norm;
     a.cosv = m->rope_cos;
     a.sinv = m->rope_sin;
+    a.tree_depth = tree ? m->tree_depth : nullptr;
+    a.tree_anc = tree ? m->tree_anc : nullptr;
     a.tokens = tokens;
     a.hv = m->fz_h;
     a.ssv = m->fz_ss;

@@ -35,6 +35,12 @@ struct Batch {
     SeqDesc s[VF_MAX_BATCH];
 };
 
+// Tree-structured drafts: parent row (within the sequence) of every row; -1 for row 0.
+struct TreeDesc {
+    int8_t parent[VF_MAX_BATCH][VF_MAX_DRAFTS + 1];
+};
+typedef unsigned long long tree_mask_t;  // bit j: row j of the sequence is an ancestor of (or is) this row
+
 struct AcceptDesc {
     const float *q;             // [k, V] or NULL
     const float *u;             // [2*(k+1)]
@@ -49,6 +55,8 @@ struct DrawDesc {
     double zmax, S, u, t;       // row maximum, softmax normaliser, uniform, temperature
     const float *q;             // draft distribution row or NULL
     int32_t row, x_excl, active, acc;
+    int32_t n_excl;             // tree verification: tokens of the refused children of the deciding node
+    int32_t excl[VF_MAX_DRAFTS];
 };
 
 // ---- model / sequence host structs ------------------------------------------------------------
@@ -84,6 +92,8 @@ struct vf_model {
     int32_t *scratch_i32;       // [64]
     float *ss;                  // per-16-column sums of squares of h rows, [d/16][64]
     int32_t *counters;          // split-K arrival counters, [VF_N_COUNTERS], zero between kernels
+    tree_mask_t *tree_anc;      // tree verify: ancestor mask of every row of the call, [R]
+    int32_t *tree_depth;        // tree verify: depth of every row, [R]
     int fast_path;              // option: use the few-row kernels when they apply
     int persistent;             // option: use the persistent whole-pass kernel when it applies
     // persistent kernel: single-assignment activation buffers, barrier counters, layer table
@@ -228,12 +238,23 @@ int vf_launch_rope_table(const vf_model *m, hipStream_t st);
 int vf_launch_embed(const vf_model *m, const Batch &b, const int32_t *tokens, hipStream_t st);
 int vf_launch_norm(const vf_model *m, const float *gain, void *x_out, const float *part, int nparts,
                    int rows, int ld_rows, hipStream_t st);
+// depth != NULL (tree verify): row r stands at position len + depth[row], not len + r
 int vf_launch_qkv_finish(const vf_model *m, const Batch &b, int layer, const float *part, int nparts,
-                         int ld_rows, hipStream_t st);
+                         int ld_rows, const int32_t *depth, hipStream_t st);
+// ancestor masks and depths of every row of the call from the parent table, into the model workspace
+int vf_launch_tree_prep(const vf_model *m, const Batch &b, const TreeDesc &tree, hipStream_t st);
+// moves the K/V rows of the accepted path (path[row0 + j], j = 1..n_accept) to the positions right
+// after the old length; runs after the acceptance kernels have committed the new length
+int vf_launch_kv_compact(const vf_model *m, const Batch &b, const int32_t *n_accept, const int32_t *path,
+                         hipStream_t st);
+int vf_launch_accept_tree(const vf_model *m, const Batch &b, const AcceptBatch &ab, const TreeDesc &tree,
+                          const int32_t *tokens, const float *logits, int32_t *n_accept, int32_t *out_tokens,
+                          int32_t *y, int32_t *path, hipStream_t st);
 int vf_launch_swiglu(const vf_model *m, const float *part, int nparts, int rows, int ld_rows, hipStream_t st);
 int vf_launch_reduce_rows(const vf_model *m, const float *part, int nparts, int N, int row_lo, int row_hi,
                           int ld_rows, float *out, int out_ld, hipStream_t st);
-int vf_launch_attention(const vf_model *m, const Batch &b, int layer, hipStream_t st);
+// anc != NULL: rows of the call see, among the call's rows, only those in their ancestor mask
+int vf_launch_attention(const vf_model *m, const Batch &b, int layer, const tree_mask_t *anc, hipStream_t st);
 int vf_launch_state_set(int32_t *state, int idx, int32_t value, hipStream_t st);
 int vf_launch_state_add(int32_t *state, int idx, int32_t delta, hipStream_t st);
 int vf_launch_kv_read(const vf_model *m, const SeqDesc &s, int layer, int t0, int n, float *k_out,
@@ -250,7 +271,8 @@ int vf_run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logit
 size_t vf_fused_workspace_bytes(const vf_config &c);
 int vf_fused_init(vf_model *m, char *ws, hipStream_t st);
 bool vf_fused_ok(const vf_model *m, const Batch &b);
-int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, hipStream_t st);
+// tree: rows take position and visibility from the model's tree_depth / tree_anc tables
+int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, bool tree, hipStream_t st);
 int vf_fused_check(vf_model *m);
 int vf_launch_first_token(const vf_model *m, const SeqDesc &s, const float *logits_row, const float *u,
                           float temperature, hipStream_t st);
