@@ -83,6 +83,7 @@ size_t carve_model(vf_model *m, char *base) {
     size_t widest = 2 * F;
     if (nq + 2 * nkv > widest) widest = nq + 2 * nkv;
     m->part_floats = R * widest * 2;  // room for two partials of the widest layer GEMM
+    m->part_floats = std::max(m->part_floats, vf_fused_part_floats(c));  // and for the persistent kernel's K splits
     m->part = (float *)cv.take(m->part_floats * 4);
     {
         // general path: 16 slices per row of max_rows; few-row path: up to 48 rows, one slice per 128 keys

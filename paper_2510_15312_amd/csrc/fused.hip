@@ -103,7 +103,7 @@ struct FusedArgs {
     short att_first[FUSED_G];
     float inv_d, eps, scale_log2e;
     unsigned root0;   // value of the barrier's root counter when this launch starts
-    int ks_qkv, ks_o, ks_gu, ks_down;
+    int ks_qkv, ks_o, ks_gu, ks_down, ks_head;
     int lds_total;    // dynamic LDS bytes of this launch
 };
 
@@ -796,7 +796,7 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
         g.W = a.lm_head; g.N = a.vocab; g.KB = d / 32;
         g.Xh = a.hv + (size_t)(2 * a.n_layers) * hstride; g.gain = a.final_norm;
         g.ss_in = a.ssv + (size_t)(2 * a.n_layers) * sstride; g.logits = a.logits;
-        g.ks = 1; g.kbps = g.KB;
+        g.ks = a.ks_head; g.kbps = (g.KB + g.ks - 1) / g.ks;
         gemm_phase<NB, 2, 6, EPI_LOGITS>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
     }
     TRACE(99);
@@ -892,31 +892,60 @@ int vf_fused_init(vf_model *m, char *ws, hipStream_t st) {
 }
 
 // Whether the persistent kernel can run this call; fills the grid size, LDS size and K splits.
-static bool plan_fused(const vf_model *m, const Batch &b, FusedArgs &a, int *G_out) {
-    const vf_config &c = m->cfg;
-    if (c.dtype != VF_BF16 || !m->fz_h || b.total_rows > FROWS || c.d_model % 64) return false;
-    const int rows = b.total_rows, nb = (rows + 15) / 16;
+// K splits of the six GEMM phases for a call of `rows` rows (nb blocks of 16), and the floats of
+// partial-sum workspace they need.  false: some phase does not fit.
+struct Splits { int qkv, o, gu, down, head; };
+static bool plan_splits(const vf_config &c, int rows, int nb, Splits *sp, size_t *part_floats) {
     const int d = c.d_model, F = c.d_ffn, hd = c.head_dim, nq = c.n_q_heads * hd, nkv = c.n_kv_heads * hd;
-    if (std::max((nq + 2 * nkv) / 16, F / 16) > VF_N_COUNTERS) return false;
+    if (c.dtype != VF_BF16 || rows > FROWS || d % 64) return false;
+    if (std::max(std::max((nq + 2 * nkv) / 16, F / 16), (c.vocab / 16 + 1) / 2) > VF_N_COUNTERS) return false;
     const int G = FUSED_G, lds = LDS_BYTES;
     if (G % BAR_COUNTERS) return false;
-    a.ks_qkv = pick_split(G, lds, (nq + 2 * nkv) / 16, d / 32, rows, nb, false);
-    a.ks_o = pick_split(G, lds, d / 16, nq / 32, rows, nb, false);
-    a.ks_gu = pick_split(G, lds, F / 16, d / 32, rows, nb, false);
-    a.ks_down = pick_split(G, lds, (d / 16 + 1) / 2, F / 32, rows, nb, true);
-    const int ks_head = pick_split(G, lds, (c.vocab / 16 + 1) / 2, d / 32, rows, nb, false);
-    if (!a.ks_qkv || !a.ks_o || !a.ks_gu || !a.ks_down || ks_head != 1) return false;
+    sp->qkv = pick_split(G, lds, (nq + 2 * nkv) / 16, d / 32, rows, nb, false);
+    sp->o = pick_split(G, lds, d / 16, nq / 32, rows, nb, false);
+    sp->gu = pick_split(G, lds, F / 16, d / 32, rows, nb, false);
+    sp->down = pick_split(G, lds, (d / 16 + 1) / 2, F / 32, rows, nb, true);
+    sp->head = pick_split(G, lds, (c.vocab / 16 + 1) / 2, d / 32, rows, nb, false);
+    if (!sp->qkv || !sp->o || !sp->gu || !sp->down || !sp->head) return false;
     // the gain slice of a normalising phase is staged where the partial sums go later
     const int red_bytes = (FW / 2) * 2 * nb * 1024;
-    if ((d / 32 + a.ks_gu - 1) / a.ks_gu * 128 > red_bytes || (d / 32 + a.ks_qkv - 1) / a.ks_qkv * 128 > red_bytes ||
-        d / 32 * 128 > red_bytes)
+    auto slice_bytes = [&](int ks) { return (d / 32 + ks - 1) / ks * 128; };
+    if (slice_bytes(sp->gu) > red_bytes || slice_bytes(sp->qkv) > red_bytes || slice_bytes(sp->head) > red_bytes)
         return false;
     // partial tiles of the split phases: units * ks tiles of UB * NB * 256 floats
-    const size_t tiles = std::max(std::max((nq + 2 * nkv) / 16 * a.ks_qkv, d / 16 * a.ks_o),
-                                  std::max(F / 16 * a.ks_gu, (d / 16 + 1) / 2 * a.ks_down));
-    if (tiles * 2 * nb * 256 > m->part_floats) return false;
-    a.lds_total = lds;
-    *G_out = G;
+    size_t tiles = std::max(std::max((nq + 2 * nkv) / 16 * sp->qkv, d / 16 * sp->o),
+                            std::max(F / 16 * sp->gu, (d / 16 + 1) / 2 * sp->down));
+    if (sp->head > 1) tiles = std::max(tiles, (size_t)((c.vocab / 16 + 1) / 2) * sp->head);
+    *part_floats = tiles * 2 * nb * 256;
+    return true;
+}
+
+// Partial-sum workspace (floats) the persistent kernel may ask for with this model, over all row counts.
+size_t vf_fused_part_floats(const vf_config &c) {
+    size_t need = 0;
+    for (int nb = 1; nb * 16 <= FROWS; ++nb) {
+        if (c.max_rows < (nb - 1) * 16 + 1) break;
+        // the most rows a call of nb blocks can have: the smallest K slices, the most splits
+        Splits sp;
+        size_t pf = 0;
+        if (plan_splits(c, std::min(nb * 16, (int)c.max_rows), nb, &sp, &pf)) need = std::max(need, pf);
+    }
+    return need;
+}
+
+static bool plan_fused(const vf_model *m, const Batch &b, FusedArgs &a, int *G_out) {
+    if (!m->fz_h) return false;
+    const int rows = b.total_rows, nb = (rows + 15) / 16;
+    Splits sp;
+    size_t pf = 0;
+    if (!plan_splits(m->cfg, rows, nb, &sp, &pf) || pf > m->part_floats) return false;
+    a.ks_qkv = sp.qkv;
+    a.ks_o = sp.o;
+    a.ks_gu = sp.gu;
+    a.ks_down = sp.down;
+    a.ks_head = sp.head;
+    a.lds_total = LDS_BYTES;
+    *G_out = FUSED_G;
     return true;
 }
 

@@ -274,5 +274,6 @@ bool vf_fused_ok(const vf_model *m, const Batch &b);
 // tree: rows take position and visibility from the model's tree_depth / tree_anc tables
 int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, bool tree, hipStream_t st);
 int vf_fused_check(vf_model *m);
+size_t vf_fused_part_floats(const vf_config &c);
 int vf_launch_first_token(const vf_model *m, const SeqDesc &s, const float *logits_row, const float *u,
                           float temperature, hipStream_t st);
