@@ -16,6 +16,8 @@ Paper anchors (section / table):
     draft and prediction agree              -- Sec. 4.3, Eq. (reuse), Table "cases"
   * "tree-structured drafts" verified in one pass (mechanics: tree.py)
                                             -- Sec. 4, workflow
+  * top successors of every prefill position from the prefill logits
+                                            -- Sec. 4.2, workflow step "Sample"
   * fixed-size chunked prefill              -- Sec. 2 / Sec. 4.1
   * "executing the short graph several times equals one long execution"
                                             -- Sec. 4.1 (equivalence insight)
@@ -29,9 +31,10 @@ from .transformer import ModelSpec, Weights, KVCache, forward, prefill, verify
 from .acceptance import greedy_accept, stochastic_accept, first_token
 from .reuse import reuse_segment, ReusePool
 from .tree import verify_tree, tree_greedy_accept, tree_stochastic_accept, compact
+from .calibration import topk_rows
 
 __all__ = [
     "round_bf16", "ModelSpec", "Weights", "KVCache", "forward", "prefill",
     "verify", "greedy_accept", "stochastic_accept", "first_token", "reuse_segment", "ReusePool",
-    "verify_tree", "tree_greedy_accept", "tree_stochastic_accept", "compact",
+    "verify_tree", "tree_greedy_accept", "tree_stochastic_accept", "compact", "topk_rows",
 ]
