@@ -322,6 +322,33 @@ def main():
         tree_step()
     e1.record()
     torch.cuda.synchronize()
+    # chunked prefill that also hands back the top-8 successors of every position (the input of the
+    # calibration step), against the same prefill returning all logits followed by a library top-k
+    seq2 = vf.vf_seq_create(model, cfg.ctx + 8)
+    tv = torch.empty((cfg.chunk, 8), dtype=torch.float32, device="cuda:0")
+    ti = torch.empty((cfg.chunk, 8), dtype=torch.int32, device="cuda:0")
+    zall = torch.empty((cfg.chunk, V), dtype=torch.float32, device="cuda:0")
+
+    def prefill_topk(fused):
+        vf.vf_seq_set_len(seq2, 0)
+        for c0 in range(0, cfg.ctx, cfg.chunk):
+            if fused:
+                vf.vf_prefill_chunk_topk(model, seq2, ctx[c0:c0 + cfg.chunk], 8, tv, ti)
+            else:
+                vf.vf_prefill_chunk(model, seq2, ctx[c0:c0 + cfg.chunk], logits_mode=2, logits_out=zall)
+                torch.topk(zall, 8, dim=-1)
+
+    topk_ms = {}
+    for fused in (True, False):
+        prefill_topk(fused)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        prefill_topk(fused)
+        torch.cuda.synchronize()
+        topk_ms[fused] = (time.time() - t0) * 1e3
+    res["prefill_top8"] = {"ms": round(topk_ms[True], 1), "ms_all_logits_then_library_topk": round(topk_ms[False], 1),
+                           "tokens": cfg.ctx, "chunk": cfg.chunk}
+    del seq2, zall
     res["tree_verify"] = {"us_per_step": round(e0.elapsed_time(e1) * 100.0, 1), "rows": m,
                           "depth": int(max(wl_depths(parents))), "acceptance": "greedy, path compacted"}
     if args.pmc_calibration:

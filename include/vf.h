@@ -56,6 +56,7 @@ extern "C" {
 
 #define VF_PENDING   (-1)   /* token id meaning "the sequence's pending token on the device" */
 #define VF_MAX_BATCH   32   /* sequences per vf_verify / vf_accept call                      */
+#define VF_TOPK_MAX      8   /* largest k of vf_prefill_chunk_topk                            */
 #define VF_MAX_DRAFTS  32   /* draft tokens per sequence per verify (paper Sec. 5.1: cap 32) */
 
 typedef struct vf_model vf_model;   /* opaque; host struct describing a packed model */
@@ -203,6 +204,23 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
               const int32_t *row_off_host, const vf_accept_params *params_host,
               const float *logits_dev, int32_t *n_accept_dev, int32_t *out_tokens_dev,
               int32_t *y_dev, void *stream);
+
+/* ---- top successors of every prefill position (next to the three operations) ---------------- */
+
+/* vf_prefill_chunk that also returns, for EVERY row of the chunk, the top_k largest next-token
+ * logits and their ids (paper Sec. 4.2, workflow step "Sample": the top-probability successors
+ * of each context token, from which the calibrated token tree is built), without handing the
+ * [n_tokens, vocab] logits to the caller:
+ *   topk_logit_dev[n_tokens, top_k] float32, topk_id_dev[n_tokens, top_k] int32,
+ * in falling order of the logit, equal logits by rising id (entry 0 is the arg-max of the row).
+ * 1 <= top_k <= VF_TOPK_MAX.  sample_first / u_dev / temperature as in vf_prefill_chunk.  On a
+ * bfloat16 model with more than 64 rows the candidates come out of the output-head GEMM's
+ * epilogue and the logits are never written; otherwise they are computed into the model
+ * workspace first.  Both give the top_k of the same float32 logits vf_prefill_chunk with
+ * logits_mode 2 would return. */
+int vf_prefill_chunk_topk(vf_model *m, vf_seq *s, const int32_t *tokens_dev, int n_tokens, int top_k,
+                          float *topk_logit_dev, int32_t *topk_id_dev, int sample_first,
+                          const float *u_dev, float temperature, void *stream);
 
 /* ---- tree-structured drafts (next to the three operations) ---------------------------------- */
 

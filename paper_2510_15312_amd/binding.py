@@ -18,6 +18,7 @@ VF_F32, VF_BF16 = 0, 1
 VF_GREEDY, VF_STOCHASTIC = 0, 1
 VF_PENDING = -1
 VF_MAX_BATCH, VF_MAX_DRAFTS = 32, 32
+VF_TOPK_MAX = 8
 VF_OPT_FAST_PATH = 1
 VF_OPT_PERSISTENT = 2
 
@@ -27,7 +28,7 @@ EXPORTS = [
     "vf_seq_set_pending", "vf_seq_get_state", "vf_kv_read", "vf_kv_write", "vf_prefill_chunk", "vf_verify",
     "vf_accept", "vf_profile", "vf_profile_read", "vf_set_option", "vf_stream_read",
     "vf_reuse_select", "vf_reuse_pool_init", "vf_reuse_pool_update", "vf_reuse_pool_extend",
-    "vf_verify_tree", "vf_accept_tree",
+    "vf_verify_tree", "vf_accept_tree", "vf_prefill_chunk_topk",
 ]
 SITES = ["qkv", "o", "gateup", "down", "head", "attn", "small", "accept", "step"]
 
@@ -92,6 +93,7 @@ def _load():
         "vf_profile": (C.c_int, [vp, C.c_int]),
         "vf_stream_read": (C.c_int, [vp, C.POINTER(sz), vp]),
         "vf_profile_read": (C.c_int, [vp, C.POINTER(C.c_float), C.POINTER(i32)]),
+        "vf_prefill_chunk_topk": (C.c_int, [vp, vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, vp, C.c_float, vp]),
         "vf_verify_tree": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(i32), vp, vp]),
         "vf_accept_tree": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(i32),
                                      C.POINTER(vf_accept_params), vp, vp, vp, vp, vp, vp]),
@@ -260,6 +262,14 @@ def vf_accept(model, seqs, tokens, row_off, params, n_accept, out_tokens, y, log
                                  u.data_ptr() if u is not None else None)
     _check(lib.vf_accept(model.handle, hs, len(seqs), _ptr(tokens), ro, ps, _ptr(logits), _ptr(n_accept),
                          _ptr(out_tokens), _ptr(y), _stream()))
+
+
+def vf_prefill_chunk_topk(model, seq, tokens, top_k, topk_logit, topk_id, sample_first=False, u=None,
+                          temperature=0.0):
+    """tokens int32[n] (device); topk_logit float32[n, top_k], topk_id int32[n, top_k]: device tensors."""
+    _check(lib.vf_prefill_chunk_topk(model.handle, seq.handle, _ptr(tokens), tokens.numel(), int(top_k),
+                                     _ptr(topk_logit), _ptr(topk_id), int(bool(sample_first)), _ptr(u),
+                                     float(temperature), _stream()))
 
 
 def vf_verify_tree(model, seqs, tokens, row_off, parents, logits_out=None):

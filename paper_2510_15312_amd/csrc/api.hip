@@ -102,6 +102,8 @@ size_t carve_model(vf_model *m, char *base) {
     m->scratch_i32 = (int32_t *)cv.take(64 * 4);
     m->ss = (float *)cv.take((d / 16) * 64 * 4);
     m->counters = (int32_t *)cv.take(VF_N_COUNTERS * 4);
+    m->topk_cand_v = (float *)cv.take((size_t)R * vf_topk_max_slices(c) * VF_TOPK_MAX * 4);
+    m->topk_cand_i = (int32_t *)cv.take((size_t)R * vf_topk_max_slices(c) * VF_TOPK_MAX * 4);
     m->tree_anc = (tree_mask_t *)cv.take((size_t)R * 8);
     m->tree_depth = (int32_t *)cv.take((size_t)R * 4);
     m->fz_ws = (char *)cv.take(vf_fused_workspace_bytes(c));
@@ -409,6 +411,63 @@ int vf_prefill_chunk(vf_model *m, vf_seq *s, const int32_t *tokens_dev, int n_to
         float *dst = logits_mode == 1 ? logits_out_dev : m->logits;
         if ((rc = run_head(m, n_tokens, tail, n_tokens - 1, n_tokens, dst, st))) return rc;
         last_row = dst;
+    }
+    if (sample_first)
+        if ((rc = vf_launch_first_token(m, b.s[0], last_row, u_dev, temperature, st))) return rc;
+    if ((rc = vf_launch_state_add(s->state, 0, n_tokens, st))) return rc;
+    s->len_ub += n_tokens;
+    return VF_OK;
+}
+
+int vf_prefill_chunk_topk(vf_model *m, vf_seq *s, const int32_t *tokens_dev, int n_tokens, int top_k,
+                          float *topk_logit_dev, int32_t *topk_id_dev, int sample_first, const float *u_dev,
+                          float temperature, void *stream) {
+    if (!m || !s || !tokens_dev || !topk_logit_dev || !topk_id_dev)
+        return vf_fail(VF_ERR_ARG, "vf_prefill_chunk_topk: NULL argument");
+    if (s->m != m) return vf_fail(VF_ERR_ARG, "sequence belongs to another model");
+    if (n_tokens < 1) return vf_fail(VF_ERR_ARG, "n_tokens %d < 1", n_tokens);
+    if (n_tokens > m->cfg.max_rows) return vf_fail(VF_ERR_CAP, "n_tokens %d > max_rows %d", n_tokens, m->cfg.max_rows);
+    if (top_k < 1 || top_k > VF_TOPK_MAX || top_k > m->cfg.vocab)
+        return vf_fail(VF_ERR_ARG, "top_k %d outside 1..%d", top_k, VF_TOPK_MAX);
+    if (sample_first && temperature < 0.f) return vf_fail(VF_ERR_ARG, "temperature < 0");
+    if (sample_first && temperature > 0.f && !u_dev) return vf_fail(VF_ERR_ARG, "u_dev is NULL");
+    if (s->len_ub + n_tokens > s->capacity)
+        return vf_fail(VF_ERR_CAP, "KV cache: %d + %d > capacity %d", s->len_ub, n_tokens, s->capacity);
+    hipStream_t st = (hipStream_t)stream;
+    const vf_config &c = m->cfg;
+    Batch b;
+    b.n_seqs = 1;
+    b.total_rows = n_tokens;
+    b.s[0] = describe(s, 0, n_tokens);
+    int tail = 0, rc;
+    if ((rc = run_layers(m, b, tokens_dev, &tail, st))) return rc;
+    { ProfScope ps(m, VF_SITE_SMALL, st);
+      if ((rc = vf_launch_norm(m, m->final_norm, m->x, m->part, tail, n_tokens, n_tokens, st))) return rc; }
+    GemmPlan p = vf_gemm_plan(m, c.vocab, c.d_model, n_tokens, 1);
+    const float *last_row;
+    if (p.tnb) {
+        // many rows: the candidates leave the GEMM's epilogue, one list per (row, column tile)
+        const int n_tiles = (c.vocab / 16 + p.tnb - 1) / p.tnb;
+        p.topk = top_k;
+        p.topk_ids = m->topk_cand_i;
+        { ProfScope ps(m, VF_SITE_HEAD, st);
+          if ((rc = vf_launch_gemm(m, m->lm_head, m->x, m->topk_cand_v, c.vocab, c.d_model, n_tokens, 0, n_tokens,
+                                   n_tokens, p, st))) return rc; }
+        if ((rc = vf_launch_topk_merge(m, n_tokens, n_tiles, top_k, topk_logit_dev, topk_id_dev, st))) return rc;
+        if (sample_first) {  // the last row's logits in full, for the draw of the first token
+            GemmPlan p1 = vf_gemm_plan(m, c.vocab, c.d_model, n_tokens, 1);
+            ProfScope ps(m, VF_SITE_HEAD, st);
+            if ((rc = vf_launch_gemm(m, m->lm_head, m->x, m->logits - (size_t)(n_tokens - 1) * c.vocab, c.vocab,
+                                     c.d_model, n_tokens, n_tokens - 1, n_tokens, n_tokens, p1, st))) return rc;
+        }
+        last_row = m->logits;
+    } else {
+        { ProfScope ps(m, VF_SITE_HEAD, st);
+          if ((rc = vf_launch_gemm(m, m->lm_head, m->x, m->logits, c.vocab, c.d_model, n_tokens, 0, n_tokens, n_tokens,
+                                   p, st))) return rc; }
+        if ((rc = vf_launch_topk_slices(m, m->logits, n_tokens, top_k, st))) return rc;
+        if ((rc = vf_launch_topk_merge(m, n_tokens, VF_STAT_CHUNKS, top_k, topk_logit_dev, topk_id_dev, st))) return rc;
+        last_row = m->logits + (size_t)(n_tokens - 1) * c.vocab;
     }
     if (sample_first)
         if ((rc = vf_launch_first_token(m, b.s[0], last_row, u_dev, temperature, st))) return rc;

@@ -119,7 +119,13 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) VF_MFMA_KERNEL void gemm_bf16_kern
 // what they fetch is not used), so the wait before a set's LDS stores leaves the other sets' loads
 // in flight, and the barrier orders LDS traffic only.
 //
-// SWIGLU (gate/up matrix, no K split): instead of partial sums the kernel writes
+// EPI = ROWS_EPI_TOPK (output head, no K split): instead of the logits the kernel writes, per row and
+// column tile, the `topk` largest of the tile's TNB * 16 values with their column ids, in falling
+// order, equal values by rising id: candidates for the per-row merge (topk.hip).  A lane holds
+// TNB * 4 values of a row and the four lanes l, l + 16, l + 32, l + 48 share a row: one round per
+// result, in which every lane offers its best remaining value and two shuffles pick the row's.
+//
+// EPI = ROWS_EPI_SWIGLU (gate/up matrix, no K split): instead of partial sums the kernel writes
 // a = bf16(silu(gate) * up) in activation layout.  Weight block 2j holds gate columns 16j.. and
 // block 2j+1 the matching up columns, so a pair of accumulators of one lane holds both factors.
 // wavefronts per workgroup and register sets of the two tile shapes
@@ -135,10 +141,13 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) VF_MFMA_KERNEL void gemm_bf16_kern
 #ifndef ROWS_SETS_NARROW
 #define ROWS_SETS_NARROW 2
 #endif
-template <int TNB, int MB, int KSTEP, int NW, int NSETS, bool SWIGLU>
+constexpr int ROWS_EPI_PARTIAL = 0, ROWS_EPI_SWIGLU = 1, ROWS_EPI_TOPK = 2;
+template <int TNB, int MB, int KSTEP, int NW, int NSETS, int EPI>
 __global__ __launch_bounds__(NW * 64) VF_MFMA_KERNEL
 void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp, float *__restrict__ part, int N,
-                      int KB, int ncb, int row_lo, int row_hi, int ld_rows, int kb_per_split) {
+                      int KB, int ncb, int row_lo, int row_hi, int ld_rows, int kb_per_split,
+                      int32_t *__restrict__ cand_i, int topk) {
+    constexpr bool SWIGLU = EPI == ROWS_EPI_SWIGLU;
     static_assert(!SWIGLU || TNB % 2 == 0, "gate and up blocks come in pairs");
     static_assert(NSETS % 2 == 0, "set s is staged in LDS buffer s & 1");
     constexpr int NT = NW * 64;
@@ -234,7 +243,48 @@ void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp
             kb += KSTEP;
         }
     }
-    if constexpr (SWIGLU) {
+    if constexpr (EPI == ROWS_EPI_TOPK) {
+        constexpr int NV = TNB * 4;
+        const int g4 = lane >> 4, n_tiles = gridDim.x;
+        float *cand_v = part;
+        auto first_of = [](float av, int ai, float bv, int bi) { return av > bv || (av == bv && ai < bi); };
+#pragma unroll
+        for (int c = 0; c < WC; ++c) {
+            const int row = (cb0 + wave * WC + c) * 16 + (lane & 15);
+            const bool store = g4 == 0 && row >= row_lo && row < row_hi;
+            const size_t o = ((size_t)row * n_tiles + blockIdx.x) * topk;
+            // this lane's values of the row; columns past N cannot win
+            float v[NV];
+#pragma unroll
+            for (int e = 0; e < NV; ++e) v[e] = nb0 + e / 4 < NBt ? acc[e / 4][c][e % 4] : -INFINITY;
+            const int id0 = nb0 * 16 + g4 * 4;  // id of element e: id0 + 16 * (e / 4) + e % 4
+            // one round per result: the best remaining element of the lane, then of the four lanes of
+            // the row (l, l + 16, l + 32, l + 48); the lane that owns the winner retires it
+#pragma unroll 1
+            for (int r = 0; r < topk; ++r) {
+                float bv = -INFINITY;
+                int bi = 0x7fffffff;
+#pragma unroll
+                for (int e = 0; e < NV; ++e) {
+                    const int id = id0 + 16 * (e / 4) + e % 4;
+                    if (v[e] != -INFINITY && first_of(v[e], id, bv, bi)) { bv = v[e]; bi = id; }
+                }
+#pragma unroll
+                for (int off = 16; off <= 32; off <<= 1) {
+                    const float ov = __shfl_xor(bv, off, 64);
+                    const int oi = __shfl_xor(bi, off, 64);
+                    if (first_of(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+                }
+#pragma unroll
+                for (int e = 0; e < NV; ++e)
+                    if (id0 + 16 * (e / 4) + e % 4 == bi) v[e] = -INFINITY;
+                if (store) {
+                    cand_v[o + r] = bv;
+                    cand_i[o + r] = bi == 0x7fffffff ? -1 : bi;
+                }
+            }
+        }
+    } else if constexpr (SWIGLU) {
         u32x2 *a_out = reinterpret_cast<u32x2 *>(part);  // [kb][cb][lane] fragments of 16 bytes, two halves each
         const int g4 = lane >> 4;
 #pragma unroll
@@ -325,7 +375,7 @@ int launch_bf16(const vf_model *m, const void *W, const void *X, float *part, in
 }  // namespace
 
 GemmPlan vf_gemm_plan(const vf_model *m, int N, int K, int rows, int force_single) {
-    GemmPlan p{1, 1, 0, 0};
+    GemmPlan p{1, 1, 0, 0, 0, nullptr};
     if (m->cfg.dtype == VF_F32) return p;
     const int NBt = N >> 4, KB = K >> 5;
     if (rows > 64 && m->fast_path) {
@@ -363,16 +413,21 @@ int vf_launch_gemm(const vf_model *m, const void *W, const void *X, float *part,
         dim3 grid((NBt + plan.tnb - 1) / plan.tnb, plan.ks, (cbs + mb - 1) / mb);
         auto go = [&](auto kern, int nw) {
             hipLaunchKernelGGL(kern, grid, dim3(nw * 64), 0, st, (const u32x4 *)W, (const u32x4 *)X, part, N, KB, ncb,
-                               row_lo, row_hi, ld_rows, kbps);
+                               row_lo, row_hi, ld_rows, kbps, plan.topk_ids, plan.topk);
         };
-        if (plan.swiglu) {
-            if (plan.ks != 1) return vf_fail(VF_ERR_ARG, "the fused SwiGLU epilogue takes no K split");
-            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, 1, ROWS_NW_WIDE, ROWS_SETS_WIDE, true>, ROWS_NW_WIDE);
-            else go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, true>, ROWS_NW_NARROW);
+        if ((plan.swiglu || plan.topk) && plan.ks != 1)
+            return vf_fail(VF_ERR_ARG, "the fused epilogues take no K split");
+        if (plan.topk) {
+            if (plan.topk > VF_TOPK_MAX || !plan.topk_ids) return vf_fail(VF_ERR_ARG, "top-k epilogue: k %d", plan.topk);
+            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, 1, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_TOPK>, ROWS_NW_WIDE);
+            else go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, ROWS_EPI_TOPK>, ROWS_NW_NARROW);
+        } else if (plan.swiglu) {
+            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, 1, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_SWIGLU>, ROWS_NW_WIDE);
+            else go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, ROWS_EPI_SWIGLU>, ROWS_NW_NARROW);
         } else if (plan.tnb == 8) {
-            go(gemm_rows_kernel<8, 16, 1, ROWS_NW_WIDE, ROWS_SETS_WIDE, false>, ROWS_NW_WIDE);
+            go(gemm_rows_kernel<8, 16, 1, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_PARTIAL>, ROWS_NW_WIDE);
         } else {
-            go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, false>, ROWS_NW_NARROW);
+            go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, ROWS_EPI_PARTIAL>, ROWS_NW_NARROW);
         }
         VF_LAUNCH_CHECK("gemm_rows");
         return VF_OK;

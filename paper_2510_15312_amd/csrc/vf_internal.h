@@ -92,6 +92,8 @@ struct vf_model {
     int32_t *scratch_i32;       // [64]
     float *ss;                  // per-16-column sums of squares of h rows, [d/16][64]
     int32_t *counters;          // split-K arrival counters, [VF_N_COUNTERS], zero between kernels
+    float *topk_cand_v;         // top-k candidates per (row, vocabulary slice), [R, slices, VF_TOPK_MAX]
+    int32_t *topk_cand_i;
     tree_mask_t *tree_anc;      // tree verify: ancestor mask of every row of the call, [R]
     int32_t *tree_depth;        // tree verify: depth of every row, [R]
     int fast_path;              // option: use the few-row kernels when they apply
@@ -225,6 +227,8 @@ struct GemmPlan {
     int nbw;       // n-blocks per wavefront
     int tnb;       // > 0: many-row kernel with this many weight blocks per workgroup
     int swiglu;    // many-row kernel only: write bf16(silu(gate) * up) in activation layout, not partials
+    int topk;      // many-row kernel only, > 0: write this many top candidates per (row, column tile), not partials
+    int32_t *topk_ids;  // their ids (the values go where the partials would)
 };
 GemmPlan vf_gemm_plan(const vf_model *m, int N, int K, int rows, int force_single);
 // Y partials [ks][R][N] (R = ld_rows) for rows [row_lo, row_hi) of X.
@@ -275,5 +279,14 @@ bool vf_fused_ok(const vf_model *m, const Batch &b);
 int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, bool tree, hipStream_t st);
 int vf_fused_check(vf_model *m);
 size_t vf_fused_part_floats(const vf_config &c);
+// per-row top-k of logits: candidates per vocabulary slice into the model's candidate buffers, then the merge
+int vf_launch_topk_slices(const vf_model *m, const float *logits, int rows, int K, hipStream_t st);
+int vf_launch_topk_merge(const vf_model *m, int rows, int n_slices, int K, float *out_v, int32_t *out_i,
+                         hipStream_t st);
+// most (row, slice) candidate lists a row can have: slices of the slice kernel or column tiles of the GEMM
+inline int vf_topk_max_slices(const vf_config &c) {
+    const int tiles = (c.vocab / 16 + 3) / 4;  // narrow GEMM tile: four 16-column blocks
+    return tiles > VF_STAT_CHUNKS ? tiles : VF_STAT_CHUNKS;
+}
 int vf_launch_first_token(const vf_model *m, const SeqDesc &s, const float *logits_row, const float *u,
                           float temperature, hipStream_t st);

@@ -28,7 +28,7 @@ def test_every_declared_function_is_exported():
 
 def test_constants_match_header():
     text = open(os.path.join(ROOT, "include", "vf.h")).read()
-    for name in ("VF_MAX_BATCH", "VF_MAX_DRAFTS", "VF_F32", "VF_BF16", "VF_GREEDY", "VF_STOCHASTIC"):
+    for name in ("VF_MAX_BATCH", "VF_MAX_DRAFTS", "VF_TOPK_MAX", "VF_F32", "VF_BF16", "VF_GREEDY", "VF_STOCHASTIC"):
         m = re.search(rf"#define\s+{name}\s+\(?(-?\d+)\)?", text)
         assert int(m.group(1)) == getattr(vf, name), name
     assert C.sizeof(vf.binding.vf_config) == 14 * 4
