@@ -18,6 +18,8 @@ Paper anchors (section / table):
                                             -- Sec. 4, workflow
   * top successors of every prefill position from the prefill logits
                                             -- Sec. 4.2, workflow step "Sample"
+  * retrieval drafts: what followed the longest earlier occurrence of the
+    text's suffix                           -- Sec. 3, Sec. 5.1
   * fixed-size chunked prefill              -- Sec. 2 / Sec. 4.1
   * "executing the short graph several times equals one long execution"
                                             -- Sec. 4.1 (equivalence insight)
@@ -32,9 +34,10 @@ from .acceptance import greedy_accept, stochastic_accept, first_token
 from .reuse import reuse_segment, ReusePool
 from .tree import verify_tree, tree_greedy_accept, tree_stochastic_accept, compact
 from .calibration import topk_rows
+from .drafter import suffix_match_draft
 
 __all__ = [
     "round_bf16", "ModelSpec", "Weights", "KVCache", "forward", "prefill",
     "verify", "greedy_accept", "stochastic_accept", "first_token", "reuse_segment", "ReusePool",
-    "verify_tree", "tree_greedy_accept", "tree_stochastic_accept", "compact", "topk_rows",
+    "verify_tree", "tree_greedy_accept", "tree_stochastic_accept", "compact", "topk_rows", "suffix_match_draft",
 ]
