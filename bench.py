@@ -348,6 +348,20 @@ def main():
         topk_ms[fused] = (time.time() - t0) * 1e3
     res["prefill_top8"] = {"ms": round(topk_ms[True], 1), "ms_all_logits_then_library_topk": round(topk_ms[False], 1),
                            "tokens": cfg.ctx, "chunk": cfg.chunk}
+    # the same context pushed through the verify path in pieces of 32 rows (what a graph fixed to the
+    # verify shape would do with a prefill chunk): 64 passes over the weights instead of 8
+    def prefill_by_verify(rows=32):
+        vf.vf_seq_set_len(seq2, 0)
+        for c0 in range(0, cfg.ctx, rows):
+            vf.vf_verify(model, [seq2], ctx[c0:c0 + rows], [0, rows])
+            vf.vf_seq_set_len(seq2, c0 + rows)
+
+    prefill_by_verify()
+    torch.cuda.synchronize()
+    t0 = time.time()
+    prefill_by_verify()
+    torch.cuda.synchronize()
+    res["prefill_top8"]["ms_through_the_verify_path_32_rows"] = round((time.time() - t0) * 1e3, 1)
     del seq2, zall
     res["tree_verify"] = {"us_per_step": round(e0.elapsed_time(e1) * 100.0, 1), "rows": m,
                           "depth": int(max(wl_depths(parents))), "acceptance": "greedy, path compacted"}

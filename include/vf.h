@@ -296,6 +296,15 @@ int vf_reuse_pool_update(vf_reuse_pool *p, const int32_t *drafts_host, int n_dra
  * number of drafts (>= n_fresh), or a negative VF_ERR_* code. */
 int vf_reuse_pool_extend(vf_reuse_pool *p, int32_t *drafts_host, int n_fresh);
 
+/* A retrieval drafter over the token history (paper Sec. 3: the context is the draft source;
+ * Sec. 5.1: suffix-automaton retrieval).  Host memory only, no device work.  Finds the longest
+ * suffix of history_host[0..n) of length min_suffix..max_suffix that also occurs earlier (ending
+ * before the last token), takes its most recent such occurrence and copies up to k tokens that
+ * followed it (the copy stops at the end of the history) to drafts_host.  Returns the number of
+ * drafts written (0 if no suffix matches), or a negative VF_ERR_* code.  k <= VF_MAX_DRAFTS. */
+int vf_draft_suffix_match(const int32_t *history_host, int n, int max_suffix, int min_suffix, int k,
+                          int32_t *drafts_host);
+
 /* ---- options ---------------------------------------------------------------------------------- */
 
 /* VF_OPT_FAST_PATH (default 1): vf_verify on a bfloat16 model with at most 48 rows in total runs

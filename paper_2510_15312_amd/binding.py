@@ -28,7 +28,7 @@ EXPORTS = [
     "vf_seq_set_pending", "vf_seq_get_state", "vf_kv_read", "vf_kv_write", "vf_prefill_chunk", "vf_verify",
     "vf_accept", "vf_profile", "vf_profile_read", "vf_set_option", "vf_stream_read",
     "vf_reuse_select", "vf_reuse_pool_init", "vf_reuse_pool_update", "vf_reuse_pool_extend",
-    "vf_verify_tree", "vf_accept_tree", "vf_prefill_chunk_topk",
+    "vf_verify_tree", "vf_accept_tree", "vf_prefill_chunk_topk", "vf_draft_suffix_match",
 ]
 SITES = ["qkv", "o", "gateup", "down", "head", "attn", "small", "accept", "step"]
 
@@ -93,6 +93,7 @@ def _load():
         "vf_profile": (C.c_int, [vp, C.c_int]),
         "vf_stream_read": (C.c_int, [vp, C.POINTER(sz), vp]),
         "vf_profile_read": (C.c_int, [vp, C.POINTER(C.c_float), C.POINTER(i32)]),
+        "vf_draft_suffix_match": (C.c_int, [C.POINTER(i32), C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(i32)]),
         "vf_prefill_chunk_topk": (C.c_int, [vp, vp, vp, C.c_int, C.c_int, vp, vp, C.c_int, vp, C.c_float, vp]),
         "vf_verify_tree": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(i32), vp, vp]),
         "vf_accept_tree": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(i32),
@@ -290,6 +291,17 @@ def vf_accept_tree(model, seqs, tokens, row_off, parents, params, n_accept, out_
                                  u.data_ptr() if u is not None else None)
     _check(lib.vf_accept_tree(model.handle, hs, len(seqs), _ptr(tokens), ro, par, ps, _ptr(logits), _ptr(n_accept),
                               _ptr(out_tokens), _ptr(y), _ptr(path), _stream()))
+
+
+def vf_draft_suffix_match(history, k, max_suffix, min_suffix=1):
+    """history: host ints; returns the list of drafts (possibly empty)."""
+    n = len(history)
+    arr = (C.c_int32 * max(1, n))(*[int(t) for t in history])
+    out = (C.c_int32 * VF_MAX_DRAFTS)()
+    got = lib.vf_draft_suffix_match(arr, n, int(max_suffix), int(min_suffix), int(k), out)
+    if got < 0:
+        _check(got)
+    return list(out[:got])
 
 
 def vf_reuse_select(tokens, row_off, y, n_accept, seg):

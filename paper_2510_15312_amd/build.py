@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libvf.so")
-SOURCES = ["api.hip", "gemm.hip", "elementwise.hip", "attention.hip", "accept.hip", "fast.hip", "fused.hip", "reuse.hip", "topk.hip"]
+SOURCES = ["api.hip", "gemm.hip", "elementwise.hip", "attention.hip", "accept.hip", "fast.hip", "fused.hip", "reuse.hip", "topk.hip", "draft.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -50,3 +50,35 @@ def test_reuse_argument_errors():
     assert L.vf_reuse_select(0, None, ro, None, None, None, None) == vf.VF_ERR_ARG
     assert L.vf_reuse_select(vf.VF_MAX_BATCH + 1, None, ro, None, None, None, None) == vf.VF_ERR_ARG
     assert vf.lib.vf_last_error()
+
+
+@settings(max_examples=300, deadline=None)
+@given(st.lists(st.integers(0, 2), min_size=0, max_size=60), st.integers(0, 8), st.integers(1, 6), st.integers(1, 3))
+def test_retrieval_drafter_follows_the_oracle(history, k, max_suffix, min_suffix):
+    from oracle.drafter import suffix_match_draft
+    if min_suffix > max_suffix:
+        min_suffix = max_suffix
+    assert vf.vf_draft_suffix_match(history, k, max_suffix, min_suffix) == suffix_match_draft(history, k, max_suffix,
+                                                                                             min_suffix)
+
+
+def test_retrieval_drafter_hand_worked_cases_and_errors():
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    n = 0
+    for line in open(os.path.join(here, "golden", "drafter_cases.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        hist, k, mx, mn, want = [[int(t) for t in f.split()] for f in line.split("|")]
+        assert vf.vf_draft_suffix_match(hist, k[0], mx[0], mn[0]) == want, line
+        n += 1
+    assert n == 8
+    L = vf.lib
+    h = (C.c_int32 * 4)(1, 2, 1, 2)
+    out = (C.c_int32 * 32)()
+    assert L.vf_draft_suffix_match(None, 4, 2, 1, 2, out) == vf.VF_ERR_ARG
+    assert L.vf_draft_suffix_match(h, 4, 0, 1, 2, out) == vf.VF_ERR_ARG
+    assert L.vf_draft_suffix_match(h, 4, 2, 3, 2, out) == vf.VF_ERR_ARG
+    assert L.vf_draft_suffix_match(h, 4, 2, 1, 33, out) == vf.VF_ERR_ARG
+    assert L.vf_draft_suffix_match(h, 4, 2, 1, 2, None) == vf.VF_ERR_ARG
+    assert L.vf_draft_suffix_match(h, 4, 2, 1, 0, None) == 0
