@@ -46,6 +46,9 @@ constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (s
 #ifndef FUSED_PD_DOWN
 #define FUSED_PD_DOWN 5            // ring depth of the down projection (nine fragments per wavefront at the 1.5B shape)
 #endif
+#ifndef FUSED_AHEAD
+#define FUSED_AHEAD 3          // gate/up, down and head phases: this many steps of the item after next are held in registers too (0: off)
+#endif
 #ifndef FUSED_MAXP
 #define FUSED_MAXP 8              // most key parts per attention block (at most 8: the merge holds them all)
 #endif
@@ -237,10 +240,21 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 
     global_w_ptr wp[UB], wpn[UB];
     u32x4 w[PD][UB];
+    // AHEAD: a second set of registers holds the first round of the item after next, so that two
+    // items' worth of weights are requested before the barrier and during every item
+    // slots of the second set; none with three row blocks, whose accumulators leave no room
+    constexpr int A2 = (FUSED_AHEAD > 0 && UB == 2 && NB <= 2) ? (FUSED_AHEAD < PD ? FUSED_AHEAD : PD) : 0;
+    constexpr bool AHEAD = A2 > 0;
+    global_w_ptr wpa[UB];
+    u32x4 w2[AHEAD ? A2 : 1][UB];
 #pragma unroll
     for (int d = 0; d < PD; ++d)
 #pragma unroll
         for (int u = 0; u < UB; ++u) w[d][u] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int d = 0; d < (AHEAD ? A2 : 1); ++d)
+#pragma unroll
+        for (int u = 0; u < UB; ++u) w2[d][u] = u32x4{0u, 0u, 0u, 0u};
     auto unit_ptrs = [&](int it, global_w_ptr (&dst)[UB]) {
         const int unit = (wg + it * G) / g.ks;
 #pragma unroll
@@ -258,6 +272,13 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
         for (int d = 0; d < PD; ++d)
 #pragma unroll
             for (int u = 0; u < UB; ++u) w[d][u] = frag(wp[u], min(d, cnt - 1));
+        if (AHEAD && n_my > 1) {
+            unit_ptrs(1, wpa);
+#pragma unroll
+            for (int d = 0; d < A2; ++d)
+#pragma unroll
+                for (int u = 0; u < UB; ++u) w2[d][u] = frag(wpa[u], min(d, cnt - 1));
+        }
     };
     if (FUSED_PREFETCH_EARLY && n_my > 0) first_fragments();
     TRACE(1);
@@ -364,7 +385,9 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 
     for (int it = 0; it < n_my; ++it) {
         const bool has_next = it + 1 < n_my;
+        const bool has_ahead = AHEAD && it + 2 < n_my;
         unit_ptrs(has_next ? it + 1 : it, wpn);
+        if (AHEAD) unit_ptrs(has_ahead ? it + 2 : it, wpa);
         const int unit = (wg + it * G) / g.ks;
         const int nb0 = unit * UB;
         floatx4 acc[UB][NB];
@@ -390,8 +413,18 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 #pragma unroll
                 for (int u = 0; u < UB; ++u) a[u] = __builtin_bit_cast(bf16x8, live ? w[d][u] : u32x4{0u, 0u, 0u, 0u});
                 if (REFILL) {
+                    if (AHEAD && d < A2 && last_round) {
+                        // the next item's first round is already here; its slot takes the one after
 #pragma unroll
-                    for (int u = 0; u < UB; ++u) w[d][u] = frag(rp[u], min(rbase + d, cnt - 1));
+                        for (int u = 0; u < UB; ++u) w[d][u] = w2[d][u];
+                        if (has_ahead) {
+#pragma unroll
+                            for (int u = 0; u < UB; ++u) w2[d][u] = frag(wpa[u], min(d, cnt - 1));
+                        }
+                    } else {
+#pragma unroll
+                        for (int u = 0; u < UB; ++u) w[d][u] = frag(rp[u], min(rbase + d, cnt - 1));
+                    }
                 }
                 const int kx = min(wk0 + min(kbl, cnt - 1), kb1 - 1) - kb0;
 #pragma unroll
