@@ -160,13 +160,16 @@ def main():
     seq = vf.vf_seq_create(model, cap)
     ctx = torch.as_tensor(wl.make_context(V, cfg.ctx, s.context), device="cuda:0")
     u0 = torch.as_tensor(wl.make_uniforms(1, s.uniforms)[:1], device="cuda:0")
-    torch.cuda.synchronize()
-    t0 = time.time()
-    for c0 in range(0, cfg.ctx, cfg.chunk):
-        last = c0 + cfg.chunk >= cfg.ctx
-        vf.vf_prefill_chunk(model, seq, ctx[c0:c0 + cfg.chunk], sample_first=last, u=u0, temperature=temp)
-    torch.cuda.synchronize()
-    prefill_ms = (time.time() - t0) * 1e3
+    # twice: the first pass also loads the kernels; the second one, over the same positions, is timed
+    for timed in (False, True):
+        vf.vf_seq_set_len(seq, 0)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        for c0 in range(0, cfg.ctx, cfg.chunk):
+            last = c0 + cfg.chunk >= cfg.ctx
+            vf.vf_prefill_chunk(model, seq, ctx[c0:c0 + cfg.chunk], sample_first=last, u=u0, temperature=temp)
+        torch.cuda.synchronize()
+        prefill_ms = (time.time() - t0) * 1e3
     len0, pending0 = vf.vf_seq_get_state(seq)
     assert len0 == cfg.ctx
     # flops of the chunked prefill: every layer weight twice per token, plus Q K^T and P V over the causal context

@@ -330,7 +330,10 @@ __global__ __launch_bounds__(256) VF_MFMA_KERNEL void attn_fast_kernel(Batch b, 
 // softmax state per item block; the eight states are merged through LDS at the end, so nothing
 // partial leaves the workgroup.  Output in the bf16 activation (MFMA B-operand) layout the
 // general GEMM reads.
-constexpr int ROWS_QB = 2, ROWS_WAVES = 8;
+#ifndef ROWS_QB_N
+#define ROWS_QB_N 1
+#endif
+constexpr int ROWS_QB = ROWS_QB_N, ROWS_WAVES = 8;
 
 template <int HD>
 __global__ __launch_bounds__(ROWS_WAVES * 64) void attn_rows_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
