@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 GATEUP_TRAFFIC_BYTES = None
 # The same for one launch of the persistent whole-pass kernel (profiles/verify_fused_1.5b_k16_pmc.md); set to
 # None whenever that kernel changes.
-FUSED_TRAFFIC_BYTES = 3_534_800_000
+FUSED_TRAFFIC_BYTES = 3_535_400_000
 
 
 def log(*a):
@@ -129,8 +129,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--persistent", type=int, default=None,
                     help="1: the persistent whole-pass kernel, 0: one kernel per GEMM (default: the library's default)")
+    ap.add_argument("--no-side-measurements", action="store_true",
+                    help="skip the tree step, the top-k prefill and the prefill through the verify shape (profile "
+                         "runs: every launch of the step's kernel then belongs to the timed workload)")
     ap.add_argument("--pmc-calibration", action="store_true",
-                    help="also run one plain 1 GiB device copy, the yardstick for hardware byte counters")
+                    help="for counter-collection runs: also run one plain 1 GiB device copy (the yardstick for hardware "
+                         "byte counters) and skip the side measurements (tree step, top-k prefill)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the draft-verify step is a single-GPU path here "
@@ -304,70 +308,72 @@ def main():
                           "step_vs_stream_read": round(gbs / stream_gbs, 4)}
     # determinism: the timed replay must have walked the recorded trajectory
     assert ln_end == lens[K], (ln_end, lens[K])
-    # the same step on tree-structured drafts: m rows as a random tree (chains with side branches),
-    # greedy acceptance with compaction of the accepted path; the length is put back before each step
-    trng = np.random.default_rng(15312)
-    parents = [-1] + [i - 1 if trng.random() > 0.5 else int(trng.integers(0, i)) for i in range(1, m)]
-    ttok = torch.as_tensor(trng.integers(0, V, m).astype(np.int32), device="cuda:0")
-    path_t = torch.zeros(m, dtype=torch.int32, device="cuda:0")
-    tparams = [(vf.VF_GREEDY, 0.0, None, None)]
-    reset()
+    # (skipped in profile runs, whose per-kernel averages should cover the timed workload only)
+    if not (args.pmc_calibration or args.no_side_measurements):
+        # the same step on tree-structured drafts: m rows as a random tree (chains with side branches),
+        # greedy acceptance with compaction of the accepted path; the length is put back before each step
+        trng = np.random.default_rng(15312)
+        parents = [-1] + [i - 1 if trng.random() > 0.5 else int(trng.integers(0, i)) for i in range(1, m)]
+        ttok = torch.as_tensor(trng.integers(0, V, m).astype(np.int32), device="cuda:0")
+        path_t = torch.zeros(m, dtype=torch.int32, device="cuda:0")
+        tparams = [(vf.VF_GREEDY, 0.0, None, None)]
+        reset()
 
-    def tree_step():
-        vf.vf_seq_set_len(seq, len0)
-        vf.vf_verify_tree(model, [seq], ttok, [0, m], parents)
-        vf.vf_accept_tree(model, [seq], ttok, [0, m], parents, tparams, n_acc, out_t, y_t, path_t)
+        def tree_step():
+            vf.vf_seq_set_len(seq, len0)
+            vf.vf_verify_tree(model, [seq], ttok, [0, m], parents)
+            vf.vf_accept_tree(model, [seq], ttok, [0, m], parents, tparams, n_acc, out_t, y_t, path_t)
 
-    for _ in range(3):
-        tree_step()
-    e0.record()
-    for _ in range(10):
-        tree_step()
-    e1.record()
-    torch.cuda.synchronize()
-    # chunked prefill that also hands back the top-8 successors of every position (the input of the
-    # calibration step), against the same prefill returning all logits followed by a library top-k
-    seq2 = vf.vf_seq_create(model, cfg.ctx + 8)
-    tv = torch.empty((cfg.chunk, 8), dtype=torch.float32, device="cuda:0")
-    ti = torch.empty((cfg.chunk, 8), dtype=torch.int32, device="cuda:0")
-    zall = torch.empty((cfg.chunk, V), dtype=torch.float32, device="cuda:0")
+        for _ in range(3):
+            tree_step()
+        e0.record()
+        for _ in range(10):
+            tree_step()
+        e1.record()
+        torch.cuda.synchronize()
+        # chunked prefill that also hands back the top-8 successors of every position (the input of the
+        # calibration step), against the same prefill returning all logits followed by a library top-k
+        seq2 = vf.vf_seq_create(model, cfg.ctx + 8)
+        tv = torch.empty((cfg.chunk, 8), dtype=torch.float32, device="cuda:0")
+        ti = torch.empty((cfg.chunk, 8), dtype=torch.int32, device="cuda:0")
+        zall = torch.empty((cfg.chunk, V), dtype=torch.float32, device="cuda:0")
 
-    def prefill_topk(fused):
-        vf.vf_seq_set_len(seq2, 0)
-        for c0 in range(0, cfg.ctx, cfg.chunk):
-            if fused:
-                vf.vf_prefill_chunk_topk(model, seq2, ctx[c0:c0 + cfg.chunk], 8, tv, ti)
-            else:
-                vf.vf_prefill_chunk(model, seq2, ctx[c0:c0 + cfg.chunk], logits_mode=2, logits_out=zall)
-                torch.topk(zall, 8, dim=-1)
+        def prefill_topk(fused):
+            vf.vf_seq_set_len(seq2, 0)
+            for c0 in range(0, cfg.ctx, cfg.chunk):
+                if fused:
+                    vf.vf_prefill_chunk_topk(model, seq2, ctx[c0:c0 + cfg.chunk], 8, tv, ti)
+                else:
+                    vf.vf_prefill_chunk(model, seq2, ctx[c0:c0 + cfg.chunk], logits_mode=2, logits_out=zall)
+                    torch.topk(zall, 8, dim=-1)
 
-    topk_ms = {}
-    for fused in (True, False):
-        prefill_topk(fused)
+        topk_ms = {}
+        for fused in (True, False):
+            prefill_topk(fused)
+            torch.cuda.synchronize()
+            t0 = time.time()
+            prefill_topk(fused)
+            torch.cuda.synchronize()
+            topk_ms[fused] = (time.time() - t0) * 1e3
+        res["prefill_top8"] = {"ms": round(topk_ms[True], 1), "ms_all_logits_then_library_topk": round(topk_ms[False], 1),
+                               "tokens": cfg.ctx, "chunk": cfg.chunk}
+        # the same context pushed through the verify path in pieces of 32 rows (what a graph fixed to the
+        # verify shape would do with a prefill chunk): 64 passes over the weights instead of 8
+        def prefill_by_verify(rows=32):
+            vf.vf_seq_set_len(seq2, 0)
+            for c0 in range(0, cfg.ctx, rows):
+                vf.vf_verify(model, [seq2], ctx[c0:c0 + rows], [0, rows])
+                vf.vf_seq_set_len(seq2, c0 + rows)
+
+        prefill_by_verify()
         torch.cuda.synchronize()
         t0 = time.time()
-        prefill_topk(fused)
+        prefill_by_verify()
         torch.cuda.synchronize()
-        topk_ms[fused] = (time.time() - t0) * 1e3
-    res["prefill_top8"] = {"ms": round(topk_ms[True], 1), "ms_all_logits_then_library_topk": round(topk_ms[False], 1),
-                           "tokens": cfg.ctx, "chunk": cfg.chunk}
-    # the same context pushed through the verify path in pieces of 32 rows (what a graph fixed to the
-    # verify shape would do with a prefill chunk): 64 passes over the weights instead of 8
-    def prefill_by_verify(rows=32):
-        vf.vf_seq_set_len(seq2, 0)
-        for c0 in range(0, cfg.ctx, rows):
-            vf.vf_verify(model, [seq2], ctx[c0:c0 + rows], [0, rows])
-            vf.vf_seq_set_len(seq2, c0 + rows)
-
-    prefill_by_verify()
-    torch.cuda.synchronize()
-    t0 = time.time()
-    prefill_by_verify()
-    torch.cuda.synchronize()
-    res["prefill_top8"]["ms_through_the_verify_path_32_rows"] = round((time.time() - t0) * 1e3, 1)
-    del seq2, zall
-    res["tree_verify"] = {"us_per_step": round(e0.elapsed_time(e1) * 100.0, 1), "rows": m,
-                          "depth": int(max(wl_depths(parents))), "acceptance": "greedy, path compacted"}
+        res["prefill_top8"]["ms_through_the_verify_path_32_rows"] = round((time.time() - t0) * 1e3, 1)
+        del seq2, zall
+        res["tree_verify"] = {"us_per_step": round(e0.elapsed_time(e1) * 100.0, 1), "rows": m,
+                              "depth": int(max(wl_depths(parents))), "acceptance": "greedy, path compacted"}
     if args.pmc_calibration:
         a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda:0")
         b = torch.empty_like(a)
