@@ -579,7 +579,7 @@ __device__ __forceinline__ AttItem att_item(const FusedArgs &a, const Batch &b, 
 template <int HD>
 __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, int layer, const bf16_t *q, bf16_t *o,
                                   int len0, GridBar &bar, unsigned char *smem, FusedShared &sh TRACE_ARG) {
-    constexpr int KD = HD / 32, DB = HD / 16, REC = HD + ATTF_STRIDE_PAD, MAXP = 8;
+    constexpr int KD = HD / 32, DB = HD / 16, REC = HD + ATTF_STRIDE_PAD, MAXP = FUSED_MAXP;
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     const int lane = tid & 63, wave = tid >> 6, g4 = lane >> 4, l15 = lane & 15;
