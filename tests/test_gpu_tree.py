@@ -234,3 +234,66 @@ def test_greedy_tree_decoding_is_plain_greedy_decoding_on_the_gpu():
         steps += 1
     print(f"tree decoding: 40 tokens in {steps} steps", flush=True)
     assert got[:40] == want[:40] and steps < 40
+
+
+@pytest.mark.parametrize("fast", [1, 0])
+def test_tree_verify_on_paged_sequences_compacts_across_pages(fast):
+    """Two sequences in one pool with shuffled block tables; the contexts end a few rows before a page
+    boundary, so the tree's rows and the compaction both straddle pages."""
+    cfg = wl.scaled(C["1.5b_k16"], n_layers=2, vocab=4096)
+    pair = Pair(cfg, max_rows=128, max_positions=400)
+    vf.vf_set_option(pair.model, vf.VF_OPT_FAST_PATH, fast)
+    rng = np.random.default_rng(17)
+    n_pages = 10
+    pool = torch.empty(vf.vf_kv_bytes(pair.model, 64, n_pages), dtype=torch.uint8, device=DEV)
+    perm = rng.permutation(n_pages)
+    tables, ctxs, ks = [perm[:5], perm[5:]], [120, 61], [20, 9]
+    seqs, caches, toks, pars, row_off = [], [], [], [], [0]
+    for bt, n_ctx, k in zip(tables, ctxs, ks):
+        seq = pair.new_seq(len(bt) * 64, pool=pool, block_table=i32(bt))
+        cache = oracle.KVCache(pair.spec, len(bt) * 64)
+        pair.prefill_both(seq, cache, wl.make_context(cfg.vocab, n_ctx, rng), 64)
+        t, p = _random_tree(rng, k, cfg.vocab)
+        seqs.append(seq); caches.append(cache); toks.append(t); pars.append(p)
+        row_off.append(row_off[-1] + k + 1)
+    rows = row_off[-1]
+    parents = [p for ps in pars for p in ps]
+    tok_dev = i32(np.concatenate(toks))
+    logits = torch.empty((rows, cfg.vocab), dtype=torch.float32, device=DEV)
+    vf.vf_verify_tree(pair.model, seqs, tok_dev, row_off, parents, logits)
+    torch.cuda.synchronize()
+    z_gpu = logits.cpu().numpy()
+    z_or = np.concatenate([oracle.verify_tree(pair.spec, pair.ow, c, t, p) for c, t, p in zip(caches, toks, pars)])
+    err = rel_inf(z_gpu, z_or).max()
+    print(f"paged tree verify (fast path {fast}): max rel-inf logit error {err:.3e}", flush=True)
+    assert err < 2e-2
+    # accept along a path planted by hand: logits that make the deepest leaf's root path the greedy walk
+    crafted = np.full((rows, cfg.vocab), -5.0, dtype=np.float32)
+    want_paths = []
+    for b, (t, p) in enumerate(zip(toks, pars)):
+        depth = oracle.transformer.tree_depths(p)
+        leaf = int(np.argmax(depth))
+        path, a = [], leaf
+        while a >= 0:
+            path.append(a)
+            a = p[a]
+        path = path[::-1]
+        want_paths.append(path)
+        for parent, child in zip(path[:-1], path[1:]):
+            crafted[row_off[b] + parent, t[child]] = 5.0
+            # an earlier sibling with the same token would be taken instead: make those differ
+            for sib in children_of(p, parent):
+                if sib != child and t[sib] == t[child]:
+                    t[sib] = (t[sib] + 1) % cfg.vocab
+        crafted[row_off[b] + path[-1], 7] = 5.0
+    tok_dev = i32(np.concatenate(toks))
+    n_acc, out, y, path = _gpu_accept_tree(pair, seqs, tok_dev, row_off, parents, [GREEDY] * 2, f32(crafted))
+    for b, (seq, cache, n_ctx) in enumerate(zip(seqs, caches, ctxs)):
+        wp = want_paths[b]
+        a = len(wp) - 1
+        assert a >= 2 and n_acc[b] == a and list(path[row_off[b]:row_off[b] + a + 1]) == wp
+        assert vf.vf_seq_get_state(seq) == (n_ctx + 1 + a, 7)
+        oracle.compact(cache, n_ctx, wp)
+        for layer in (0, cfg.n_layers - 1):
+            (kg, vg), (ko, vo) = pair.kv_both(seq, cache, layer, n_ctx - 3, a + 4)
+            assert np.abs(kg - ko).max() <= 1e-2 * np.abs(ko).max() and np.abs(vg - vo).max() <= 1e-2 * np.abs(vo).max()
