@@ -208,3 +208,99 @@ def test_config4_full_size_properties():
         assert top2[1] - top2[0] <= 2 * err * np.abs(zs[a]).max(), (a, top2)
     print(f"3b full size: accepted {a} of {k} drafts from the target's own continuation", flush=True)
     assert vf.vf_seq_get_state(seq)[0] == cfg.ctx + 1 + a
+
+
+def test_config3_full_size_tree_properties():
+    """1.5B shape at full size, context 2048: properties of the tree verify that hold at any size.
+    A chain is the plain verify bit for bit; a node of a random tree gets the logits that a plain
+    verify of its root path gives to the path's last row (both are GPU results, each allowed 2e-2
+    against the exact model); after acceptance along a planted path the compacted cache continues
+    like the cache of that plain verify."""
+    cfg = C["1.5b_k16"]
+    k, m = cfg.k, cfg.k + 1
+    s = wl.streams(cfg)
+    wd = wl.make_weights(cfg, s.weights)
+    cap = cfg.ctx + 4 * m
+    model = vf.vf_model_create(vf.config_from(cfg, cfg.chunk, cap), vf.upload_weights(wd, cfg.dtype, DEV), DEV)
+    del wd
+    seq = vf.vf_seq_create(model, cap)
+    toks_ctx = i32(wl.make_context(cfg.vocab, cfg.ctx, s.context))
+    print("1.5b full size tree: prefill ...", flush=True)
+    for c0 in range(0, cfg.ctx, cfg.chunk):
+        vf.vf_prefill_chunk(model, seq, toks_ctx[c0:c0 + cfg.chunk])
+    rng = np.random.default_rng(33)
+    tokens = rng.integers(0, cfg.vocab, m).astype(np.int32)
+    tok_dev = i32(tokens)
+
+    def run(fn):
+        z = torch.empty((m, cfg.vocab), dtype=torch.float32, device=DEV)
+        vf.vf_seq_set_len(seq, cfg.ctx)
+        fn(z)
+        torch.cuda.synchronize()
+        return z.cpu().numpy()
+
+    plain = run(lambda z: vf.vf_verify(model, [seq], tok_dev, [0, m], z))
+    chain = run(lambda z: vf.vf_verify_tree(model, [seq], tok_dev, [0, m], [-1] + list(range(k)), z))
+    assert np.array_equal(plain, chain)
+    parents = [-1] + [i - 1 if rng.random() > 0.5 else int(rng.integers(0, i)) for i in range(1, m)]
+    tree = run(lambda z: vf.vf_verify_tree(model, [seq], tok_dev, [0, m], parents, z))
+    depth = [0] * m
+    for i in range(1, m):
+        depth[i] = depth[parents[i]] + 1
+    worst = 0.0
+    for leaf in (int(np.argmax(depth)), m - 1):
+        path, a = [], leaf
+        while a >= 0:
+            path.append(a)
+            a = parents[a]
+        path = path[::-1]
+        pt = i32(tokens[path])
+        zp = torch.empty((len(path), cfg.vocab), dtype=torch.float32, device=DEV)
+        vf.vf_seq_set_len(seq, cfg.ctx)
+        vf.vf_verify(model, [seq], pt, [0, len(path)], zp)
+        torch.cuda.synchronize()
+        err = rel_inf(tree[path], zp.cpu().numpy()).max()
+        worst = max(worst, err)
+        print(f"1.5b full size tree: path of depth {len(path) - 1} to row {leaf}: tree vs plain verify {err:.3e}", flush=True)
+        assert err < 4e-2
+    # acceptance along the deepest path (crafted logits), compaction, then one more plain step:
+    # its logits must match the same step taken after a plain verify + accept of that path
+    leaf = int(np.argmax(depth))
+    path, a = [], leaf
+    while a >= 0:
+        path.append(a)
+        a = parents[a]
+    path = path[::-1]
+    crafted = np.full((m, cfg.vocab), -5.0, dtype=np.float32)
+    tk = tokens.copy()
+    for parent, child in zip(path[:-1], path[1:]):
+        crafted[parent, tk[child]] = 5.0
+        for sib in range(1, m):
+            if parents[sib] == parent and sib != child and tk[sib] == tk[child]:
+                tk[sib] = (tk[sib] + 1) % cfg.vocab
+    crafted[path[-1], 11] = 5.0
+    n_acc = torch.zeros(1, dtype=torch.int32, device=DEV)
+    o_t, y_t, p_t = (torch.zeros(m, dtype=torch.int32, device=DEV) for _ in range(3))
+    greedy = [(vf.VF_GREEDY, 0.0, None, None)]
+    nxt = i32([vf.VF_PENDING, 5, 6, 7])
+    after = []
+    for use_tree in (True, False):
+        vf.vf_seq_set_len(seq, cfg.ctx)
+        if use_tree:
+            vf.vf_verify_tree(model, [seq], i32(tk), [0, m], parents)
+            vf.vf_accept_tree(model, [seq], i32(tk), [0, m], parents, greedy, n_acc, o_t, y_t, p_t, f32(crafted))
+            assert int(n_acc.item()) == len(path) - 1 and p_t.cpu().tolist()[:len(path)] == path
+        else:
+            pt = i32(tk[path])
+            vf.vf_verify(model, [seq], pt, [0, len(path)])
+            vf.vf_accept(model, [seq], pt, [0, len(path)], greedy, n_acc, o_t[:len(path)], y_t[:len(path)],
+                         f32(crafted[path]))
+            assert int(n_acc.item()) == len(path) - 1
+        assert vf.vf_seq_get_state(seq) == (cfg.ctx + len(path), 11)
+        z = torch.empty((4, cfg.vocab), dtype=torch.float32, device=DEV)
+        vf.vf_verify(model, [seq], nxt, [0, 4], z)
+        torch.cuda.synchronize()
+        after.append(z.cpu().numpy())
+    err = rel_inf(after[0], after[1]).max()
+    print(f"1.5b full size tree: next step on the compacted cache vs on the plain cache {err:.3e}", flush=True)
+    assert err < 4e-2
