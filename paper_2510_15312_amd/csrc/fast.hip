@@ -333,19 +333,26 @@ __global__ __launch_bounds__(256) VF_MFMA_KERNEL void attn_fast_kernel(Batch b, 
 #ifndef ROWS_QB_N
 #define ROWS_QB_N 1
 #endif
+#ifndef ROWS_PART_TILES
+#define ROWS_PART_TILES 64   // key tiles (of 32 keys) per workgroup of the many-row attention before the keys are split
+#endif
 constexpr int ROWS_QB = ROWS_QB_N, ROWS_WAVES = 8;
 
 template <int HD>
 __global__ __launch_bounds__(ROWS_WAVES * 64) void attn_rows_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
                                                                    bf16_t *__restrict__ o, int hq, int hkv, int ncb,
-                                                                   float scale_log2e) {
+                                                                   float scale_log2e, int n_parts,
+                                                                   float *__restrict__ part) {
     constexpr int KD = HD / 32, DB = HD / 16;
     extern __shared__ __align__(16) unsigned char rows_smem[];
     floatx4 *o_s = reinterpret_cast<floatx4 *>(rows_smem);                            // [wave][db][lane]
     float *ml_s = reinterpret_cast<float *>(rows_smem + ROWS_WAVES * DB * 64 * 16);  // [wave][2][16]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g4 = lane >> 4, l15 = lane & 15;
-    const int kvh = blockIdx.y;
-    const SeqDesc &s = b.s[blockIdx.z];
+    // n_parts > 1: the keys of a block are shared out over n_parts workgroups (blockIdx.z = sequence *
+    // n_parts + part), each leaving an unnormalised record [max, sum, -, -, O[hd]] per (row, head) for
+    // the merge kernel; long contexts then fill the GPU with more than one workgroup per block
+    const int kvh = blockIdx.y, kpart = blockIdx.z % n_parts;
+    const SeqDesc &s = b.s[blockIdx.z / n_parts];
     const int group = hq / hkv, n_items = s.nrows * group;
     const int item0 = blockIdx.x * (16 * ROWS_QB);
     if (item0 >= n_items) return;
@@ -373,9 +380,11 @@ __global__ __launch_bounds__(ROWS_WAVES * 64) void attn_rows_kernel(Batch b, int
         st[c].l_run = 0.f;
     }
     const int tiles = blk_last[ROWS_QB - 1] / ATT_TILE + 1;  // the last block sees the most keys
+    const int tpp = (tiles + n_parts - 1) / n_parts;
+    const int t_begin = kpart * tpp, t_end = min(tiles, t_begin + tpp);
     AttTile<HD> tile;
 #pragma unroll 1
-    for (int t = wave; t < tiles; t += ROWS_WAVES) {
+    for (int t = t_begin + wave; t < t_end; t += ROWS_WAVES) {
         const int t0 = t * ATT_TILE;
         tile.load(s, layer, hkv, kvh, t, false, lane);
         tile.mask_values(t0, kmax, lane);
@@ -406,7 +415,11 @@ __global__ __launch_bounds__(ROWS_WAVES * 64) void attn_rows_kernel(Batch b, int
                 L += ml_s[(w * 2 + 1) * 16 + l15] * wt;
                 acc += o_s[(w * DB + wave) * 64 + lane] * wt;
             }
-            if (valid[c]) {
+            if (valid[c] && n_parts > 1) {
+                float *rec = part + (((size_t)row[c] * hq + head[c]) * n_parts + kpart) * (HD + ATTF_STRIDE_PAD);
+                if (wave == 0 && g4 == 0) *reinterpret_cast<float2 *>(rec) = float2{M, L};
+                *reinterpret_cast<floatx4 *>(rec + ATTF_STRIDE_PAD + wave * 16 + g4 * 4) = acc;
+            } else if (valid[c]) {
                 const float inv = 1.0f / L;
                 const int k = head[c] * HD + wave * 16 + g4 * 4;
                 *reinterpret_cast<u32x2 *>(o + xfrag_index(row[c], k, ncb)) =
@@ -449,6 +462,24 @@ __global__ __launch_bounds__(HD) void attn_fast_combine_kernel(Batch b, const fl
     }
     for (; i < used; ++i) acc += p[i * REC + ATTF_STRIDE_PAD + d] * ws[i];
     o[(size_t)row * hq * HD + head * HD + d] = (bf16_t)(acc / L);
+}
+
+// The same merge for the many-row kernel's key parts; the output goes to the activation layout.
+template <int HD>
+__global__ __launch_bounds__(HD) void attn_rows_combine_kernel(const float *__restrict__ part, bf16_t *__restrict__ o,
+                                                               int hq, int n_parts, int ncb) {
+    constexpr int REC = HD + ATTF_STRIDE_PAD;
+    const int row = blockIdx.x / hq, head = blockIdx.x % hq, d = threadIdx.x;
+    const float *p = part + ((size_t)row * hq + head) * n_parts * REC;
+    float M = -1e30f;
+    for (int i = 0; i < n_parts; ++i) M = fmaxf(M, p[i * REC]);
+    float L = 0.f, acc = 0.f;
+    for (int i = 0; i < n_parts; ++i) {
+        const float w = exp2f(p[i * REC] - M);
+        L += p[i * REC + 1] * w;
+        acc += p[i * REC + ATTF_STRIDE_PAD + d] * w;
+    }
+    o[xfrag_index(row, head * HD + d, ncb)] = (bf16_t)(acc / L);
 }
 
 // ---- host side -------------------------------------------------------------------------------------
@@ -592,9 +623,17 @@ int run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_o
 int vf_launch_attention_rows(const vf_model *m, const Batch &b, int layer, hipStream_t st) {
     const vf_config &c = m->cfg;
     const int group = c.n_q_heads / c.n_kv_heads;
-    int max_items = 0;
-    for (int i = 0; i < b.n_seqs; ++i) max_items = max(max_items, b.s[i].nrows * group);
-    const dim3 grid((max_items + 16 * ROWS_QB - 1) / (16 * ROWS_QB), c.n_kv_heads, b.n_seqs);
+    int max_items = 0, max_keys = 0;
+    for (int i = 0; i < b.n_seqs; ++i) {
+        max_items = max(max_items, b.s[i].nrows * group);
+        max_keys = max(max_keys, b.s[i].len_ub + b.s[i].nrows);
+    }
+    // about ROWS_PART_TILES key tiles per workgroup; the record buffer has room for 16 parts per (row, head)
+    const int max_tiles = (max_keys + ATT_TILE - 1) / ATT_TILE;
+    int n_parts = min(16, max(1, (max_tiles + ROWS_PART_TILES - 1) / ROWS_PART_TILES));
+    const size_t rec_floats = (size_t)b.total_rows * c.n_q_heads * (c.head_dim + ATTF_STRIDE_PAD);
+    while (n_parts > 1 && rec_floats * n_parts > m->attn_part_floats) --n_parts;
+    const dim3 grid((max_items + 16 * ROWS_QB - 1) / (16 * ROWS_QB), c.n_kv_heads, b.n_seqs * n_parts);
     const int ncb = (b.total_rows + 15) >> 4;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)c.head_dim);
     const int lds = ROWS_WAVES * (c.head_dim / 16) * 64 * 16 + ROWS_WAVES * 2 * 16 * 4;
@@ -606,11 +645,20 @@ int vf_launch_attention_rows(const vf_model *m, const Batch &b, int layer, hipSt
     }
     if (c.head_dim == 128)
         hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(ROWS_WAVES * 64), lds, st, b, layer, (const bf16_t *)m->q,
-                           (bf16_t *)m->o, c.n_q_heads, c.n_kv_heads, ncb, scale_log2e);
+                           (bf16_t *)m->o, c.n_q_heads, c.n_kv_heads, ncb, scale_log2e, n_parts, m->attn_part);
     else
         hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(ROWS_WAVES * 64), lds, st, b, layer, (const bf16_t *)m->q,
-                           (bf16_t *)m->o, c.n_q_heads, c.n_kv_heads, ncb, scale_log2e);
+                           (bf16_t *)m->o, c.n_q_heads, c.n_kv_heads, ncb, scale_log2e, n_parts, m->attn_part);
     VF_LAUNCH_CHECK("attn_rows");
+    if (n_parts > 1) {
+        if (c.head_dim == 128)
+            hipLaunchKernelGGL(attn_rows_combine_kernel<128>, dim3(b.total_rows * c.n_q_heads), dim3(128), 0, st,
+                               m->attn_part, (bf16_t *)m->o, c.n_q_heads, n_parts, ncb);
+        else
+            hipLaunchKernelGGL(attn_rows_combine_kernel<64>, dim3(b.total_rows * c.n_q_heads), dim3(64), 0, st,
+                               m->attn_part, (bf16_t *)m->o, c.n_q_heads, n_parts, ncb);
+        VF_LAUNCH_CHECK("attn_rows_combine");
+    }
     return VF_OK;
 }
 
