@@ -34,7 +34,7 @@ constexpr int FW = 8;            // wavefronts per workgroup
 constexpr int FT = FW * 64;      // threads per workgroup
 constexpr int FROWS = 48;        // most rows of a call
 #ifndef BAR_COUNTERS
-#define BAR_COUNTERS 32           // counters a barrier's arrivals are spread over
+#define BAR_COUNTERS 64           // counters a barrier's arrivals are spread over
 #endif
 constexpr int ATT_COUNTERS = 4096;  // arrival counters of the attention blocks inside the barrier block (uints)
 constexpr int LDS_BYTES = 152 * 1024;  // dynamic LDS of the one workgroup a CU holds (160 KB less the static part)
