@@ -49,6 +49,9 @@ constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (s
 #ifndef FUSED_AHEAD
 #define FUSED_AHEAD 3          // gate/up, down and head phases: this many steps of the item after next are held in registers too (0: off)
 #endif
+#ifndef FUSED_LAST_MERGES
+#define FUSED_LAST_MERGES 1     // attention: the last part to arrive merges the block (0: all parts wait and merge a slice each)
+#endif
 #ifndef FUSED_MAXP
 #define FUSED_MAXP 8              // most key parts per attention block (at most 8: the merge holds them all)
 #endif
@@ -686,6 +689,18 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
             }
             stores_done();
             __syncthreads();
+#if FUSED_LAST_MERGES
+            // the part that counts itself in last merges the whole block (wavefront w takes d-block w);
+            // the others are done: nobody waits, nothing is polled
+            if (tid == 0) {
+                unsigned *cnt = a.bar + ATT_COUNTERS + it.blk;
+                const unsigned old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                sh.s_last = old + 1u == (unsigned)P * (unsigned)(layer + 1);
+            }
+            __syncthreads();
+            TRACE(22);
+            const int db = sh.s_last ? wave : DB;
+#else
             if (tid == 0) {
                 unsigned *cnt = a.bar + ATT_COUNTERS + it.blk;
                 __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -702,6 +717,7 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
             lds_sync();
             TRACE(22);
             const int db = part + wave * P;
+#endif
             if (db < DB) {
                 // all records in flight at once (slots past P repeat the last part and weigh nothing);
                 // the records of a layer have a buffer of their own, so ordinary loads see them
