@@ -52,6 +52,9 @@ constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (s
 #ifndef FUSED_LAST_MERGES
 #define FUSED_LAST_MERGES 1     // attention: the last part to arrive merges the block (0: all parts wait and merge a slice each)
 #endif
+#ifndef FUSED_FREE_SPLIT
+#define FUSED_FREE_SPLIT 1     // a phase of at most one item per workgroup may use a K split that does not divide the grid
+#endif
 #ifndef FUSED_MAXP
 #define FUSED_MAXP 8              // most key parts per attention block (at most 8: the merge holds them all)
 #endif
@@ -865,7 +868,9 @@ int pick_split(int G, int lds_total, int units, int KB, int rows, int nb, bool a
     const int lim = slice_limit(lds_total, rows, nb);
     int best = 0;
     for (int ks = 1; ks <= G && ks <= KB; ++ks) {
-        if (G % ks) continue;
+        // workgroup w takes items w, w + G, ...: they share a K slice if ks divides G, or if there is
+        // at most one item per workgroup
+        if (G % ks && !(FUSED_FREE_SPLIT && allow_fill && units * ks <= G)) continue;
         const int kbps = (KB + ks - 1) / ks;
         if ((KB + kbps - 1) / kbps != ks) continue;  // every split must own k-blocks
         if (kbps > lim) continue;
