@@ -178,10 +178,20 @@ struct Trace {
 #define TRACE_PASS
 #endif
 
+// Where a row of the call goes in the KV cache and which rotary angle it takes; the same in every
+// layer of a launch (sequence lengths do not change while it runs), so it is worked out once.
+struct RowMeta {
+    bf16_t *kv;      // the sequence's KV pool
+    int n_pages;     // pages in that pool
+    int page, tin;   // page and row inside the page of the row's cache slot
+    int pos;         // position whose rotary angle the row takes
+    int live;        // 0: the slot lies outside the sequence's capacity, nothing is written
+};
 struct FusedShared {
     float rs_s[64];
     float rs_tmp[FW][64];
     int s_last;
+    RowMeta rows[FROWS];
 };
 
 // ---- embedding: row r by workgroup r ---------------------------------------------------------------
@@ -210,6 +220,82 @@ __device__ __forceinline__ void embed_phase(const FusedArgs &a, const Batch &b) 
     }
 }
 
+// Staged activations: k-block kx, row r holds 32 bf16 = four 16-byte quarters.  An MFMA operand read
+// takes quarter q of sixteen consecutive rows, 64 bytes apart: rows r and r + 4 would meet in the
+// same LDS banks.  Quarter q of row r therefore sits at position (q + r / 4) mod 4 of its row.
+#ifndef FUSED_BB_AHEAD
+#define FUSED_BB_AHEAD 1          // GEMM phases: activation fragments are read from LDS this many steps ahead of their MFMAs (0: right before)
+#endif
+#ifndef FUSED_SCALAR_WAVE
+#define FUSED_SCALAR_WAVE 0
+#endif
+#ifndef FUSED_EPI_PREFETCH
+#define FUSED_EPI_PREFETCH 1      // what an epilogue reads from memory is requested before the item's MFMA loop
+#endif
+#ifndef FUSED_XS_SWIZZLE
+#define FUSED_XS_SWIZZLE 0
+#endif
+__device__ __forceinline__ int xs_quarter(int q, int row) { return FUSED_XS_SWIZZLE ? ((q + (row >> 2)) & 3) : q; }
+
+// Epilogues of the persistent kernel.  What they read from memory is requested before the item's
+// MFMA loop (epi_prefetch) and only used after it, so that no round trip is left between the last
+// MFMA and the stores.
+//   QKV: bias, rotary embedding, q to its buffer, K and V rows into the cache (row table in LDS)
+//   residual: h = h_in + y, and the tile's sums of squares for the next RMSNorm
+struct EpiPre { floatx4 v; };
+template <int EPI>
+__device__ __forceinline__ EpiPre epi_prefetch(const FastGemm &g, const FusedShared &sh, int row, int nb, int lane) {
+    EpiPre p;
+    p.v = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int n0 = nb * 16 + (lane >> 4) * 4;
+    if (EPI == EPI_RESID) {
+        p.v = ssa_load_f4(g.h_in + (size_t)row * g.N + n0);
+    } else if (EPI == EPI_QKV) {
+        const int half = g.hd >> 1, i0 = (n0 % g.hd) >> 1;
+        const size_t at = (size_t)sh.rows[row].pos * half + i0;   // past the K heads: loaded, not used
+        const float2 c = *reinterpret_cast<const float2 *>(g.cosv + at), sn = *reinterpret_cast<const float2 *>(g.sinv + at);
+        p.v = floatx4{c.x, sn.x, c.y, sn.y};
+    }
+    return p;
+}
+__device__ __forceinline__ void epi_resid_pre(const FastGemm &g, int row, bool live, int nb, int lane, floatx4 v, const EpiPre &pre) {
+    const int n0 = nb * 16 + (lane >> 4) * 4;
+    floatx4 hv = {0.f, 0.f, 0.f, 0.f};
+    if (live) {
+        hv = pre.v + v;
+        st_f32x4<true>(g.h + (size_t)row * g.N + n0, hv);
+    }
+    float ssq = hv[0] * hv[0] + hv[1] * hv[1] + hv[2] * hv[2] + hv[3] * hv[3];
+    ssq += __shfl_xor(ssq, 16, 64);
+    ssq += __shfl_xor(ssq, 32, 64);
+    if (live && (lane >> 4) == 0) st_f32<true>(g.ss_out + nb * 64 + row, ssq);
+}
+__device__ __forceinline__ void epi_qkv_pre(const FastGemm &g, const FusedShared &sh, int row, int nb, int lane, floatx4 v, const EpiPre &pre) {
+    const int n0 = nb * 16 + (lane >> 4) * 4;
+    const int hd = g.hd, half = hd >> 1;
+    if (g.bias) v += load_global_f4(g.bias + n0);
+    const RowMeta rm = sh.rows[row];
+    if (!rm.live) return;
+    const int head = n0 / hd, p0 = n0 % hd;
+    if (head < g.hq + g.hkv) {
+        const int i0 = p0 >> 1;  // packed columns 2i, 2i+1 are elements i and i + hd/2
+        const float c0 = pre.v[0], s0 = pre.v[1], c1 = pre.v[2], s1 = pre.v[3];
+        const float a0 = v[0] * c0 - v[1] * s0, b0 = v[1] * c0 + v[0] * s0;
+        const float a1 = v[2] * c1 - v[3] * s1, b1 = v[3] * c1 + v[2] * s1;
+        bf16_t *dst = head < g.hq ? g.q + ((size_t)row * g.hq + head) * hd
+                                  : rm.kv + kv_k_index(g.layer, rm.n_pages, rm.page, g.hkv, head - g.hq, rm.tin, 0, hd);
+        st_u32<true>(dst + i0, pack2_bf16(a0, a1));          // i0 is even: 4-byte aligned
+        st_u32<true>(dst + i0 + half, pack2_bf16(b0, b1));
+    } else {
+        const int vh = head - g.hq - g.hkv;
+        for (int i = 0; i < 4; ++i) {
+            const bf16_t x = (bf16_t)v[i];
+            st_u16<true>(rm.kv + kv_v_index(g.layer, rm.n_pages, rm.page, g.hkv, vh, rm.tin, p0 + i, hd),
+                         __builtin_bit_cast(unsigned short, x));
+        }
+    }
+}
+
 // ---- GEMM phase -------------------------------------------------------------------------------------
 // Work items = (unit of UB weight blocks) x (K split); workgroup w takes items w, w + G, ...  G is
 // a multiple of ks, so all items of a workgroup share one K slice and its activations are staged
@@ -229,7 +315,9 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
     constexpr int XP = 16;                   // staging loads in flight per thread
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));  // per-thread index math is redone per phase instead of living across all of them
-    const int lane = tid & 63, wave = tid >> 6;
+    // the wavefront's number as a scalar: what depends on it alone (its run of k-blocks, which
+    // steps are live, fragment offsets) is then computed by the scalar unit
+    const int lane = tid & 63, wave = FUSED_SCALAR_WAVE ? __builtin_amdgcn_readfirstlane(tid >> 6) : tid >> 6;
     const int G = gridDim.x, wg = blockIdx.x;
     const int m = g.m, KB = g.KB, NBt = g.N >> 4;
     const int n_units = (NBt + UB - 1) / UB;
@@ -345,12 +433,14 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
             c = c0;
 #pragma unroll
             for (int i = 0; i < XP; ++i) {
-                if (base + tid + i * FT < pieces) {
-                    const float r = sh.rs_s[row];
-                    const floatx4 gv = *reinterpret_cast<const floatx4 *>(gain_s + c * 4);
-                    u32x2 *dst = reinterpret_cast<u32x2 *>(xs) + (((c >> 3) * m + row) * 8 + (c & 7));
-                    *dst = pack4_bf16(v[i][0] * r * gv[0], v[i][1] * r * gv[1], v[i][2] * r * gv[2], v[i][3] * r * gv[3]);
-                }
+                // no branch: a piece past the last row was loaded from the last row (clamped) and is
+                // written there again, the same value its owner writes; straight-line code lets the
+                // LDS reads of all pieces go out ahead of the arithmetic
+                const int rr = min(row, m - 1);
+                const float r = sh.rs_s[rr];
+                const floatx4 gv = *reinterpret_cast<const floatx4 *>(gain_s + c * 4);
+                u32x2 *dst = reinterpret_cast<u32x2 *>(xs) + (((c >> 3) * m + rr) * 8 + (xs_quarter((c & 7) >> 1, rr) << 1) + (c & 1));
+                *dst = pack4_bf16(v[i][0] * r * gv[0], v[i][1] * r * gv[1], v[i][2] * r * gv[2], v[i][3] * r * gv[3]);
                 row += qstep;
                 c += rstep;
                 if (c >= chunks) { c -= chunks; ++row; }
@@ -375,7 +465,8 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
             c = c0;
 #pragma unroll
             for (int i = 0; i < XP; ++i) {
-                if (base + tid + i * FT < pieces) xs[((c >> 2) * m + row) * 4 + (c & 3)] = v[i];
+                const int rr = min(row, m - 1);  // a piece past the last row: the last row's, written again
+                xs[((c >> 2) * m + rr) * 4 + xs_quarter(c & 3, rr)] = v[i];
                 row += qstep;
                 c += rstep;
                 if (c >= chunks) { c -= chunks; ++row; }
@@ -385,9 +476,12 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
     lds_sync();
     TRACE(3);
 
-    int rowc[NB];
+    int xoff[NB];  // this lane's 16 bytes of row block c inside a k-block of the staged activations
 #pragma unroll
-    for (int c = 0; c < NB; ++c) rowc[c] = min(c * 16 + (lane & 15), m - 1);
+    for (int c = 0; c < NB; ++c) {
+        const int row = min(c * 16 + (lane & 15), m - 1);
+        xoff[c] = row * 4 + xs_quarter(lane >> 4, row);
+    }
 
     for (int it = 0; it < n_my; ++it) {
         const bool has_next = it + 1 < n_my;
@@ -401,6 +495,14 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
         for (int u = 0; u < UB; ++u)
 #pragma unroll
             for (int c = 0; c < NB; ++c) acc[u][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+        // this thread's epilogue tile (whole wavefronts: NTH is a multiple of 64) and what its epilogue reads
+        constexpr int NTH_ = EPI == EPI_SWIGLU ? NB * 64 : UB * NB * 64;
+        EpiPre pre;
+        pre.v = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (FUSED_EPI_PREFETCH && (EPI == EPI_RESID || EPI == EPI_QKV) && tid < NTH_) {
+            const int eu = tid / (NB * 64), ec = (tid >> 6) % NB;
+            pre = epi_prefetch<EPI>(g, sh, min(ec * 16 + (lane & 15), m - 1), min(nb0 + eu, NBt - 1), lane);
+        }
         // One round = PD steps of straight-line code.  REFILL: after its use every slot is loaded
         // again, with the same item's next round or, in the last round, the next item's first; the
         // final round of the final item has nothing left to load and runs without.
@@ -411,6 +513,17 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 #pragma unroll
             for (int u = 0; u < UB; ++u) rp[u] = last_round ? wpn[u] : wp[u];
             const int rbase = last_round ? 0 : (r + 1) * PD;
+            // activation fragments leave LDS FUSED_BB_AHEAD steps before the MFMAs that use them, so
+            // that no MFMA waits for a read issued right in front of it
+            constexpr int BA = FUSED_BB_AHEAD < PD ? FUSED_BB_AHEAD : PD - 1;
+            bf16x8 bb[BA + 1][NB];
+            auto read_bb = [&](int d) {
+                const int kx = min(wk0 + min(r * PD + d, cnt - 1), kb1 - 1) - kb0;
+#pragma unroll
+                for (int c = 0; c < NB; ++c) bb[d % (BA + 1)][c] = __builtin_bit_cast(bf16x8, xs[kx * m * 4 + xoff[c]]);
+            };
+#pragma unroll
+            for (int d = 0; d < BA; ++d) read_bb(d);
 #pragma unroll
             for (int d = 0; d < PD; ++d) {
                 const int kbl = r * PD + d;
@@ -432,13 +545,13 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
                         for (int u = 0; u < UB; ++u) w[d][u] = frag(rp[u], min(rbase + d, cnt - 1));
                     }
                 }
-                const int kx = min(wk0 + min(kbl, cnt - 1), kb1 - 1) - kb0;
+                if (d + BA < PD) read_bb(d + BA);
 #pragma unroll
                 for (int c = 0; c < NB; ++c) {
-                    const bf16x8 bb = __builtin_bit_cast(bf16x8, xs[(kx * m + rowc[c]) * 4 + (lane >> 4)]);
+                    const bf16x8 b1 = bb[d % (BA + 1)][c];
 #pragma unroll
                     for (int u = 0; u < UB; ++u)
-                        acc[u][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], bb, acc[u][c], 0, 0, 0);
+                        acc[u][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b1, acc[u][c], 0, 0, 0);
                 }
             }
         };
@@ -530,9 +643,11 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
             const int row = c * 16 + (lane & 15);
             const bool live = row < m && nb < NBt;
             if (EPI == EPI_RESID) {
-                epi_resid<COH>(g, row, live, nb, lane, v0);
+                if (FUSED_EPI_PREFETCH) epi_resid_pre(g, row, live, nb, lane, v0, pre);
+                else epi_resid<COH>(g, row, live, nb, lane, v0);
             } else if (live) {
-                if (EPI == EPI_QKV) epi_qkv<COH>(g, b, row, nb, lane, v0);
+                if (EPI == EPI_QKV && FUSED_EPI_PREFETCH) epi_qkv_pre(g, sh, row, nb, lane, v0, pre);
+                else if (EPI == EPI_QKV) epi_qkv<COH>(g, b, row, nb, lane, v0);
                 else if (EPI == EPI_SWIGLU) epi_swiglu<COH>(g, row, nb, lane, v0, v1);
                 else __builtin_nontemporal_store(v0, reinterpret_cast<floatx4 *>(g.logits + (size_t)row * g.N + nb * 16 + (lane >> 4) * 4));
             }
@@ -776,9 +891,22 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
     // length of the sequence of this workgroup's first attention item (lengths are constant during a launch)
     int len0 = 0;
     if (a.att_first[blockIdx.x] >= 0) len0 = b.s[att_item(a, b, a.att_first[blockIdx.x]).seq].state[0];
+    if ((int)threadIdx.x < FROWS) {
+        const int row = min((int)threadIdx.x, a.m - 1);
+        const SeqDesc &s = b.s[find_seq(b, row)];
+        const int len = s.state[0], slot = len + (row - s.row0);
+        RowMeta rm;
+        rm.kv = reinterpret_cast<bf16_t *>(s.kv);
+        rm.n_pages = s.n_pages;
+        rm.live = slot >= 0 && slot < s.capacity;
+        rm.page = rm.live ? kv_page(s, slot) : 0;
+        rm.tin = rm.live ? slot % VF_TILE : 0;
+        rm.pos = rm.live ? (a.tree_depth ? len + a.tree_depth[row] : slot) : 0;
+        sh.rows[threadIdx.x] = rm;
+    }
     TRACE(0);
     embed_phase(a, b);
-    bar.arrive();
+    bar.arrive();   // (a workgroup barrier inside: the row table is visible to every wavefront from here on)
 
     FastGemm base;
     base.m = a.m;
