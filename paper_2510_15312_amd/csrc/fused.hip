@@ -232,6 +232,12 @@ __device__ __forceinline__ void embed_phase(const FusedArgs &a, const Batch &b) 
 #ifndef FUSED_EPI_PREFETCH
 #define FUSED_EPI_PREFETCH 1      // what an epilogue reads from memory is requested before the item's MFMA loop
 #endif
+#ifndef FUSED_SGB
+#define FUSED_SGB 1               // GEMM phases: LDS reads are scheduled this many steps ahead of their MFMAs (0: left to the compiler)
+#endif
+#ifndef FUSED_SGB_STAGE
+#define FUSED_SGB_STAGE 2           // staging of a normalising phase: LDS reads this many pieces ahead of the LDS writes (0: left to the compiler)
+#endif
 #ifndef FUSED_XS_SWIZZLE
 #define FUSED_XS_SWIZZLE 0
 #endif
@@ -296,6 +302,38 @@ __device__ __forceinline__ void epi_qkv_pre(const FastGemm &g, const FusedShared
     }
 }
 
+// Second half of the staging of a normalising phase: x = bf16(h * rstd * gain) for the XP pieces
+// (four columns of one row each) this thread loaded, written to the staged activations.  The three
+// LDS arrays are distinct (restrict), which lets the reads of later pieces pass the writes of
+// earlier ones.  No branch: a piece past the last row was loaded from the last row (clamped) and is
+// written there again, the same value its owner writes.
+template <int XP>
+__device__ __forceinline__ void scale_and_stage(const floatx4 (&v)[XP], const float *__restrict__ rs, const float *__restrict__ gain,
+                                                u32x2 *__restrict__ out, int row, int c, int qstep, int rstep, int chunks, int m) {
+#pragma unroll
+    for (int i = 0; i < XP; ++i) {
+        const int rr = min(row, m - 1);
+        const float r = rs[rr];
+        const floatx4 gv = *reinterpret_cast<const floatx4 *>(gain + c * 4);
+        u32x2 *dst = out + (((c >> 3) * m + rr) * 8 + (xs_quarter((c & 7) >> 1, rr) << 1) + (c & 1));
+        *dst = pack4_bf16(v[i][0] * r * gv[0], v[i][1] * r * gv[1], v[i][2] * r * gv[2], v[i][3] * r * gv[3]);
+        row += qstep;
+        c += rstep;
+        if (c >= chunks) { c -= chunks; ++row; }
+    }
+    // order for the instruction scheduler: the two LDS reads of a piece go out FUSED_SGB_STAGE pieces
+    // ahead of the piece's LDS write
+    if (FUSED_SGB_STAGE > 0) {
+        constexpr int SA = FUSED_SGB_STAGE < XP ? FUSED_SGB_STAGE : XP;
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * SA, 0);
+#pragma unroll
+        for (int i = 0; i < XP; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            if (i + SA < XP) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+    }
+}
+
 // ---- GEMM phase -------------------------------------------------------------------------------------
 // Work items = (unit of UB weight blocks) x (K split); workgroup w takes items w, w + G, ...  G is
 // a multiple of ks, so all items of a workgroup share one K slice and its activations are staged
@@ -312,7 +350,10 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
     constexpr bool COH = EPI != EPI_LOGITS;  // logits are read by the next kernel only
     constexpr int RW = FW / 2;               // wavefronts whose partial sums sit in LDS at a time
     constexpr int RED_BYTES = RW * 2 * NB * 1024;
-    constexpr int XP = 16;                   // staging loads in flight per thread
+#ifndef FUSED_XP
+#define FUSED_XP 16
+#endif
+    constexpr int XP = FUSED_XP;             // staging loads in flight per thread
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));  // per-thread index math is redone per phase instead of living across all of them
     // the wavefront's number as a scalar: what depends on it alone (its run of k-blocks, which
@@ -429,22 +470,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
                 lds_sync();
                 TRACE(7);
             }
-            row = row0;
-            c = c0;
-#pragma unroll
-            for (int i = 0; i < XP; ++i) {
-                // no branch: a piece past the last row was loaded from the last row (clamped) and is
-                // written there again, the same value its owner writes; straight-line code lets the
-                // LDS reads of all pieces go out ahead of the arithmetic
-                const int rr = min(row, m - 1);
-                const float r = sh.rs_s[rr];
-                const floatx4 gv = *reinterpret_cast<const floatx4 *>(gain_s + c * 4);
-                u32x2 *dst = reinterpret_cast<u32x2 *>(xs) + (((c >> 3) * m + rr) * 8 + (xs_quarter((c & 7) >> 1, rr) << 1) + (c & 1));
-                *dst = pack4_bf16(v[i][0] * r * gv[0], v[i][1] * r * gv[1], v[i][2] * r * gv[2], v[i][3] * r * gv[3]);
-                row += qstep;
-                c += rstep;
-                if (c >= chunks) { c -= chunks; ++row; }
-            }
+            scale_and_stage<XP>(v, sh.rs_s, gain_s, reinterpret_cast<u32x2 *>(xs), row0, c0, qstep, rstep, chunks, m);
         }
     } else {
         const int chunks = nk * 4, pieces = m * chunks;
@@ -552,6 +578,18 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 #pragma unroll
                     for (int u = 0; u < UB; ++u)
                         acc[u][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b1, acc[u][c], 0, 0, 0);
+                }
+            }
+            // Order of the round's LDS reads and MFMAs for the instruction scheduler: the reads of
+            // the first steps, then per step its MFMAs followed by the reads of a later step, so
+            // that an MFMA never waits for a read issued right in front of it.
+            if (FUSED_SGB > 0) {
+                constexpr int SA = FUSED_SGB < PD ? FUSED_SGB : PD;
+                __builtin_amdgcn_sched_group_barrier(0x100, SA * NB, 0);
+#pragma unroll
+                for (int d = 0; d < PD; ++d) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, UB * NB, 0);
+                    if (d + SA < PD) __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);
                 }
             }
         };
