@@ -220,14 +220,8 @@ __device__ __forceinline__ void embed_phase(const FusedArgs &a, const Batch &b) 
     }
 }
 
-// Staged activations: k-block kx, row r holds 32 bf16 = four 16-byte quarters.  An MFMA operand read
-// takes quarter q of sixteen consecutive rows, 64 bytes apart: rows r and r + 4 would meet in the
-// same LDS banks.  Quarter q of row r therefore sits at position (q + r / 4) mod 4 of its row.
 #ifndef FUSED_BB_AHEAD
 #define FUSED_BB_AHEAD 1          // GEMM phases: activation fragments are read from LDS this many steps ahead of their MFMAs (0: right before)
-#endif
-#ifndef FUSED_SCALAR_WAVE
-#define FUSED_SCALAR_WAVE 0
 #endif
 #ifndef FUSED_EPI_PREFETCH
 #define FUSED_EPI_PREFETCH 1      // what an epilogue reads from memory is requested before the item's MFMA loop
@@ -238,10 +232,6 @@ __device__ __forceinline__ void embed_phase(const FusedArgs &a, const Batch &b) 
 #ifndef FUSED_SGB_STAGE
 #define FUSED_SGB_STAGE 2           // staging of a normalising phase: LDS reads this many pieces ahead of the LDS writes (0: left to the compiler)
 #endif
-#ifndef FUSED_XS_SWIZZLE
-#define FUSED_XS_SWIZZLE 0
-#endif
-__device__ __forceinline__ int xs_quarter(int q, int row) { return FUSED_XS_SWIZZLE ? ((q + (row >> 2)) & 3) : q; }
 
 // Epilogues of the persistent kernel.  What they read from memory is requested before the item's
 // MFMA loop (epi_prefetch) and only used after it, so that no round trip is left between the last
@@ -315,7 +305,7 @@ __device__ __forceinline__ void scale_and_stage(const floatx4 (&v)[XP], const fl
         const int rr = min(row, m - 1);
         const float r = rs[rr];
         const floatx4 gv = *reinterpret_cast<const floatx4 *>(gain + c * 4);
-        u32x2 *dst = out + (((c >> 3) * m + rr) * 8 + (xs_quarter((c & 7) >> 1, rr) << 1) + (c & 1));
+        u32x2 *dst = out + (((c >> 3) * m + rr) * 8 + (c & 7));
         *dst = pack4_bf16(v[i][0] * r * gv[0], v[i][1] * r * gv[1], v[i][2] * r * gv[2], v[i][3] * r * gv[3]);
         row += qstep;
         c += rstep;
@@ -356,9 +346,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
     constexpr int XP = FUSED_XP;             // staging loads in flight per thread
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));  // per-thread index math is redone per phase instead of living across all of them
-    // the wavefront's number as a scalar: what depends on it alone (its run of k-blocks, which
-    // steps are live, fragment offsets) is then computed by the scalar unit
-    const int lane = tid & 63, wave = FUSED_SCALAR_WAVE ? __builtin_amdgcn_readfirstlane(tid >> 6) : tid >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
     const int G = gridDim.x, wg = blockIdx.x;
     const int m = g.m, KB = g.KB, NBt = g.N >> 4;
     const int n_units = (NBt + UB - 1) / UB;
@@ -492,7 +480,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 #pragma unroll
             for (int i = 0; i < XP; ++i) {
                 const int rr = min(row, m - 1);  // a piece past the last row: the last row's, written again
-                xs[((c >> 2) * m + rr) * 4 + xs_quarter(c & 3, rr)] = v[i];
+                xs[((c >> 2) * m + rr) * 4 + (c & 3)] = v[i];
                 row += qstep;
                 c += rstep;
                 if (c >= chunks) { c -= chunks; ++row; }
@@ -506,7 +494,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 #pragma unroll
     for (int c = 0; c < NB; ++c) {
         const int row = min(c * 16 + (lane & 15), m - 1);
-        xoff[c] = row * 4 + xs_quarter(lane >> 4, row);
+        xoff[c] = row * 4 + (lane >> 4);
     }
 
     for (int it = 0; it < n_my; ++it) {
