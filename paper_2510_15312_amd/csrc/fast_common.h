@@ -374,6 +374,12 @@ template <int HD> struct AttTile {
     bf16x8 kf[2][HD / 32], vf[HD / 16];
     // coh: the tile holds keys written during this launch by other workgroups
     __device__ __forceinline__ void load(const SeqDesc &s, int layer, int hkv, int kvh, int t, bool coh, int lane) {
+        // one branch, two straight-line copies: every load of a copy is issued before any is waited for
+        if (coh) load_as<true>(s, layer, hkv, kvh, t, lane);
+        else load_as<false>(s, layer, hkv, kvh, t, lane);
+    }
+    template <bool coh>
+    __device__ __forceinline__ void load_as(const SeqDesc &s, int layer, int hkv, int kvh, int t, int lane) {
         const int g4 = lane >> 4, l15 = lane & 15;
         const int krow = 8 * (l15 >> 2) + (l15 & 3);
         const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);

@@ -229,8 +229,8 @@ __device__ __forceinline__ void embed_phase(const FusedArgs &a, const Batch &b) 
 #ifndef FUSED_SGB
 #define FUSED_SGB 1               // GEMM phases: LDS reads are scheduled this many steps ahead of their MFMAs (0: left to the compiler)
 #endif
-#ifndef FUSED_SGB_STAGE
-#define FUSED_SGB_STAGE 2           // staging of a normalising phase: LDS reads this many pieces ahead of the LDS writes (0: left to the compiler)
+#ifndef FUSED_STAGE_GROUP
+#define FUSED_STAGE_GROUP 4       // staging of a normalising phase: pieces whose LDS reads (1/rms, gain) are issued together
 #endif
 
 // Epilogues of the persistent kernel.  What they read from memory is requested before the item's
@@ -238,12 +238,14 @@ __device__ __forceinline__ void embed_phase(const FusedArgs &a, const Batch &b) 
 // MFMA and the stores.
 //   QKV: bias, rotary embedding, q to its buffer, K and V rows into the cache (row table in LDS)
 //   residual: h = h_in + y, and the tile's sums of squares for the next RMSNorm
-struct EpiPre { floatx4 v; };
+struct EpiPre { floatx4 v, bias; };
 template <int EPI>
 __device__ __forceinline__ EpiPre epi_prefetch(const FastGemm &g, const FusedShared &sh, int row, int nb, int lane) {
     EpiPre p;
     p.v = floatx4{0.f, 0.f, 0.f, 0.f};
+    p.bias = floatx4{0.f, 0.f, 0.f, 0.f};
     const int n0 = nb * 16 + (lane >> 4) * 4;
+    if (EPI == EPI_QKV && g.bias) p.bias = load_global_f4(g.bias + n0);
     if (EPI == EPI_RESID) {
         p.v = ssa_load_f4(g.h_in + (size_t)row * g.N + n0);
     } else if (EPI == EPI_QKV) {
@@ -269,7 +271,7 @@ __device__ __forceinline__ void epi_resid_pre(const FastGemm &g, int row, bool l
 __device__ __forceinline__ void epi_qkv_pre(const FastGemm &g, const FusedShared &sh, int row, int nb, int lane, floatx4 v, const EpiPre &pre) {
     const int n0 = nb * 16 + (lane >> 4) * 4;
     const int hd = g.hd, half = hd >> 1;
-    if (g.bias) v += load_global_f4(g.bias + n0);
+    v += pre.bias;
     const RowMeta rm = sh.rows[row];
     if (!rm.live) return;
     const int head = n0 / hd, p0 = n0 % hd;
@@ -300,26 +302,29 @@ __device__ __forceinline__ void epi_qkv_pre(const FastGemm &g, const FusedShared
 template <int XP>
 __device__ __forceinline__ void scale_and_stage(const floatx4 (&v)[XP], const float *__restrict__ rs, const float *__restrict__ gain,
                                                 u32x2 *__restrict__ out, int row, int c, int qstep, int rstep, int chunks, int m) {
+    constexpr int GRP = FUSED_STAGE_GROUP;  // pieces whose LDS reads are issued together
 #pragma unroll
-    for (int i = 0; i < XP; ++i) {
-        const int rr = min(row, m - 1);
-        const float r = rs[rr];
-        const floatx4 gv = *reinterpret_cast<const floatx4 *>(gain + c * 4);
-        u32x2 *dst = out + (((c >> 3) * m + rr) * 8 + (c & 7));
-        *dst = pack4_bf16(v[i][0] * r * gv[0], v[i][1] * r * gv[1], v[i][2] * r * gv[2], v[i][3] * r * gv[3]);
-        row += qstep;
-        c += rstep;
-        if (c >= chunks) { c -= chunks; ++row; }
-    }
-    // order for the instruction scheduler: the two LDS reads of a piece go out FUSED_SGB_STAGE pieces
-    // ahead of the piece's LDS write
-    if (FUSED_SGB_STAGE > 0) {
-        constexpr int SA = FUSED_SGB_STAGE < XP ? FUSED_SGB_STAGE : XP;
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * SA, 0);
+    for (int i0 = 0; i0 < XP; i0 += GRP) {
+        float r[GRP];
+        floatx4 gv[GRP];
+        int at[GRP];
 #pragma unroll
-        for (int i = 0; i < XP; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-            if (i + SA < XP) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        for (int j = 0; j < GRP; ++j) {
+            const int rr = min(row, m - 1);
+            r[j] = rs[rr];
+            gv[j] = *reinterpret_cast<const floatx4 *>(gain + c * 4);
+            at[j] = ((c >> 3) * m + rr) * 8 + (c & 7);
+            row += qstep;
+            c += rstep;
+            if (c >= chunks) { c -= chunks; ++row; }
+        }
+        asm volatile("" ::: "memory");  // the group's reads are issued before its first product
+#pragma unroll
+        for (int j = 0; j < GRP; ++j) {
+            if (i0 + j < XP) {
+                const floatx4 x = v[i0 + j < XP ? i0 + j : 0];
+                out[at[j]] = pack4_bf16(x[0] * r[j] * gv[j][0], x[1] * r[j] * gv[j][1], x[2] * r[j] * gv[j][2], x[3] * r[j] * gv[j][3]);
+            }
         }
     }
 }
@@ -450,9 +455,12 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
                 lds_sync();
                 TRACE(6);
                 if (tid < 64) {
-                    float tot = 0.f;
+                    float part[FW], tot = 0.f;
 #pragma unroll
-                    for (int j = 0; j < FW; ++j) tot += sh.rs_tmp[j][tid];
+                    for (int j = 0; j < FW; ++j) part[j] = sh.rs_tmp[j][tid];
+                    asm volatile("" ::: "memory");  // the eight reads are issued together
+#pragma unroll
+                    for (int j = 0; j < FW; ++j) tot += part[j];
                     sh.rs_s[tid] = 1.0f / sqrtf(tot * g.inv_d + g.eps);
                 }
                 lds_sync();
@@ -513,6 +521,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
         constexpr int NTH_ = EPI == EPI_SWIGLU ? NB * 64 : UB * NB * 64;
         EpiPre pre;
         pre.v = floatx4{0.f, 0.f, 0.f, 0.f};
+        pre.bias = floatx4{0.f, 0.f, 0.f, 0.f};
         if (FUSED_EPI_PREFETCH && (EPI == EPI_RESID || EPI == EPI_QKV) && tid < NTH_) {
             const int eu = tid / (NB * 64), ec = (tid >> 6) % NB;
             pre = epi_prefetch<EPI>(g, sh, min(ec * 16 + (lane & 15), m - 1), min(nb0 + eu, NBt - 1), lane);
@@ -587,6 +596,8 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
         else round_body(std::false_type{}, rounds - 1);
         TRACE(4);
         // ---- wavefront partial sums: upper half through LDS into the lower half, then all four ----
+        // (the LDS reads of a stage are issued together, ahead of the first sum: the empty asm
+        // statements keep the compiler from moving each read down to its use)
         if (wave >= RW) {
 #pragma unroll
             for (int u = 0; u < UB; ++u)
@@ -595,13 +606,16 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
         }
         lds_sync();
         if (wave < RW) {
+            floatx4 other[UB][NB];
 #pragma unroll
             for (int u = 0; u < UB; ++u)
 #pragma unroll
-                for (int c = 0; c < NB; ++c) {
-                    const int idx = ((wave * UB + u) * NB + c) * 64 + lane;
-                    red[idx] = acc[u][c] + red[idx];
-                }
+                for (int c = 0; c < NB; ++c) other[u][c] = red[((wave * UB + u) * NB + c) * 64 + lane];
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+#pragma unroll
+                for (int c = 0; c < NB; ++c) red[((wave * UB + u) * NB + c) * 64 + lane] = acc[u][c] + other[u][c];
         }
         lds_sync();
 
@@ -611,17 +625,27 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
         const int t = tid;
         floatx4 v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
         if (t < NTH) {
+            floatx4 p0[RW], p1[RW];
             if (EPI == EPI_SWIGLU) {
                 const int c = t >> 6;
 #pragma unroll
                 for (int ww = 0; ww < RW; ++ww) {
-                    v0 += red[((ww * UB + 0) * NB + c) * 64 + lane];
-                    v1 += red[((ww * UB + (UB - 1)) * NB + c) * 64 + lane];
+                    p0[ww] = red[((ww * UB + 0) * NB + c) * 64 + lane];
+                    p1[ww] = red[((ww * UB + (UB - 1)) * NB + c) * 64 + lane];
                 }
             } else {
                 const int u = t / (NB * 64), c = (t >> 6) % NB;
 #pragma unroll
-                for (int ww = 0; ww < RW; ++ww) v0 += red[((ww * UB + u) * NB + c) * 64 + lane];
+                for (int ww = 0; ww < RW; ++ww) {
+                    p0[ww] = red[((ww * UB + u) * NB + c) * 64 + lane];
+                    p1[ww] = floatx4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int ww = 0; ww < RW; ++ww) {
+                v0 += p0[ww];
+                if (EPI == EPI_SWIGLU) v1 += p1[ww];
             }
         }
         bool do_epi = true;
@@ -729,7 +753,9 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
     constexpr int KD = HD / 32, DB = HD / 16, REC = HD + ATTF_STRIDE_PAD, MAXP = FUSED_MAXP;
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
-    const int lane = tid & 63, wave = tid >> 6, g4 = lane >> 4, l15 = lane & 15;
+    // the wavefront's number as a scalar: which tile it takes, and whether that tile holds keys of
+    // this launch, are then decided by scalar branches
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g4 = lane >> 4, l15 = lane & 15;
     const int G = gridDim.x, hq = a.hq, hkv = a.hkv, group = hq / hkv, P = a.att_parts;
     floatx4 *o_s = reinterpret_cast<floatx4 *>(smem);                      // [wave][db][lane]
     float *ml_s = reinterpret_cast<float *>(smem + FW * DB * 64 * 16);    // [wave][2][16]
@@ -809,13 +835,23 @@ __device__ __forceinline__ void attn_phase(const FusedArgs &a, const Batch &b, i
         floatx4 acc = {0.f, 0.f, 0.f, 0.f};
         float M = -1e30f, L = 0.f;
         if (wave < DB) {
-#pragma unroll
-            for (int w = 0; w < FW; ++w) M = fmaxf(M, ml_s[(w * 2) * 16 + l15]);
+            // all LDS reads of the merge are issued together, ahead of the arithmetic
+            float mw[FW], lw[FW];
+            floatx4 ow[FW];
 #pragma unroll
             for (int w = 0; w < FW; ++w) {
-                const float wt = exp2f(ml_s[(w * 2) * 16 + l15] - M);
-                L += ml_s[(w * 2 + 1) * 16 + l15] * wt;
-                acc += o_s[(w * DB + wave) * 64 + lane] * wt;
+                mw[w] = ml_s[(w * 2) * 16 + l15];
+                lw[w] = ml_s[(w * 2 + 1) * 16 + l15];
+                ow[w] = o_s[(w * DB + wave) * 64 + lane];
+            }
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int w = 0; w < FW; ++w) M = fmaxf(M, mw[w]);
+#pragma unroll
+            for (int w = 0; w < FW; ++w) {
+                const float wt = exp2f(mw[w] - M);
+                L += lw[w] * wt;
+                acc += ow[w] * wt;
             }
         }
         TRACE(21);
