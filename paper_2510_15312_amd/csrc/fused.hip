@@ -420,22 +420,27 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
         // (lane = row, wavefront = every FW-th block of columns); pieces of four columns
         const int chunks = nk * 8, pieces = m * chunks;
         const int qstep = FT / chunks, rstep = FT % chunks;
+        // sums of squares of the column blocks wave, wave + FW, ... of row `lane`: the block index is
+        // the same for the whole wavefront, so the scalar unit forms each address (uniform base +
+        // per-lane offset) and the 0/1 factor of a block past the last.  Lanes past the last row
+        // read the last row's sums; their 1/rms is never used.
         float t[16];
+        const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+        const unsigned ss_lane = (unsigned)min(lane, m - 1);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int j = wave + i * FW;
-            // clamped index, then a multiply by 0 or 1: a select would be turned back into a branch
-            // around the load, and the loads would wait for one another
-            t[i] = ssa_load_f1(g.ss_in + min(j, g.n_ss - 1) * 64 + min(lane, m - 1)) * ((lane < m && j < g.n_ss) ? 1.f : 0.f);
+            const int j = wave_s + i * FW;
+            t[i] = ssa_load_f1(g.ss_in + min(j, g.n_ss - 1) * 64 + ss_lane) * (j < g.n_ss ? 1.f : 0.f);
         }
         floatx4 gn = load_global_f4(g.gain + (size_t)kb0 * 32 + min(tid, chunks - 1) * 4);
+        const float *xh_slice = g.Xh + (size_t)kb0 * 32;
         for (int base = 0; base < pieces; base += FT * XP) {
             floatx4 v[XP];
             int row = (base + tid) / chunks, c = (base + tid) % chunks;
             const int row0 = row, c0 = c;
 #pragma unroll
             for (int i = 0; i < XP; ++i) {
-                v[i] = ssa_load_f4(g.Xh + (size_t)min(row, m - 1) * KB * 32 + (size_t)kb0 * 32 + c * 4);
+                v[i] = ssa_load_f4(xh_slice + (unsigned)(min(row, m - 1) * KB * 32 + c * 4));  // uniform base + 32-bit offset
                 row += qstep;
                 c += rstep;
                 if (c >= chunks) { c -= chunks; ++row; }
@@ -471,13 +476,14 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
     } else {
         const int chunks = nk * 4, pieces = m * chunks;
         const int qstep = FT / chunks, rstep = FT % chunks;
+        const bf16_t *x_slice = g.X + (size_t)kb0 * 32;
         for (int base = 0; base < pieces; base += FT * XP) {
             u32x4 v[XP];
             int row = (base + tid) / chunks, c = (base + tid) % chunks;
             const int row0 = row, c0 = c;
 #pragma unroll
             for (int i = 0; i < XP; ++i) {
-                v[i] = ssa_load_16(g.X + (size_t)min(row, m - 1) * KB * 32 + (size_t)kb0 * 32 + c * 8);
+                v[i] = ssa_load_16(x_slice + (unsigned)(min(row, m - 1) * KB * 32 + c * 8));  // uniform base + 32-bit offset
                 row += qstep;
                 c += rstep;
                 if (c >= chunks) { c -= chunks; ++row; }
