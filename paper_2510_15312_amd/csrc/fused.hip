@@ -229,6 +229,9 @@ __device__ __forceinline__ void embed_phase(const FusedArgs &a, const Batch &b) 
 #ifndef FUSED_SGB
 #define FUSED_SGB 1               // GEMM phases: LDS reads are scheduled this many steps ahead of their MFMAs (0: left to the compiler)
 #endif
+#ifndef FUSED_XP
+#define FUSED_XP 16                // activation staging: loads in flight per thread (a multiple of FUSED_STAGE_GROUP)
+#endif
 #ifndef FUSED_STAGE_GROUP
 #define FUSED_STAGE_GROUP 4       // staging of a normalising phase: pieces whose LDS reads (1/rms, gain) are issued together
 #endif
@@ -345,10 +348,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
     constexpr bool COH = EPI != EPI_LOGITS;  // logits are read by the next kernel only
     constexpr int RW = FW / 2;               // wavefronts whose partial sums sit in LDS at a time
     constexpr int RED_BYTES = RW * 2 * NB * 1024;
-#ifndef FUSED_XP
-#define FUSED_XP 16
-#endif
-    constexpr int XP = FUSED_XP;             // staging loads in flight per thread
+    constexpr int XP = FUSED_XP;
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));  // per-thread index math is redone per phase instead of living across all of them
     const int lane = tid & 63, wave = tid >> 6;
