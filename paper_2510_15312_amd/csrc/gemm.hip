@@ -199,16 +199,22 @@ void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp
         for (int half = 0; half < KSTEP; ++half) {
             if (kb + half >= kb_limit) continue;
             const u32x4 *st = lds[buf] + half * NF * 64;
-            bf16x8 bfr[WC];
+            // every fragment of the k-block leaves LDS before the first MFMA, so that no MFMA waits for
+            // a read issued right in front of it
+            bf16x8 bfr[WC], afr[TNB];
 #pragma unroll
             for (int c = 0; c < WC; ++c) bfr[c] = __builtin_bit_cast(bf16x8, st[(TNB + wave * WC + c) * 64 + lane]);
 #pragma unroll
-            for (int n = 0; n < TNB; ++n) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, st[n * 64 + lane]);
+            for (int n = 0; n < TNB; ++n) afr[n] = __builtin_bit_cast(bf16x8, st[n * 64 + lane]);
+#pragma unroll
+            for (int n = 0; n < TNB; ++n)
 #pragma unroll
                 for (int c = 0; c < WC; ++c)
-                    acc[n][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bfr[c], acc[n][c], 0, 0, 0);
-            }
+                    acc[n][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[n], bfr[c], acc[n][c], 0, 0, 0);
+            // order for the instruction scheduler: the k-block's LDS reads, then its MFMAs (reads two or
+            // three weight fragments ahead of the MFMAs, the rest under them, measured the same)
+            __builtin_amdgcn_sched_group_barrier(0x100, WC + TNB, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, TNB * WC, 0);
         }
     };
     u32x4 r[NSETS][NL];
