@@ -232,6 +232,9 @@ __device__ __forceinline__ void embed_phase(const FusedArgs &a, const Batch &b) 
 #ifndef FUSED_XP
 #define FUSED_XP 16                // activation staging: loads in flight per thread (a multiple of FUSED_STAGE_GROUP)
 #endif
+#ifndef FUSED_SHORT_COPY
+#define FUSED_SHORT_COPY 1          // plain activation staging: a copy of half the depth for calls whose pieces it covers
+#endif
 #ifndef FUSED_STAGE_GROUP
 #define FUSED_STAGE_GROUP 4       // staging of a normalising phase: pieces whose LDS reads (1/rms, gain) are issued together
 #endif
@@ -477,29 +480,36 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
         const int chunks = nk * 4, pieces = m * chunks;
         const int qstep = FT / chunks, rstep = FT % chunks;
         const bf16_t *x_slice = g.X + (size_t)kb0 * 32;
-        for (int base = 0; base < pieces; base += FT * XP) {
-            u32x4 v[XP];
-            int row = (base + tid) / chunks, c = (base + tid) % chunks;
-            const int row0 = row, c0 = c;
+        // passes of `depth` loads in flight per thread; few pieces (a K slice of a call of few rows)
+        // take the short copy, which issues half as many loads that only repeat the last row
+        auto stage_copy = [&](auto depth_tag) {
+            constexpr int D = decltype(depth_tag)::value;
+            for (int base = 0; base < pieces; base += FT * D) {
+                u32x4 v[D];
+                int row = (base + tid) / chunks, c = (base + tid) % chunks;
+                const int row0 = row, c0 = c;
 #pragma unroll
-            for (int i = 0; i < XP; ++i) {
-                v[i] = ssa_load_16(x_slice + (unsigned)(min(row, m - 1) * KB * 32 + c * 8));  // uniform base + 32-bit offset
-                row += qstep;
-                c += rstep;
-                if (c >= chunks) { c -= chunks; ++row; }
-            }
-            if (!FUSED_PREFETCH_EARLY && base == 0) first_fragments();
-            row = row0;
-            c = c0;
+                for (int i = 0; i < D; ++i) {
+                    v[i] = ssa_load_16(x_slice + (unsigned)(min(row, m - 1) * KB * 32 + c * 8));  // uniform base + 32-bit offset
+                    row += qstep;
+                    c += rstep;
+                    if (c >= chunks) { c -= chunks; ++row; }
+                }
+                if (!FUSED_PREFETCH_EARLY && base == 0) first_fragments();
+                row = row0;
+                c = c0;
 #pragma unroll
-            for (int i = 0; i < XP; ++i) {
-                const int rr = min(row, m - 1);  // a piece past the last row: the last row's, written again
-                xs[((c >> 2) * m + rr) * 4 + (c & 3)] = v[i];
-                row += qstep;
-                c += rstep;
-                if (c >= chunks) { c -= chunks; ++row; }
+                for (int i = 0; i < D; ++i) {
+                    const int rr = min(row, m - 1);  // a piece past the last row: the last row's, written again
+                    xs[((c >> 2) * m + rr) * 4 + (c & 3)] = v[i];
+                    row += qstep;
+                    c += rstep;
+                    if (c >= chunks) { c -= chunks; ++row; }
+                }
             }
-        }
+        };
+        if (FUSED_SHORT_COPY && pieces <= FT * (XP / 2)) stage_copy(std::integral_constant<int, XP / 2>{});
+        else stage_copy(std::integral_constant<int, XP>{});
     }
     lds_sync();
     TRACE(3);
