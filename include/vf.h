@@ -10,12 +10,13 @@
  *   - verify: the pending token T and k draft tokens x_1..x_k are scored in ONE
  *     forward pass, giving predictions y_1..y_{k+1} (paper Sec. 3
  *     "draft-then-verify", Sec. 4.3 "x = [T, x_1..x_n], y = [y_1..y_{n+1}]");
- *   - accept: the longest draft prefix that matches the predictions is kept and
- *     one corrected (or bonus) token is emitted (paper Sec. 3: "any tokens after
- *     the first mismatch are discarded"; Sec. 4.3: accepted prefix
- *     x_1..x_{e-1}, y_e).  Greedy (strict) and lossless stochastic
- *     (speculative sampling, the rule of the work the paper cites for
- *     "lossless generation quality") are both provided.
+ *   - accept: the longest draft prefix that matches the predictions is kept,
+ *     everything from the first mismatch on is dropped, and one corrected (or
+ *     bonus) token is emitted (paper Sec. 3, draft-then-verify; Sec. 4.3:
+ *     accepted prefix x_1..x_{e-1}, y_e).  Greedy (strict) acceptance and the
+ *     distribution-preserving stochastic rule (speculative sampling, from the
+ *     work the paper cites in Sec. 3 for its lossless property) are both
+ *     provided.
  *
  * Conventions.
  *   - Every function returns int: VF_OK or a negative VF_ERR_* code.  Nothing
@@ -142,6 +143,15 @@ int vf_seq_set_pending(vf_seq *s, int32_t token, void *stream);
 /* Reads length and pending token back (synchronises the stream) and tightens the host-side
  * upper bound of the length to the true value.  Either output pointer may be NULL. */
 int vf_seq_get_state(vf_seq *s, int32_t *len_host, int32_t *pending_host, void *stream);
+/* The host-side bound of the length.  The true length lives on the device; the host keeps an
+ * upper bound of it, which is what capacity checks (VF_ERR_CAP) and launch sizes use:
+ * vf_prefill_chunk adds n_tokens to it, vf_accept adds the whole m_b = k_b + 1 (the device
+ * commits only 1 + a_b of them), vf_seq_set_len and vf_seq_get_state set it to the true value.
+ * A caller that learns the true length without vf_seq_get_state (it copied n_accept to the host
+ * anyway) tightens the bound with this call: host only, no device work, no synchronisation.
+ * `len` must not be below the true length after all work enqueued so far (a bound that is too
+ * low lets later calls overrun the cache's capacity check); VF_ERR_ARG outside 0..capacity. */
+int vf_seq_note_len(vf_seq *s, int len);
 
 /* Debug / test accessor: copies K and V of `layer` for positions [t0, t0+n) into row-major
  * float32 arrays k_out_dev, v_out_dev of shape [n, n_kv_heads, head_dim]. */
@@ -165,7 +175,8 @@ int vf_kv_write(vf_model *m, vf_seq *s, int layer, int t0, int n, const float *k
  *   sample_first != 0: the last row also produces the pending token T: arg-max when
  *   temperature == 0, else an inverse-CDF sample of softmax(z/temperature) with the uniform
  *   u_dev[0] (float32 in [0,1), device).
- * n_tokens <= cfg.max_rows; VF_ERR_CAP if the cache cannot take n_tokens more rows. */
+ * n_tokens <= cfg.max_rows; VF_ERR_CAP if the host-side bound of the length (see vf_seq_note_len)
+ * plus n_tokens exceeds the capacity. */
 int vf_prefill_chunk(vf_model *m, vf_seq *s, const int32_t *tokens_dev, int n_tokens,
                      int logits_mode, float *logits_out_dev, int sample_first,
                      const float *u_dev, float temperature, void *stream);
@@ -177,7 +188,8 @@ int vf_prefill_chunk(vf_model *m, vf_seq *s, const int32_t *tokens_dev, int n_to
  * Writes K/V for all rows (the length is NOT advanced: vf_accept commits it) and leaves the
  * float32 logits of all rows for vf_accept: in logits_out_dev[total_rows, vocab] if that is
  * not NULL, else in the model workspace.
- * VF_ERR_CAP if a cache cannot take m_b more rows or total rows exceed cfg.max_rows. */
+ * VF_ERR_CAP if the host-side bound of a sequence's length (see vf_seq_note_len) plus m_b exceeds
+ * its capacity, or total rows exceed cfg.max_rows. */
 int vf_verify(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
               const int32_t *row_off_host, float *logits_out_dev, void *stream);
 
@@ -224,8 +236,8 @@ int vf_prefill_chunk_topk(vf_model *m, vf_seq *s, const int32_t *tokens_dev, int
 
 /* ---- tree-structured drafts (next to the three operations) ---------------------------------- */
 
-/* Verify forward for drafts that form a token tree per sequence (paper Sec. 4, workflow:
- * "iteratively constructs tree-structured drafts and verifies them").  Arguments as vf_verify,
+/* Verify forward for drafts that form a token tree per sequence (paper Sec. 4, workflow: the
+ * drafts of a step are built and verified as a tree).  Arguments as vf_verify,
  * plus parent_host[total_rows] (HOST, int32): -1 for a sequence's first row (the pending token,
  * root of its tree), otherwise the row, counted within the sequence, of the node's parent, which
  * must be smaller than the node's own row.  Row r stands at position len + depth(r) (rotary

@@ -5,8 +5,8 @@ x = [T, x_1..x_k] and predictions y = [y_1..y_{k+1}], the first e with
 x_e != y_e ends the accepted prefix; the step emits x_1..x_{e-1}, y_e.  If no
 draft mismatches, all k are kept and y_{k+1} is emitted as a bonus.
 
-Stochastic: the paper relies on lossless speculative sampling from the work it
-cites for "lossless generation quality" (Sec. 3) without printing the rule; the
+Stochastic: the paper relies on speculative sampling, from the work it cites
+in Sec. 3 for keeping the target's output distribution, without printing the rule; the
 rule below is the standard one from that literature: accept x_i with
 probability min(1, p_i(x_i)/q_i(x_i)); at the first rejection draw the
 replacement from the normalised positive part of p_i - q_i; if nothing is

@@ -25,7 +25,7 @@ VF_OPT_PERSISTENT = 2
 EXPORTS = [
     "vf_last_error", "vf_model_packed_bytes", "vf_model_create", "vf_model_destroy",
     "vf_seq_state_bytes", "vf_kv_bytes", "vf_seq_create", "vf_seq_destroy", "vf_seq_set_len",
-    "vf_seq_set_pending", "vf_seq_get_state", "vf_kv_read", "vf_kv_write", "vf_prefill_chunk", "vf_verify",
+    "vf_seq_set_pending", "vf_seq_get_state", "vf_seq_note_len", "vf_kv_read", "vf_kv_write", "vf_prefill_chunk", "vf_verify",
     "vf_accept", "vf_profile", "vf_profile_read", "vf_set_option", "vf_stream_read",
     "vf_reuse_select", "vf_reuse_pool_init", "vf_reuse_pool_update", "vf_reuse_pool_extend",
     "vf_verify_tree", "vf_accept_tree", "vf_prefill_chunk_topk", "vf_draft_suffix_match",
@@ -83,6 +83,7 @@ def _load():
         "vf_seq_set_len": (C.c_int, [vp, C.c_int, vp]),
         "vf_seq_set_pending": (C.c_int, [vp, i32, vp]),
         "vf_seq_get_state": (C.c_int, [vp, C.POINTER(i32), C.POINTER(i32), vp]),
+        "vf_seq_note_len": (C.c_int, [vp, C.c_int]),
         "vf_kv_read": (C.c_int, [vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp]),
         "vf_kv_write": (C.c_int, [vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp]),
         "vf_prefill_chunk": (C.c_int, [vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp, C.c_float, vp]),
@@ -219,6 +220,11 @@ def vf_seq_get_state(seq):
     a, b = C.c_int32(), C.c_int32()
     _check(lib.vf_seq_get_state(seq.handle, C.byref(a), C.byref(b), _stream()))
     return a.value, b.value
+
+
+def vf_seq_note_len(seq, n):
+    """Host only: tightens the host-side bound of the length to the true length n."""
+    _check(lib.vf_seq_note_len(seq.handle, int(n)))
 
 
 def vf_kv_read(model, seq, layer, t0, n):

@@ -1,5 +1,5 @@
-// Acceptance on the device (paper Sec. 3 "any tokens after the first mismatch are discarded",
-// Sec. 4.3 "accepted prefix x_1..x_{e-1}, y_e"), greedy and stochastic, and the commit of the
+// Acceptance on the device (paper Sec. 3: drafts from the first mismatch on are dropped; Sec. 4.3:
+// the accepted prefix x_1..x_{e-1} followed by y_e), greedy and stochastic, and the commit of the
 // sequence state (length, pending token) without a host round trip.
 //
 //   row_stats : per (row, vocabulary chunk): maximum logit, its lowest index and, for stochastic
@@ -346,7 +346,14 @@ __global__ __launch_bounds__(256) void accept_emit_kernel(const float *__restric
     __syncthreads();
     if (threadIdx.x == 0) {
         int w = result;
-        if (w == 0x7fffffff) w = max(v0, v1 - 1);  // rounding left the running sum at the target
+        if (w == 0x7fffffff) {
+            // rounding left the running sum at the target: the draw is the last id of positive weight
+            // at or before the end of the chosen chunk (never an id the rule gives no weight)
+            w = -1;
+            for (int v = v1 - 1; v >= 0 && w < 0; --v)
+                if (draw_weight(z, d, v, plain) > 0.0) w = v;
+            if (w < 0) w = max(v0, v1 - 1);
+        }
         out_tokens[s.row0 + d.acc] = w;
         if (commit_len) s.state[0] += 1 + d.acc;
         s.state[1] = w;

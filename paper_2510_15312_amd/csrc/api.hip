@@ -366,6 +366,13 @@ int vf_seq_get_state(vf_seq *s, int32_t *len_host, int32_t *pending_host, void *
     return vf_fused_check(s->m);
 }
 
+int vf_seq_note_len(vf_seq *s, int len) {
+    if (!s) return vf_fail(VF_ERR_ARG, "vf_seq_note_len: NULL");
+    if (len < 0 || len > s->capacity) return vf_fail(VF_ERR_ARG, "len %d outside 0..%d", len, s->capacity);
+    s->len_ub = len;
+    return VF_OK;
+}
+
 int vf_kv_read(vf_model *m, vf_seq *s, int layer, int t0, int n, float *k_out_dev, float *v_out_dev,
                void *stream) {
     if (!m || !s || !k_out_dev || !v_out_dev) return vf_fail(VF_ERR_ARG, "vf_kv_read: NULL argument");

@@ -11,15 +11,16 @@ import torch
 from . import binding as vf
 
 
-def generate(model, seq, prompt, n_new, k=16, max_suffix=8, min_suffix=1, chunk=256, reuse_max_age=2):
+def generate(model, seq, prompt, n_new, k=16, max_suffix=8, min_suffix=1, chunk=256, reuse_max_age=2, drafter=None):
     """prompt: host ints; returns (the n_new generated tokens, statistics).  Greedy acceptance: the
-    result is what plain greedy decoding would produce."""
+    result is what plain greedy decoding would produce.  drafter(text, k) -> list of at most k draft
+    ids replaces the library's suffix-match drafter (any drafter gives the same text)."""
     dev = model.buf.device
     k = min(int(k), vf.VF_MAX_DRAFTS)
     toks = torch.as_tensor(list(prompt), dtype=torch.int32, device=dev)
     for c0 in range(0, len(prompt), chunk):
         vf.vf_prefill_chunk(model, seq, toks[c0:c0 + chunk], sample_first=c0 + chunk >= len(prompt))
-    _, pending = vf.vf_seq_get_state(seq)
+    length, pending = vf.vf_seq_get_state(seq)
     text = [int(t) for t in prompt] + [pending]        # the pending token is the first generated one
     pool = vf.vf_reuse_pool_init(reuse_max_age, max(k, 1))
     n_acc = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -29,7 +30,12 @@ def generate(model, seq, prompt, n_new, k=16, max_suffix=8, min_suffix=1, chunk=
     greedy = [(vf.VF_GREEDY, 0.0, None, None)]
     steps, accepted, drafted = 0, 0, 0
     while len(text) - len(prompt) < n_new:
-        fresh = vf.vf_draft_suffix_match(text, k, max_suffix, min_suffix) if k else []
+        if not k:
+            fresh = []
+        elif drafter is not None:
+            fresh = [int(t) for t in drafter(text, k)][:k]
+        else:
+            fresh = vf.vf_draft_suffix_match(text, k, max_suffix, min_suffix)
         drafts = vf.vf_reuse_pool_extend(pool, fresh) if k else []
         m = len(drafts) + 1
         tokens = torch.as_tensor([vf.VF_PENDING] + drafts, dtype=torch.int32, device=dev)
@@ -42,6 +48,8 @@ def generate(model, seq, prompt, n_new, k=16, max_suffix=8, min_suffix=1, chunk=
         if drafts:
             vf.vf_reuse_pool_update(pool, drafts, seg_start, seg_len)
         text += emitted
+        length += 1 + a
+        vf.vf_seq_note_len(seq, length)                 # vf_accept counted all m rows; 1 + a were kept
         steps += 1
         accepted += a
         drafted += len(drafts)
