@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+METRIC = "verify-step latency (\u00b5s) + achieved HBM GB/s vs peak, 1.5B shape k=16"
 # HBM bytes per launch of the gate/up GEMM kernel from hardware counters (FETCH_SIZE + WRITE_SIZE,
 # each scaled by what the same counter reads for a plain 1 GiB copy); 56,474,000 when last taken, see
 # profiles/gateup_gemm_1.5b_k16_pmc.md.  None: the kernel's source has changed since.
@@ -72,45 +73,195 @@ def draft_with_distribution(vf, torch, model, seq, pending, k, temperature, scal
     return drafts, torch.stack(qs).contiguous()
 
 
-def cpu_baseline(cfg, wd, ctx_len, k, temperature):
-    """The oracle's verify + accept on the host: 4 of the 28 layers plus the full output head and
-    acceptance are timed on a cache of ctx_len random rows (about 5 s of repeats each for the
-    0-layer and the 4-layer model), and the step is extrapolated linearly in the layer count."""
+def cpu_baseline(cfg, wd, ctx_tokens, step_inputs, lens, own_prefill, budget_s=8.0):
+    """The oracle as it stands, at full depth, on the host cores: float32 copies of the weights (the
+    accumulation precision the workload fixes), the steps' own tokens, draft distributions and
+    uniforms, teacher-forced along the recorded trajectory.  own_prefill: the oracle first prefills
+    the context itself in the workload's chunks (timed separately); otherwise its cache starts from
+    random bfloat16 rows of the same shape (a context of the same length costs the same to attend
+    to).  A bounded sample: as many successive steps as fit `budget_s` seconds, at least two."""
     import oracle
+    from oracle.loop import truncate
     from oracle.transformer import LayerWeights
-    import workloads as wl
     cores = len(os.sched_getaffinity(0))
-    rng = np.random.default_rng(7)
-    f64 = lambda a: np.asarray(a, dtype=np.float64)
-    layers = [LayerWeights(**{n: f64(v) for n, v in lw.items()}) for lw in wd["layers"][:4]]
-    embed, fnorm = f64(wd["embed"]), f64(wd["final_norm"])
-    m = k + 1
-    toks = rng.integers(0, cfg.vocab, m)
-    q = rng.dirichlet(np.full(cfg.vocab, 0.05), size=k).astype(np.float32)
-    u = wl.make_uniforms(m, rng)
-    times = {}
-    for nl in (0, 4):
-        spec = oracle.ModelSpec(nl, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn,
-                                cfg.vocab, cfg.dtype, cfg.rope_theta, cfg.rms_eps)
-        w = oracle.Weights(embed, fnorm, layers[:nl])
-        cache = oracle.KVCache(spec, ctx_len + m)
-        if nl:
-            cache.k[:, :, :ctx_len] = oracle.round_bf16(rng.standard_normal(cache.k[:, :, :ctx_len].shape))
-            cache.v[:, :, :ctx_len] = oracle.round_bf16(rng.standard_normal(cache.v[:, :, :ctx_len].shape))
-        best, t_start = [], time.perf_counter()
-        while len(best) < 3 or time.perf_counter() - t_start < 5.0:
-            cache.len = ctx_len
-            t0 = time.perf_counter()
-            z = oracle.verify(spec, w, cache, toks[0], toks[1:])
-            oracle.stochastic_accept(z.astype(np.float32), toks[1:], q, u, temperature)
-            best.append(time.perf_counter() - t0)
-        times[nl] = float(np.median(best))
-    per_layer = (times[4] - times[0]) / 4
-    full = times[0] + cfg.n_layers * per_layer
-    return {"value": round(full * 1e6, 1), "unit": "us/step", "cores": cores, "kind": "oracle",
-            "sample": f"numpy float64 oracle verify+accept, {m} rows, ctx {ctx_len}: 4 of {cfg.n_layers} "
-                      f"layers ({per_layer * 1e3:.1f} ms/layer) + full output head and acceptance "
-                      f"({times[0] * 1e3:.1f} ms), extrapolated linearly to {cfg.n_layers} layers"}
+    dt = np.float32
+    spec = oracle.ModelSpec(cfg.n_layers, cfg.d_model, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn,
+                            cfg.vocab, cfg.dtype, cfg.rope_theta, cfg.rms_eps)
+    c = lambda a: np.asarray(a, dtype=dt)
+    w = oracle.Weights(c(wd["embed"]), c(wd["final_norm"]),
+                       [LayerWeights(**{n: c(v) for n, v in lw.items()}) for lw in wd["layers"]])
+    m = len(step_inputs[0][0])
+    cache = oracle.KVCache(spec, lens[min(len(step_inputs), len(lens) - 1)] + m, dt)
+    prefill_s = None
+    if own_prefill:
+        t0 = time.perf_counter()
+        oracle.prefill(spec, w, cache, ctx_tokens, cfg.chunk, dt)
+        prefill_s = time.perf_counter() - t0
+    else:
+        rng = np.random.default_rng(7)
+        n = lens[0]
+        cache.k[:, :, :n] = oracle.round_bf16(rng.standard_normal(cache.k[:, :, :n].shape, dtype=np.float32))
+        cache.v[:, :, :n] = oracle.round_bf16(rng.standard_normal(cache.v[:, :, :n].shape, dtype=np.float32))
+    times, t_start = [], time.perf_counter()
+    for i, (tokens, mode, temperature, q, u) in enumerate(step_inputs):
+        if len(times) >= 2 and time.perf_counter() - t_start > budget_s:
+            break
+        cache.len = lens[i]
+        t0 = time.perf_counter()
+        z = oracle.verify(spec, w, cache, tokens[0], tokens[1:], dt)
+        if mode == "stochastic":
+            oracle.stochastic_accept(z, tokens[1:], q, u, temperature)
+        else:
+            oracle.greedy_accept(z, tokens[1:])
+        times.append(time.perf_counter() - t0)
+        truncate(cache, lens[i + 1])                    # what the recorded trajectory kept
+    step = float(np.median(times))
+    sample = (f"numpy oracle (float32 accumulation, {cfg.n_layers} layers, full vocabulary) verify+accept on the first "
+              f"{len(times)} of the timed steps' own inputs ({m} rows, context {lens[0]}), median; ")
+    sample += (f"cache from the oracle's own chunked prefill of the {lens[0]}-token context ({prefill_s:.1f} s, not in the value)"
+               if own_prefill else "cache of random bfloat16 rows of the same length")
+    out = {"value": round(step * 1e6, 1), "unit": "us/step", "cores": cores, "kind": "oracle", "sample": sample}
+    if prefill_s is not None:
+        out["prefill_s"] = round(prefill_s, 2)
+    return out
+
+
+def bench_mix(args, cfg, torch, wl, vf):
+    """The batched RAG mix: 16 paged sequences with lognormal context lengths, each prefilled in
+    256-token chunks into a shared pool of 64-token pages behind a permuted block table; a step =
+    one batched vf_verify + vf_accept over the ragged rows (draft counts 1..32, greedy and
+    stochastic acceptance mixed, one sequence with a dense draft distribution).  The lengths are put
+    back between steps (outside the timed pairs of events), so every step is the same step."""
+    K, W = args.steps, args.warmup
+    s = wl.streams(cfg)
+    mix = wl.rag_mix(cfg, s.mix)
+    B, V = cfg.batch, cfg.vocab
+    total = int(np.sum(mix.k + 1))
+    model, wd = build_model(cfg, vf, wl, torch, max(cfg.chunk, total), int(mix.ctx.max()) + 128)
+    if args.persistent is not None:
+        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, args.persistent)
+    pool = torch.empty(vf.vf_kv_bytes(model, cfg.page_tokens, mix.n_pages), dtype=torch.uint8, device="cuda:0")
+    seqs, ctxs = [], []
+    for b in range(B):
+        bt = torch.as_tensor(mix.block_tables[b], dtype=torch.int32, device="cuda:0")
+        seqs.append(vf.vf_seq_create(model, len(mix.block_tables[b]) * cfg.page_tokens, pool, bt, "cuda:0"))
+        ctxs.append(torch.as_tensor(wl.make_context(V, int(mix.ctx[b]), s.context), device="cuda:0"))
+    for timed in (False, True):   # the first pass also loads the kernels
+        for sq in seqs:
+            vf.vf_seq_set_len(sq, 0)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        for b in range(B):
+            n = int(mix.ctx[b])
+            for c0 in range(0, n, cfg.chunk):
+                vf.vf_prefill_chunk(model, seqs[b], ctxs[b][c0:c0 + cfg.chunk], sample_first=c0 + cfg.chunk >= n)
+        torch.cuda.synchronize()
+        prefill_ms = (time.time() - t0) * 1e3
+    log(f"[bench] prefill of {int(mix.ctx.sum())} tokens in {B} sequences: {prefill_ms:.1f} ms")
+    row_off = [0]
+    for kb in mix.k:
+        row_off.append(row_off[-1] + int(kb) + 1)
+    toks, params, dense_done = [], [], False
+    for b in range(B):
+        kb = int(mix.k[b])
+        drafts = wl.copy_span_drafts(ctxs[b].cpu().numpy(), kb, 0.6, V, s.drafts).tolist()
+        toks += [vf.VF_PENDING] + drafts
+        if mix.stochastic[b]:
+            u = torch.as_tensor(wl.make_uniforms(kb + 1, s.uniforms), device="cuda:0")
+            q = None
+            if not dense_done:
+                qs = s.gumbel.dirichlet(np.full(V, 0.05), size=kb).astype(np.float32)
+                qs[np.arange(kb), drafts] += 0.5
+                q = torch.as_tensor((qs / qs.sum(-1, keepdims=True, dtype=np.float64)).astype(np.float32), device="cuda:0")
+                dense_done = True
+            params.append((vf.VF_STOCHASTIC, cfg.temperature, q, u))
+        else:
+            params.append((vf.VF_GREEDY, 0.0, None, None))
+    tokens = torch.tensor(toks, dtype=torch.int32, device="cuda:0")
+    n_acc = torch.zeros(B, dtype=torch.int32, device="cuda:0")
+    out_t = torch.zeros(total, dtype=torch.int32, device="cuda:0")
+    y_t = torch.zeros(total, dtype=torch.int32, device="cuda:0")
+    pend0 = [vf.vf_seq_get_state(sq)[1] for sq in seqs]
+
+    def step(ev=None):
+        for b, sq in enumerate(seqs):
+            vf.vf_seq_set_len(sq, int(mix.ctx[b]))
+            vf.vf_seq_set_pending(sq, pend0[b])
+        if ev is not None:
+            ev[0].record()
+        vf.vf_verify(model, seqs, tokens, row_off)
+        vf.vf_accept(model, seqs, tokens, row_off, params, n_acc, out_t, y_t)
+        if ev is not None:
+            ev[1].record()
+
+    for _ in range(W):
+        step()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    torch.cuda.synchronize()
+    for i in range(K):
+        step(evs[i])
+    torch.cuda.synchronize()
+    per = np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
+    ms_per_step = float(per.mean()) * 1e-3
+    kvb = cfg.kv_bytes_per_token()
+    bytes_step = cfg.weight_bytes() + int(mix.ctx.sum() + total) * kvb + total * kvb + 2 * total * V * 4
+    gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
+    vf.vf_profile(model, True)
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    vf.vf_profile(model, False)
+    prof = vf.vf_profile_read(model)
+    site_tbl = {n: {"us_per_step": round(prof[n][0] / K * 1e3, 1), "launches_per_step": prof[n][1] // K} for n in prof}
+    log("[bench] per-site time per step (instrumented pass): " + json.dumps(site_tbl))
+    if prof["step"][1]:
+        kern = f"verify_fused_kernel (embedding, {cfg.n_layers} decoder layers, output head in one persistent launch)"
+        k_bytes = float(cfg.weight_bytes() + int(mix.ctx.sum() + total) * kvb + total * kvb + total * V * 4)
+        avg_us = prof["step"][0] / prof["step"][1] * 1e3
+    else:
+        kern = "gemm_rows_kernel (gate/up GEMM + SwiGLU, many-row tile), one launch per layer"
+        k_bytes = float(2 * cfg.d_ffn * cfg.d_model * 2 + total * cfg.d_model * 2 + total * cfg.d_ffn * 2)
+        avg_us = prof["gateup"][0] / prof["gateup"][1] * 1e3
+    achieved = k_bytes / (avg_us * 1e-6) / 1e9
+    flops = 2.0 * total * (cfg.weight_bytes() // 2)
+    res = {
+        "metric": f"verify-step latency (\u00b5s) + achieved HBM GB/s vs peak, {cfg.name}",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_layers}L d{cfg.d_model} {cfg.n_q_heads}/{cfg.n_kv_heads} heads hd{cfg.head_dim} "
+                               f"ffn{cfg.d_ffn} vocab{V}; {B} paged sequences (64-token pages, permuted block tables), contexts "
+                               f"{int(mix.ctx.min())}..{int(mix.ctx.max())} (sum {int(mix.ctx.sum())}) prefilled in {cfg.chunk}-token "
+                               f"chunks, one batched ragged verify step of {total} rows (k_b 1..32), greedy and stochastic "
+                               f"acceptance mixed, repeated {K} times from the same state",
+                   "batch": B, "rows_per_step": total},
+        "us_per_step": round(ms_per_step * 1e3, 1),
+        "us_per_step_p10_p50_p90": [round(float(np.percentile(per, p)), 1) for p in (10, 50, 90)],
+        "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes_per_step": int(bytes_step),
+        "TFLOP/s": round(flops / (ms_per_step * 1e-3) / 1e12, 1),
+        "prefill": {"tokens": int(mix.ctx.sum()), "chunk": cfg.chunk, "ms": round(prefill_ms, 1)},
+        "roofline": {"bound": "hbm", "kernel": kern, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "avg_launch_us": round(avg_us, 2),
+                     "bytes_per_launch": int(k_bytes)},
+        "sites_us_per_step": {n: site_tbl[n]["us_per_step"] for n in site_tbl},
+    }
+    if not args.no_cpu_baseline:
+        # a bounded sample: the shortest sequence of the mix alone, prefilled and verified by the oracle
+        b = int(np.argmin(mix.ctx))
+        r0, r1 = row_off[b], row_off[b + 1]
+        tk = tokens[r0:r1].cpu().numpy().astype(np.int64)
+        tk[0] = pend0[b]
+        mode, t_, q_, u_ = params[b]
+        host = [(tk, "stochastic" if mode == vf.VF_STOCHASTIC else "greedy", t_, None if q_ is None else q_.cpu().numpy(),
+                 None if u_ is None else u_.cpu().numpy())] * 4
+        n = int(mix.ctx[b])
+        ctx_host = ctxs[b].cpu().numpy()
+        del model
+        torch.cuda.empty_cache()
+        cb = cpu_baseline(cfg, wd, ctx_host, host, [n] * 5, own_prefill=True, budget_s=6.0)
+        cb["sample"] = (f"ONE of the {B} sequences (the shortest: context {n}, {r1 - r0} rows) instead of the batch; " + cb["sample"])
+        res["cpu_baseline"] = cb
+    print(json.dumps(res), flush=True)
 
 
 def wl_depths(parents):
@@ -149,6 +300,8 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(3)
     cfg = wl.CONFIGS[args.config]
+    if cfg.batch > 1:
+        return bench_mix(args, cfg, torch, wl, vf)
     k, m, K, W = cfg.k, cfg.k + 1, args.steps, args.warmup
     n_traj = max(K, W)
     cap = (cfg.ctx + (n_traj + 1) * m + 63) // 64 * 64
@@ -254,10 +407,10 @@ def main():
     # all weights once + the KV cache read + the new KV rows and the logits written), else the
     # gate/up GEMM of the per-GEMM chain (its weight matrix once)
     if prof["step"][1]:
-        kern = "verify_fused_kernel (embedding, 28 decoder layers, output head in one persistent launch)"
+        kern = f"verify_fused_kernel (embedding, {cfg.n_layers} decoder layers, output head in one persistent launch)"
         k_bytes = float(np.mean([cfg.weight_bytes() + (lens[i] + m) * kvb + m * kvb + m * V * 4 for i in range(K)]))
         avg_us = prof["step"][0] / prof["step"][1] * 1e3
-        traffic = FUSED_TRAFFIC_BYTES
+        traffic = FUSED_TRAFFIC_BYTES if args.config == "1.5b_k16" else None
     else:
         kern = "gemm_fast_kernel<2,2,6,EPI_SWIGLU,4> (gate/up GEMM + SwiGLU)"
         k_bytes = float(2 * cfg.d_ffn * cfg.d_model * 2)
@@ -269,7 +422,7 @@ def main():
     log("[bench] per-site time per step (instrumented pass): " + json.dumps(site_tbl))
 
     res = {
-        "metric": "verify-step latency (us) + achieved HBM GB/s vs peak, 1.5B shape k=16",
+        "metric": METRIC if args.config == "1.5b_k16" else f"verify-step latency (\u00b5s) + achieved HBM GB/s vs peak, {cfg.name}",
         "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
@@ -382,10 +535,17 @@ def main():
         torch.cuda.synchronize()
         del a, b
     if not args.no_cpu_baseline:
-        del model
+        n_cpu = min(K, 12)
+        host_steps = []
+        for tokens, params in steps_in[:n_cpu]:
+            _, t_, q_, u_ = params[0]
+            host_steps.append((tokens.cpu().numpy().astype(np.int64), cfg.mode, t_,
+                               None if q_ is None else q_.cpu().numpy(), None if u_ is None else u_.cpu().numpy()))
+        ctx_host = ctx.cpu().numpy()
+        del model, steps_in
         torch.cuda.empty_cache()
         t0 = time.time()
-        res["cpu_baseline"] = cpu_baseline(cfg, wd, cfg.ctx, k, cfg.temperature or 1.0)
+        res["cpu_baseline"] = cpu_baseline(cfg, wd, ctx_host, host_steps, lens, own_prefill=args.config == "1.5b_k16")
         log(f"[bench] cpu baseline took {time.time() - t0:.1f}s")
     print(json.dumps(res), flush=True)
 

@@ -127,12 +127,16 @@ def tree_depths(parents):
     return depth
 
 
-def forward(spec: ModelSpec, w: Weights, cache: KVCache, tokens, dt=np.float64, parents=None):
+def forward(spec: ModelSpec, w: Weights, cache: KVCache, tokens, dt=np.float64, parents=None, logit_rows=None):
     """Run `tokens` (ids) at positions cache.len.. through the model.
 
     Appends their K/V rows to the cache and returns the logits [n, V] (dtype
     `dt`): row r is the model's prediction for the token after position
     cache.len + r.  `w` must already hold arrays of dtype `dt`.
+
+    logit_rows: if given, the output head is applied to these rows only and
+    the result is [len(logit_rows), V] (the same values: a row's logits depend
+    on no other row of the final hidden state); the layers run on all rows.
 
     parents (tree-structured drafts, Sec. 4 "tree-structured drafts"): row r is
     a node of a token tree rooted at row 0.  It stands at the position of its
@@ -195,6 +199,8 @@ def forward(spec: ModelSpec, w: Weights, cache: KVCache, tokens, dt=np.float64, 
         a = act(silu(x @ lw.w_gate.T) * (x @ lw.w_up.T))
         h = h + a @ lw.w_down.T
     cache.len = p0 + n
+    if logit_rows is not None:
+        h = h[np.asarray(logit_rows, dtype=np.int64)]
     return act(rmsnorm(h, w.final_norm, spec.rms_eps)) @ w.embed.T
 
 
@@ -206,7 +212,8 @@ def prefill(spec, w, cache, tokens, chunk, dt=np.float64):
     tokens = np.asarray(tokens)
     z = None
     for s in range(0, len(tokens), chunk):
-        z = forward(spec, w, cache, tokens[s:s + chunk], dt)
+        piece = tokens[s:s + chunk]
+        z = forward(spec, w, cache, piece, dt, logit_rows=[len(piece) - 1])
     return z[-1]
 
 

@@ -11,10 +11,11 @@ import torch
 from . import binding as vf
 
 
-def generate(model, seq, prompt, n_new, k=16, max_suffix=8, min_suffix=1, chunk=256, reuse_max_age=2, drafter=None):
+def generate(model, seq, prompt, n_new, k=16, max_suffix=8, min_suffix=1, chunk=256, reuse_max_age=2, drafter=None, reuse=True):
     """prompt: host ints; returns (the n_new generated tokens, statistics).  Greedy acceptance: the
     result is what plain greedy decoding would produce.  drafter(text, k) -> list of at most k draft
-    ids replaces the library's suffix-match drafter (any drafter gives the same text)."""
+    ids replaces the library's suffix-match drafter (any drafter gives the same text); reuse=False
+    leaves the pool of rejected drafts out."""
     dev = model.buf.device
     k = min(int(k), vf.VF_MAX_DRAFTS)
     toks = torch.as_tensor(list(prompt), dtype=torch.int32, device=dev)
@@ -36,16 +37,16 @@ def generate(model, seq, prompt, n_new, k=16, max_suffix=8, min_suffix=1, chunk=
             fresh = [int(t) for t in drafter(text, k)][:k]
         else:
             fresh = vf.vf_draft_suffix_match(text, k, max_suffix, min_suffix)
-        drafts = vf.vf_reuse_pool_extend(pool, fresh) if k else []
+        drafts = vf.vf_reuse_pool_extend(pool, fresh) if k and reuse else fresh
         m = len(drafts) + 1
         tokens = torch.as_tensor([vf.VF_PENDING] + drafts, dtype=torch.int32, device=dev)
         vf.vf_verify(model, [seq], tokens, [0, m])
         vf.vf_accept(model, [seq], tokens, [0, m], greedy, n_acc, out[:m], y[:m])
-        if drafts:
+        if drafts and reuse:
             vf.vf_reuse_select(tokens, [0, m], y[:m], n_acc, seg)
         host = torch.cat([n_acc, seg, out[:m]]).cpu().tolist()          # the step's one synchronisation
         a, seg_start, seg_len, emitted = host[0], host[1], host[2], host[3:4 + host[0]]
-        if drafts:
+        if drafts and reuse:
             vf.vf_reuse_pool_update(pool, drafts, seg_start, seg_len)
         text += emitted
         length += 1 + a

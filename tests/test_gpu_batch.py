@@ -14,13 +14,13 @@ from oracle.loop import plain_greedy, truncate
 import workloads as wl
 import paper_2510_15312_amd as vf
 from util_oracle import rel_inf
-from util_gpu import DEV, Pair, i32, f32, accept_margin_ok
+from util_gpu import DEV, Pair, i32, f32, accept_margin_ok, stochastic_margins
 
 pytestmark = pytest.mark.gpu
 C = wl.CONFIGS
 
 
-def _paged_setup(pair, cfg, mix):
+def _paged_setup(pair, cfg, mix, check_kv=False):
     """Pool + one paged sequence per entry of the mix, prefilled on both sides."""
     pool = torch.empty(vf.vf_kv_bytes(pair.model, 64, mix.n_pages), dtype=torch.uint8, device=DEV)
     seqs, caches, pendings, ctxs = [], [], [], []
@@ -33,6 +33,12 @@ def _paged_setup(pair, cfg, mix):
         ctx = wl.make_context(cfg.vocab, n_ctx, pair.s.context)
         z_or, z_gpu = pair.prefill_both(seq, cache, ctx, cfg.chunk)
         assert rel_inf(z_gpu[None], z_or[None]).max() < 2e-2, b
+        if check_kv:   # the deepest layer's K/V carry every attention pass below it
+            (kg, vg), (ko, vo) = pair.kv_both(seq, cache, cfg.n_layers - 1, 0, n_ctx)
+            ek, ev = np.abs(kg - ko).max() / np.abs(ko).max(), np.abs(vg - vo).max() / np.abs(vo).max()
+            print(f"sequence {b}: context {n_ctx}: prefill last-row error "
+                  f"{rel_inf(z_gpu[None], z_or[None]).max():.3e}, K {ek:.2e}, V {ev:.2e}", flush=True)
+            assert ek <= 1e-2 and ev <= 1e-2, (b, ek, ev)
         seqs.append(seq)
         caches.append(cache)
         ctxs.append(ctx)
@@ -40,13 +46,13 @@ def _paged_setup(pair, cfg, mix):
     return pool, seqs, caches, pendings, ctxs
 
 
-def _run_mix(cfg, mix, expect_fast, persistent=True):
+def _run_mix(cfg, mix, expect_fast, persistent=True, check_kv=False):
     total = int(np.sum(mix.k + 1))
     pair = Pair(cfg, max_rows=max(cfg.chunk, total), max_positions=int(mix.ctx.max()) + 64 + 64)
     s = pair.s
     assert vf.lib.vf_set_option(pair.model.handle, vf.VF_OPT_FAST_PATH, 1) == 0
     vf.vf_set_option(pair.model, vf.VF_OPT_PERSISTENT, int(persistent))
-    pool, seqs, caches, pendings, ctxs = _paged_setup(pair, cfg, mix)
+    pool, seqs, caches, pendings, ctxs = _paged_setup(pair, cfg, mix, check_kv)
     B = len(seqs)
     temp = cfg.temperature
     # inputs per sequence: the target's own continuation with one mismatch; stochastic sequences
@@ -80,7 +86,7 @@ def _run_mix(cfg, mix, expect_fast, persistent=True):
     vf.vf_accept(pair.model, seqs, tok_dev, row_off, params, n_acc, out, y)
     torch.cuda.synchronize()
     zg, n_acc, out, y = logits.cpu().numpy(), n_acc.cpu().numpy(), out.cpu().numpy(), y.cpu().numpy()
-    worst = 0.0
+    worst, direct = 0.0, 0
     for b in range(B):
         drafts, q, u = per_seq[b]
         k, r0, r1 = len(drafts), row_off[b], row_off[b + 1]
@@ -99,8 +105,25 @@ def _run_mix(cfg, mix, expect_fast, persistent=True):
             assert np.all(out[r0 + a2 + 1:r1] == -1)
             ln, pend = vf.vf_seq_get_state(seqs[b])
             assert ln == int(mix.ctx[b]) + 1 + a2 and pend == out2[-1], b
+        # directly against the oracle's own decisions, wherever these cannot flip under twice the
+        # measured logit error
+        z32 = z.astype(np.float32)
+        if mode == "greedy":
+            a_or, out_or, _ = oracle.greedy_accept(z32, drafts)
+            if accept_margin_ok(z32, drafts, "greedy", None, None, 1.0, 2 * err):
+                assert n_acc[b] == a_or and np.array_equal(out[r0:r0 + a_or + 1], out_or), (b, "direct")
+                direct += 1
+        else:
+            a_or, out_or, _ = oracle.stochastic_accept(z32, drafts, q, u, temp)
+            _, safe, draw_safe = stochastic_margins(z32, drafts, q, u, temp, 2 * np.abs(zg[r0:r1] - z).max())
+            if safe:
+                assert n_acc[b] == a_or and np.array_equal(out[r0:r0 + a_or], out_or[:a_or]), (b, "direct")
+                direct += 1
+            if draw_safe:
+                assert out[r0 + a_or] == out_or[-1], (b, "direct draw")
     print(f"mix of {B} sequences, {total} rows ({'persistent' if persistent and expect_fast else 'few-row' if expect_fast else 'general'} kernels): "
-          f"worst logit error {worst:.3e}; accepted {n_acc.tolist()} of {mix.k.tolist()}", flush=True)
+          f"worst logit error {worst:.3e}; accepted {n_acc.tolist()} of {mix.k.tolist()}; "
+          f"{direct} of {B} sequences compared directly with the oracle's decisions", flush=True)
     return pair, seqs, ctxs, pendings, per_seq, zg, row_off
 
 
@@ -123,6 +146,23 @@ def test_rag_mix_batched_paged_verify_against_oracle():
         err = rel_inf(lg.cpu().numpy(), zg[row_off[b]:row_off[b + 1]]).max()
         print(f"sequence {b}: alone + contiguous vs batched + paged: {err:.3e}", flush=True)
         assert err < 2e-2
+
+
+def test_rag_mix_full_widths_long_contexts_against_oracle():
+    """Six sequences of the real mix at their real context lengths (4416 and 3375 tokens among
+    them), full 1.5B layer widths, two layers: contexts of more than 2048 keys share their keys out
+    over several workgroups in the many-row attention, whose records a second kernel merges; here
+    that path is compared with the oracle element by element, in the prefill (K/V of the last layer,
+    last-row logits) and in the batched verify step (121 rows, mixed acceptance)."""
+    from types import SimpleNamespace
+    cfg = wl.scaled(C["1.5b_rag_mix"], n_layers=2, vocab=32768)
+    full = wl.rag_mix(cfg, wl.streams(cfg).mix)
+    pick = [5, 7, 3, 11, 0, 9]
+    mix = SimpleNamespace(ctx=full.ctx[pick], k=full.k[pick], stochastic=full.stochastic[pick],
+                          n_pages=full.n_pages, block_tables=[full.block_tables[i] for i in pick])
+    assert sorted(mix.ctx.tolist())[-2:] == [3375, 4416] and int(np.sum(mix.k + 1)) > 48
+    assert mix.stochastic.any() and not mix.stochastic.all()
+    _run_mix(cfg, mix, expect_fast=False, check_kv=True)
 
 
 def test_small_paged_batch_through_the_few_row_kernels():

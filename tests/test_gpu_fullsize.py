@@ -19,7 +19,7 @@ from oracle.loop import truncate
 import workloads as wl
 import paper_2510_15312_amd as vf
 from util_oracle import rel_inf, spec_of, weights_of
-from util_gpu import DEV, Pair, i32, f32, gpu_accept, accept_margin_ok
+from util_gpu import DEV, Pair, i32, f32, gpu_accept, accept_margin_ok, stochastic_margins
 
 pytestmark = pytest.mark.gpu
 C = wl.CONFIGS
@@ -67,7 +67,7 @@ def test_config3_full_size_stochastic_steps():
     """1.5B shape, context 2048 in 256-token chunks, successive k=16 stochastic steps with a dense
     draft distribution; every step is teacher-forced from the oracle's trajectory."""
     cfg = C["1.5b_k16"]
-    k, m, n_steps = cfg.k, cfg.k + 1, 3
+    k, m, n_steps = cfg.k, cfg.k + 1, 8
     dt = np.float32          # the accumulation precision the config fixes; see the module docstring
     s = wl.streams(cfg)
     wd = wl.make_weights(cfg, s.weights)
@@ -105,7 +105,7 @@ def test_config3_full_size_stochastic_steps():
     assert np.array_equal(vg.cpu().numpy(), cache.v[5, :, 100:108].transpose(1, 0, 2).astype(np.float32))
     u0 = wl.make_uniforms(1, s.uniforms)
     pending = oracle.first_token(z_last, cfg.temperature, u0[1])
-    worst, decisions, screened = 0.0, 0, 0
+    worst, decisions, screened, asserted = 0.0, 0, 0, 0
     pair = type("P", (), {"model": model})
     for step in range(n_steps):
         scratch = cache.clone()
@@ -124,34 +124,143 @@ def test_config3_full_size_stochastic_steps():
         tokens = i32(np.concatenate([[pending], drafts]))
         logits = torch.empty((m, cfg.vocab), dtype=torch.float32, device=DEV)
         vf.vf_seq_set_len(seq, ln)                       # teacher forcing: the oracle's state
-        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, 1)  # first through the persistent kernel (the default)
+        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, 0)  # one kernel per GEMM: logits only
         vf.vf_verify(model, [seq], tokens, [0, m], logits)
         torch.cuda.synchronize()
-        errs_p = rel_inf(logits.cpu().numpy(), z)
-        print(f"1.5b full size: step {step} persistent kernel: row errors mean {errs_p.mean():.3e} max {errs_p.max():.3e}",
-              flush=True)
-        worst = max(worst, errs_p.max())
-        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, 0)  # then one kernel per GEMM; acceptance runs on these logits
+        errs_c = rel_inf(logits.cpu().numpy(), z)
+        worst = max(worst, errs_c.max())
+        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, 1)  # the persistent kernel (the default): acceptance runs on these logits
         vf.vf_verify(model, [seq], tokens, [0, m], logits)
         torch.cuda.synchronize()
         zg = logits.cpu().numpy()
         errs = rel_inf(zg, z)
         err = errs.max()
         worst = max(worst, err)
-        print(f"1.5b full size: step {step} row errors mean {errs.mean():.3e} max {err:.3e}", flush=True)
+        print(f"1.5b full size: step {step}: row errors mean {errs.mean():.3e} max {err:.3e} "
+              f"(one kernel per GEMM: mean {errs_c.mean():.3e} max {errs_c.max():.3e})", flush=True)
         params = [(vf.VF_STOCHASTIC, cfg.temperature, f32(q), f32(u))]
         n_acc, out_t, y = gpu_accept(pair, [seq], tokens, [0, m], params)
         a2, out2, y2 = oracle.stochastic_accept(zg, drafts, q, u, cfg.temperature)
         assert np.array_equal(y, y2)
         if accept_margin_ok(zg, drafts, "stochastic", q, u, cfg.temperature, 1e-9):
             assert n_acc[0] == a2 and np.array_equal(out_t[:a2 + 1], out2)
+        # directly against the oracle's trajectory: where no decision of the oracle can flip under
+        # twice the measured logit error, counts and accepted ids must be the oracle's
+        _, safe, draw_safe = stochastic_margins(z, drafts, q, u, cfg.temperature, 2 * np.abs(zg - z).max())
         decisions += 1
+        if safe:
+            assert n_acc[0] == a_or and np.array_equal(out_t[:a_or], out_or[:a_or]), (step, n_acc[0], a_or)
+            asserted += 1
+        if draw_safe:
+            assert out_t[a_or] == out_or[-1], step
         if n_acc[0] != a_or:
-            screened += 1                                # inside the logit-error margin
-        print(f"1.5b full size: step {step} verify error {err:.3e}, oracle accepted {a_or}, gpu {n_acc[0]}", flush=True)
+            screened += 1                                # only possible inside the margin (asserted above)
+        print(f"1.5b full size: step {step}: oracle accepted {a_or}, gpu {n_acc[0]}; decisions safe: {safe}", flush=True)
         pending = int(out_or[-1])
-    print(f"1.5b full size: worst logit error {worst:.3e}; steps {decisions}, differing accept counts {screened}", flush=True)
+    print(f"1.5b full size: worst logit error {worst:.3e}; steps {decisions}, compared directly {asserted}, "
+          f"differing accept counts inside the margin {screened}", flush=True)
     assert worst < 2e-2
+    assert asserted >= 1
+
+
+def test_config3_widths_depth6_error_against_both_oracle_precisions():
+    """What the 28-layer comparison cannot tell apart from noise, measured where noise does not
+    dominate: full 1.5B widths and vocabulary, context 2048 in 256-token chunks, 6 layers, 17 verify
+    rows, prefill and verify together (no cache import).  The oracle in float64 is the truth; the
+    oracle accumulating in float32 is what exact arithmetic at the precision the config fixes
+    ("fp32 accumulate") gives.  The GPU's error against the truth may not exceed the float32
+    oracle's own error by more than a quarter (row mean; half for the worst row)."""
+    cfg = wl.scaled(C["1.5b_k16"], n_layers=6)
+    k, m = cfg.k, cfg.k + 1
+    s = wl.streams(cfg)
+    wd = wl.make_weights(cfg, s.weights)
+    spec = spec_of(cfg)
+    ctx = wl.make_context(cfg.vocab, cfg.ctx, s.context)
+    drafts = wl.copy_span_drafts(ctx, k, 1.0, cfg.vocab, s.drafts)
+    z_last, z_ver = {}, {}
+    for dt in (np.float64, np.float32):
+        ow = weights_of(wd, dt)
+        cache = oracle.KVCache(spec, cfg.ctx + m, dt)
+        z_last[dt] = oracle.prefill(spec, ow, cache, ctx, cfg.chunk, dt)
+        if dt is np.float64:
+            pending = oracle.first_token(z_last[dt])
+        z_ver[dt] = oracle.verify(spec, ow, cache, pending, drafts, dt)
+        del ow, cache
+        print(f"depth 6: oracle in {np.dtype(dt).name} done", flush=True)
+    model = vf.vf_model_create(vf.config_from(cfg, cfg.chunk, cfg.ctx + 2 * m), vf.upload_weights(wd, cfg.dtype, DEV), DEV)
+    del wd
+    seq = vf.vf_seq_create(model, cfg.ctx + 2 * m)
+    toks = i32(ctx)
+    out = torch.empty(cfg.vocab, dtype=torch.float32, device=DEV)
+    for c0 in range(0, cfg.ctx, cfg.chunk):
+        last = c0 + cfg.chunk >= cfg.ctx
+        vf.vf_prefill_chunk(model, seq, toks[c0:c0 + cfg.chunk], logits_mode=1 if last else 0,
+                            logits_out=out if last else None)
+    tokens = i32(np.concatenate([[pending], drafts]))
+    logits = torch.empty((m, cfg.vocab), dtype=torch.float32, device=DEV)
+    ref32 = rel_inf(z_ver[np.float32], z_ver[np.float64])
+    ref32_last = rel_inf(z_last[np.float32][None], z_last[np.float64][None]).max()
+    e_last = rel_inf(out.cpu().numpy()[None], z_last[np.float64][None]).max()
+    print(f"depth 6: last prefill row: gpu {e_last:.3e}, float32 oracle {ref32_last:.3e}", flush=True)
+    assert e_last < 2e-2
+    for persistent in (1, 0):
+        vf.vf_set_option(model, vf.VF_OPT_PERSISTENT, persistent)
+        vf.vf_verify(model, [seq], tokens, [0, m], logits)
+        torch.cuda.synchronize()
+        e = rel_inf(logits.cpu().numpy(), z_ver[np.float64])
+        print(f"depth 6: verify rows ({'persistent kernel' if persistent else 'one kernel per GEMM'}): gpu mean {e.mean():.3e} "
+              f"max {e.max():.3e}; float32 oracle mean {ref32.mean():.3e} max {ref32.max():.3e}", flush=True)
+        assert e.max() < 2e-2
+        assert e.mean() <= 1.25 * ref32.mean(), (e.mean(), ref32.mean())
+        assert e.max() <= 1.5 * ref32.max(), (e.max(), ref32.max())
+
+
+def test_config4_widths_against_oracle():
+    """3B widths (d 3072, 24/8 heads, ffn 8192), the full 128256 vocabulary, context 4096 in
+    256-token chunks, 33 verify rows, two layers, against the oracle element by element: the
+    persistent kernel here stages its activations in K slices and shares the keys of a block out
+    over several workgroups, and the prefill attention merges key parts with its second kernel."""
+    cfg = wl.scaled(C["3b_k32"], n_layers=2)
+    k, m = cfg.k, cfg.k + 1
+    pair = Pair(cfg, max_rows=cfg.chunk, max_positions=cfg.ctx + 2 * m)
+    s = pair.s
+    ctx = wl.make_context(cfg.vocab, cfg.ctx, s.context)
+    cache, seq = oracle.KVCache(pair.spec, cfg.ctx + m), pair.new_seq(cfg.ctx + 2 * m)
+    z_or, z_gpu = pair.prefill_both(seq, cache, ctx, cfg.chunk)
+    err = rel_inf(z_gpu[None], z_or[None]).max()
+    (kg, vg), (ko, vo) = pair.kv_both(seq, cache, cfg.n_layers - 1, 0, cfg.ctx)
+    ek, ev = np.abs(kg - ko).max() / np.abs(ko).max(), np.abs(vg - vo).max() / np.abs(vo).max()
+    print(f"3b widths: prefill last-row error {err:.3e}, last-layer K {ek:.2e}, V {ev:.2e}", flush=True)
+    assert err < 2e-2 and ek <= 1e-2 and ev <= 1e-2
+    pending = oracle.first_token(z_or)
+    cont = oracle.loop.plain_greedy(pair.spec, pair.ow, cache.clone(), pending, k)
+    drafts = wl.inject_mismatch(cont, 23, cfg.vocab, s.drafts)
+    z = oracle.verify(pair.spec, pair.ow, cache, pending, drafts)
+    tokens = i32(np.concatenate([[pending], drafts]))
+    logits = torch.empty((m, cfg.vocab), dtype=torch.float32, device=DEV)
+    a_or, out_or, y_or = oracle.greedy_accept(z.astype(np.float32), drafts)
+    greedy = [(vf.VF_GREEDY, 0.0, None, None)]
+    for name, fast, persistent in (("persistent kernel", 1, 1), ("one kernel per GEMM", 1, 0), ("general kernels", 0, 1)):
+        vf.vf_set_option(pair.model, vf.VF_OPT_FAST_PATH, fast)
+        vf.vf_set_option(pair.model, vf.VF_OPT_PERSISTENT, persistent)
+        vf.vf_seq_set_len(seq, cfg.ctx)
+        vf.vf_verify(pair.model, [seq], tokens, [0, m], logits)
+        torch.cuda.synchronize()
+        zg = logits.cpu().numpy()
+        errs = rel_inf(zg, z)
+        print(f"3b widths: 33 verify rows, {name}: error mean {errs.mean():.3e} max {errs.max():.3e}", flush=True)
+        assert np.isfinite(zg).all() and errs.max() < 2e-2
+        (kg, vg), (ko, vo) = pair.kv_both(seq, cache, cfg.n_layers - 1, cfg.ctx, m)
+        assert np.abs(kg - ko).max() <= 2e-2 * np.abs(ko).max() and np.abs(vg - vo).max() <= 2e-2 * np.abs(vo).max()
+        n_acc, out, y = gpu_accept(pair, [seq], tokens, [0, m], greedy)
+        a2, out2, y2 = oracle.greedy_accept(zg, drafts)
+        assert np.array_equal(y, y2) and n_acc[0] == a2 and np.array_equal(out[:a2 + 1], out2)
+        if accept_margin_ok(z.astype(np.float32), drafts, "greedy", None, None, 1.0, 2 * errs.max()):
+            assert n_acc[0] == a_or and np.array_equal(out[:a_or + 1], out_or)
+            print(f"3b widths: {name}: direct match with the oracle, accepted {a_or} of {k}", flush=True)
+    vf.vf_set_option(pair.model, vf.VF_OPT_FAST_PATH, 1)
+    vf.vf_set_option(pair.model, vf.VF_OPT_PERSISTENT, 1)
+    vf.vf_seq_get_state(seq)                             # would report a grid barrier that gave up
 
 
 def test_config4_full_size_properties():

@@ -13,7 +13,7 @@ from oracle.loop import plain_greedy, truncate
 import workloads as wl
 import paper_2510_15312_amd as vf
 from util_oracle import rel_inf
-from util_gpu import DEV, Pair, tol_of, i32, f32, gpu_accept, accept_margin_ok
+from util_gpu import DEV, Pair, tol_of, i32, f32, gpu_accept, accept_margin_ok, stochastic_margins
 
 pytestmark = pytest.mark.gpu
 
@@ -137,6 +137,13 @@ def test_prefill_verify_accept_against_oracle(name):
     if mode == "greedy" and accept_margin_ok(z32, drafts, mode, q, u, temp, 2 * err):
         assert n_acc[0] == a_or and np.array_equal(out[:a_or + 1], out_or)
         print(f"tier-2 direct: accepted {a_or} of {k} (mismatch injected at {e})", flush=True)
+    if mode == "stochastic":
+        _, safe, draw_safe = stochastic_margins(z32, drafts, q, u, temp, 2 * np.abs(zg - z).max())
+        if safe:
+            assert n_acc[0] == a_or and np.array_equal(out[:a_or], out_or[:a_or])
+        if draw_safe:
+            assert out[a_or] == out_or[-1]
+        print(f"tier-2 direct (stochastic): accepted {a_or} of {k}; decisions safe {safe}, draw safe {draw_safe}", flush=True)
 
 
 @pytest.mark.parametrize("persistent", [1, 0])

@@ -246,3 +246,15 @@ def test_bf16_mode_rounds_only_where_stated():
     spec32 = spec_of(wl.scaled(cfg, dtype="f32"))
     z32 = oracle.forward(spec32, w, oracle.KVCache(spec32, 16), wl.make_context(cfg.vocab, 9, wl.streams(cfg).context))
     assert rel_inf(z, z32).max() < 3e-2
+
+
+def test_logit_rows_selects_rows_of_the_full_result():
+    """forward(..., logit_rows=r) is rows r of forward(...): the head is row-wise."""
+    spec, w, _, _ = _setup(SMALL)
+    toks = [3, 9, 1, 7, 7, 2]
+    a, b = oracle.KVCache(spec, 16), oracle.KVCache(spec, 16)
+    full = oracle.forward(spec, w, a, toks)
+    some = oracle.forward(spec, w, b, toks, logit_rows=[5, 0, 2])
+    assert some.shape == (3, spec.vocab)
+    assert np.allclose(some, full[[5, 0, 2]], rtol=1e-12, atol=1e-14)
+    assert np.array_equal(a.k, b.k) and np.array_equal(a.v, b.v)

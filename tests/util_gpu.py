@@ -114,3 +114,53 @@ def gpu_accept(pair, seqs, tokens, row_off, params, logits=None):
     vf.vf_accept(pair.model, seqs, tokens, row_off, params, n_acc, out, y, logits)
     torch.cuda.synchronize()
     return n_acc.cpu().numpy(), out.cpu().numpy(), y.cpu().numpy()
+
+
+def stochastic_margins(z, drafts, q, u, temperature, abs_err):
+    """How far the oracle's stochastic decisions on logits z are from flipping, measured against a
+    perturbation of every logit by at most abs_err.
+
+    p(x) = exp((z_x - lse) / T): moving every logit by at most abs_err moves log p(x) by at most
+    2 * abs_err / T (z_x one way, the normaliser the other), so p(x) changes by a factor within
+    exp(+-2 abs_err / T).  A draft's decision u q(x) < p(x) cannot flip if u q(x) lies outside
+    [p e^-c, p e^c], c = 2 abs_err / T.  The replacement / bonus draw is safe if u' * total stays
+    inside the chosen id's CDF step when every weight changes by that factor (taken as a shift of
+    at most (e^c - 1) * total of either edge).
+
+    Returns (n_accept, accept_safe, draw_safe)."""
+    z = np.asarray(z, dtype=np.float32).astype(np.float64)
+    k = len(drafts)
+    t = np.float64(np.float32(temperature))
+    c = 2.0 * abs_err / t
+    a, out, _ = oracle.stochastic_accept(z, drafts, q, u, temperature)
+    accept_safe = True
+    for i in range(min(a + 1, k)):
+        e = np.exp((z[i] - z[i].max()) / t)
+        p = e / e.sum()
+        x = int(drafts[i])
+        qx = 1.0 if q is None else float(q[i][x])
+        uq = float(u[i]) * qx
+        if p[x] * np.exp(-c) <= uq <= p[x] * np.exp(c):
+            accept_safe = False
+    i = a
+    e = np.exp((z[i] - z[i].max()) / t)
+    p = e / e.sum()
+    if i < k:
+        if q is None:
+            r = p.copy()
+            r[int(drafts[i])] = 0.0
+        else:
+            r = np.maximum(p - np.asarray(q[i], dtype=np.float64), 0.0)
+        if r.sum() == 0.0:
+            r = p
+    else:
+        r = p
+    cdf = np.cumsum(r)
+    tgt = float(u[k + 1 + i]) * cdf[-1]
+    w = int(out[-1])
+    lo = cdf[w - 1] if w > 0 else 0.0
+    shift = np.expm1(c) * cdf[-1]
+    draw_safe = bool(accept_safe and (cdf[w] - tgt) > shift and (tgt - lo) > shift)
+    if q is not None and i < k:
+        draw_safe = False      # a residual max(0, p - q) can change by more than the factor e^c near p = q
+    return a, accept_safe, draw_safe
