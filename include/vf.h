@@ -217,6 +217,23 @@ int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *token
               const float *logits_dev, int32_t *n_accept_dev, int32_t *out_tokens_dev,
               int32_t *y_dev, void *stream);
 
+/* vf_accept for callers that must not allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results,
+ * same state commit as vf_accept; the only difference is where the kernels keep their
+ * intermediate results (per-chunk row statistics, draw descriptors, per-chunk draw sums): in
+ * about 0.53 MB of device memory that is part of the loaded library itself (one copy per GPU,
+ * held until the process ends) instead of the model workspace.  The call allocates nothing and
+ * frees nothing, on the device or through any library.
+ *   - total rows (row_off[n_seqs]) must not exceed VF_ACCEPT_STATIC_MAX_ROWS: VF_ERR_CAP.
+ *   - every call on one GPU uses the same scratch, whichever model or stream it is given:
+ *     calls that overlap in time on one GPU race; issue them on one stream or order them.
+ *   - nothing in the scratch needs to start at zero; a call overwrites what it reads. */
+#define VF_ACCEPT_STATIC_MAX_ROWS 512
+int vf_accept_static(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+                     const int32_t *row_off_host, const vf_accept_params *params_host,
+                     const float *logits_dev, int32_t *n_accept_dev, int32_t *out_tokens_dev,
+                     int32_t *y_dev, void *stream);
+
 /* ---- top successors of every prefill position (next to the three operations) ---------------- */
 
 /* vf_prefill_chunk that also returns, for EVERY row of the chunk, the top_k largest next-token

@@ -19,6 +19,7 @@ VF_GREEDY, VF_STOCHASTIC = 0, 1
 VF_PENDING = -1
 VF_MAX_BATCH, VF_MAX_DRAFTS = 32, 32
 VF_TOPK_MAX = 8
+VF_ACCEPT_STATIC_MAX_ROWS = 512
 VF_OPT_FAST_PATH = 1
 VF_OPT_PERSISTENT = 2
 
@@ -26,7 +27,7 @@ EXPORTS = [
     "vf_last_error", "vf_model_packed_bytes", "vf_model_create", "vf_model_destroy",
     "vf_seq_state_bytes", "vf_kv_bytes", "vf_seq_create", "vf_seq_destroy", "vf_seq_set_len",
     "vf_seq_set_pending", "vf_seq_get_state", "vf_seq_note_len", "vf_kv_read", "vf_kv_write", "vf_prefill_chunk", "vf_verify",
-    "vf_accept", "vf_profile", "vf_profile_read", "vf_set_option", "vf_stream_read",
+    "vf_accept", "vf_accept_static", "vf_profile", "vf_profile_read", "vf_set_option", "vf_stream_read",
     "vf_reuse_select", "vf_reuse_pool_init", "vf_reuse_pool_update", "vf_reuse_pool_extend",
     "vf_verify_tree", "vf_accept_tree", "vf_prefill_chunk_topk", "vf_draft_suffix_match",
 ]
@@ -90,6 +91,8 @@ def _load():
         "vf_verify": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), vp, vp]),
         "vf_accept": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(vf_accept_params),
                                 vp, vp, vp, vp, vp]),
+        "vf_accept_static": (C.c_int, [vp, C.POINTER(vp), C.c_int, vp, C.POINTER(i32), C.POINTER(vf_accept_params),
+                                       vp, vp, vp, vp, vp]),
         "vf_set_option": (C.c_int, [vp, C.c_int, C.c_int]),
         "vf_profile": (C.c_int, [vp, C.c_int]),
         "vf_stream_read": (C.c_int, [vp, C.POINTER(sz), vp]),
@@ -269,6 +272,17 @@ def vf_accept(model, seqs, tokens, row_off, params, n_accept, out_tokens, y, log
                                  u.data_ptr() if u is not None else None)
     _check(lib.vf_accept(model.handle, hs, len(seqs), _ptr(tokens), ro, ps, _ptr(logits), _ptr(n_accept),
                          _ptr(out_tokens), _ptr(y), _stream()))
+
+
+def vf_accept_static(model, seqs, tokens, row_off, params, n_accept, out_tokens, y, logits=None):
+    """vf_accept with the library's static device scratch; arguments as vf_accept."""
+    hs, ro = _batch(seqs, row_off)
+    ps = (vf_accept_params * len(seqs))()
+    for i, (mode, temp, q, u) in enumerate(params):
+        ps[i] = vf_accept_params(mode, temp, q.data_ptr() if q is not None else None,
+                                 u.data_ptr() if u is not None else None)
+    _check(lib.vf_accept_static(model.handle, hs, len(seqs), _ptr(tokens), ro, ps, _ptr(logits), _ptr(n_accept),
+                                _ptr(out_tokens), _ptr(y), _stream()))
 
 
 def vf_prefill_chunk_topk(model, seq, tokens, top_k, topk_logit, topk_id, sample_first=False, u=None,

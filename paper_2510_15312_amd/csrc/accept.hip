@@ -14,6 +14,55 @@
 
 namespace {
 
+// Where the kernels below keep what they hand to one another: per (row, vocabulary chunk) statistics,
+// one draw descriptor per sequence, and the per-chunk weight sums of the draw.
+struct AcceptScratch {
+    float *smax;        // [rows, VF_STAT_CHUNKS]
+    int32_t *sidx;      // [rows, VF_STAT_CHUNKS]
+    double *ssum;       // [rows, VF_STAT_CHUNKS]
+    DrawDesc *draw;     // [VF_MAX_BATCH]
+    double *draw_sums;  // [VF_MAX_BATCH, VF_STAT_CHUNKS]
+};
+
+// Scratch of vf_accept_static: the same buffers for up to VF_ACCEPT_STATIC_MAX_ROWS rows, in device
+// memory that belongs to the loaded library (one copy per GPU, held until the process ends) instead of
+// the model workspace.  The name is only a host-side handle: the device address is asked for once per
+// device (static_scratch) and that pointer is what the launches get.
+constexpr size_t SS_SMAX = 0;
+constexpr size_t SS_SIDX = SS_SMAX + (size_t)VF_ACCEPT_STATIC_MAX_ROWS * VF_STAT_CHUNKS * 4;
+constexpr size_t SS_SSUM = SS_SIDX + (size_t)VF_ACCEPT_STATIC_MAX_ROWS * VF_STAT_CHUNKS * 4;
+constexpr size_t SS_DRAW = SS_SSUM + (size_t)VF_ACCEPT_STATIC_MAX_ROWS * VF_STAT_CHUNKS * 8;
+constexpr size_t SS_DSUM = (SS_DRAW + sizeof(DrawDesc) * VF_MAX_BATCH + 255) / 256 * 256;
+constexpr size_t SS_BYTES = SS_DSUM + (size_t)VF_MAX_BATCH * VF_STAT_CHUNKS * 8;
+static __device__ __align__(256) unsigned char scratch[SS_BYTES];
+
+constexpr int SS_MAX_DEVICES = 64;
+unsigned char *g_scratch_ptr[SS_MAX_DEVICES];  // device address of `scratch` on every GPU seen so far
+
+// Device address of the static scratch on the current device; resolved on the first call per device.
+int static_scratch(AcceptScratch *out) {
+    int dev = 0;
+    VF_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= SS_MAX_DEVICES) return vf_fail(VF_ERR_UNSUPPORTED, "device ordinal %d", dev);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        VF_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return vf_fail(VF_ERR_HIP, "hipGetSymbolAddress returned no address");
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    unsigned char *base = g_scratch_ptr[dev];
+    out->smax = reinterpret_cast<float *>(base + SS_SMAX);
+    out->sidx = reinterpret_cast<int32_t *>(base + SS_SIDX);
+    out->ssum = reinterpret_cast<double *>(base + SS_SSUM);
+    out->draw = reinterpret_cast<DrawDesc *>(base + SS_DRAW);
+    out->draw_sums = reinterpret_cast<double *>(base + SS_DSUM);
+    return VF_OK;
+}
+
+AcceptScratch model_scratch(const vf_model *m) {
+    return AcceptScratch{m->stat_max, m->stat_idx, m->stat_sum, m->draw, m->draw_sums};
+}
+
 struct MaxIdx {
     float v;
     int i;
@@ -360,24 +409,24 @@ __global__ __launch_bounds__(256) void accept_emit_kernel(const float *__restric
     }
 }
 
-int launch_all(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
-               const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y, int commit_len,
-               hipStream_t st) {
+int launch_all(const vf_model *m, const AcceptScratch &sc, const Batch &b, const AcceptBatch &ab,
+               const int32_t *tokens, const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y,
+               int commit_len, hipStream_t st) {
     const int V = m->cfg.vocab;
     hipLaunchKernelGGL(row_stats_kernel, dim3(VF_STAT_CHUNKS, b.total_rows), dim3(256), 0, st, logits, V, b, ab,
-                       m->stat_max, m->stat_idx, m->stat_sum);
+                       sc.smax, sc.sidx, sc.ssum);
     VF_LAUNCH_CHECK("row_stats");
     hipLaunchKernelGGL(accept_decide_kernel, dim3(b.n_seqs), dim3(256), 0, st, logits, V, b, ab, tokens,
-                       m->stat_max, m->stat_idx, m->stat_sum, n_accept, out_tokens, y, m->draw, commit_len);
+                       sc.smax, sc.sidx, sc.ssum, n_accept, out_tokens, y, sc.draw, commit_len);
     VF_LAUNCH_CHECK("accept_decide");
     bool any = false;
     for (int i = 0; i < b.n_seqs; ++i) any = any || ab.a[i].mode == VF_STOCHASTIC;
     if (!any) return VF_OK;
-    hipLaunchKernelGGL(draw_sums_kernel, dim3(VF_STAT_CHUNKS, b.n_seqs), dim3(256), 0, st, logits, V, m->draw,
-                       m->draw_sums);
+    hipLaunchKernelGGL(draw_sums_kernel, dim3(VF_STAT_CHUNKS, b.n_seqs), dim3(256), 0, st, logits, V, sc.draw,
+                       sc.draw_sums);
     VF_LAUNCH_CHECK("draw_sums");
-    hipLaunchKernelGGL(accept_emit_kernel, dim3(b.n_seqs), dim3(256), 0, st, logits, V, b, m->draw,
-                       m->draw_sums, out_tokens, commit_len);
+    hipLaunchKernelGGL(accept_emit_kernel, dim3(b.n_seqs), dim3(256), 0, st, logits, V, b, sc.draw,
+                       sc.draw_sums, out_tokens, commit_len);
     VF_LAUNCH_CHECK("accept_emit");
     return VF_OK;
 }
@@ -386,7 +435,26 @@ int launch_all(const vf_model *m, const Batch &b, const AcceptBatch &ab, const i
 
 int vf_launch_accept(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
                      const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y, hipStream_t st) {
-    return launch_all(m, b, ab, tokens, logits, n_accept, out_tokens, y, 1, st);
+    return launch_all(m, model_scratch(m), b, ab, tokens, logits, n_accept, out_tokens, y, 1, st);
+}
+
+// The same kernels with the library's static device scratch instead of the model workspace.
+int vf_launch_accept_static(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
+                            const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y,
+                            hipStream_t st) {
+    if (b.total_rows > VF_ACCEPT_STATIC_MAX_ROWS)
+        return vf_fail(VF_ERR_CAP, "vf_accept_static: %d rows exceed the static scratch (%d rows)", b.total_rows,
+                       VF_ACCEPT_STATIC_MAX_ROWS);
+    AcceptScratch sc;
+    const int rc = static_scratch(&sc);
+    if (rc) return rc;
+    return launch_all(m, sc, b, ab, tokens, logits, n_accept, out_tokens, y, 1, st);
+}
+
+// Resolves the static scratch of the current device ahead of the first vf_accept_static (set-up time).
+int vf_accept_static_init() {
+    AcceptScratch sc;
+    return static_scratch(&sc);
 }
 
 int vf_launch_accept_tree(const vf_model *m, const Batch &b, const AcceptBatch &ab, const TreeDesc &tree,
@@ -428,6 +496,6 @@ int vf_launch_first_token(const vf_model *m, const SeqDesc &s, const float *logi
     ab.a[0].temperature = temperature > 0.f ? temperature : 1.f;
     ab.a[0].mode = temperature > 0.f ? VF_STOCHASTIC : VF_GREEDY;
     if (u) ab.a[0].u = u - 1;  // the draw reads u[1]; the caller's single uniform sits at u[0]
-    int32_t *scratch = m->scratch_i32;
-    return launch_all(m, b, ab, scratch + 8, logits_row, scratch, scratch + 16, scratch + 24, 0, st);
+    int32_t *ws = m->scratch_i32;
+    return launch_all(m, model_scratch(m), b, ab, ws + 8, logits_row, ws, ws + 16, ws + 24, 0, st);
 }

@@ -264,6 +264,7 @@ int vf_model_create(const vf_config *cfg, const vf_weights *w, void *packed_dev,
     // activation buffers start at zero so that padding rows of a 16-row block are finite
     TRYHIP(hipMemsetAsync(m->h, 0, (size_t)((char *)m->base + m->bytes - (char *)m->h), st));
     if (c.dtype == VF_BF16) TRY(vf_fused_init(m, m->fz_ws, st));
+    TRY(vf_accept_static_init());  // device address of the static acceptance scratch on this GPU
 #undef TRY
 #undef TRYHIP
     *out = m;
@@ -566,7 +567,7 @@ int vf_verify_tree(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *
 }
 
 static int accept_impl(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
-                       const int32_t *row_off_host, const int32_t *parent_host, bool tree,
+                       const int32_t *row_off_host, const int32_t *parent_host, bool tree, bool static_scratch,
                        const vf_accept_params *params_host, const float *logits_dev, int32_t *n_accept_dev,
                        int32_t *out_tokens_dev, int32_t *y_dev, int32_t *path_dev, void *stream, const char *who) {
     Batch b;
@@ -604,6 +605,10 @@ static int accept_impl(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32
                                             path_dev, (hipStream_t)stream)))
                 return rc;
             if ((rc = vf_launch_kv_compact(m, b, n_accept_dev, path_dev, (hipStream_t)stream))) return rc;
+        } else if (static_scratch) {
+            if ((rc = vf_launch_accept_static(m, b, ab, tokens_dev, logits, n_accept_dev, out_tokens_dev, y_dev,
+                                              (hipStream_t)stream)))
+                return rc;
         } else if ((rc = vf_launch_accept(m, b, ab, tokens_dev, logits, n_accept_dev, out_tokens_dev, y_dev,
                                           (hipStream_t)stream))) {
             return rc;
@@ -616,15 +621,22 @@ static int accept_impl(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32
 int vf_accept(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
               const int32_t *row_off_host, const vf_accept_params *params_host, const float *logits_dev,
               int32_t *n_accept_dev, int32_t *out_tokens_dev, int32_t *y_dev, void *stream) {
-    return accept_impl(m, seqs, n_seqs, tokens_dev, row_off_host, nullptr, false, params_host, logits_dev,
+    return accept_impl(m, seqs, n_seqs, tokens_dev, row_off_host, nullptr, false, false, params_host, logits_dev,
                        n_accept_dev, out_tokens_dev, y_dev, nullptr, stream, "vf_accept");
+}
+
+int vf_accept_static(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
+                     const int32_t *row_off_host, const vf_accept_params *params_host, const float *logits_dev,
+                     int32_t *n_accept_dev, int32_t *out_tokens_dev, int32_t *y_dev, void *stream) {
+    return accept_impl(m, seqs, n_seqs, tokens_dev, row_off_host, nullptr, false, true, params_host, logits_dev,
+                       n_accept_dev, out_tokens_dev, y_dev, nullptr, stream, "vf_accept_static");
 }
 
 int vf_accept_tree(vf_model *m, vf_seq *const *seqs, int n_seqs, const int32_t *tokens_dev,
                    const int32_t *row_off_host, const int32_t *parent_host, const vf_accept_params *params_host,
                    const float *logits_dev, int32_t *n_accept_dev, int32_t *out_tokens_dev, int32_t *y_dev,
                    int32_t *path_dev, void *stream) {
-    return accept_impl(m, seqs, n_seqs, tokens_dev, row_off_host, parent_host, true, params_host, logits_dev,
+    return accept_impl(m, seqs, n_seqs, tokens_dev, row_off_host, parent_host, true, false, params_host, logits_dev,
                        n_accept_dev, out_tokens_dev, y_dev, path_dev, stream, "vf_accept_tree");
 }
 

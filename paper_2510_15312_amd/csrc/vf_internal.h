@@ -269,6 +269,10 @@ int vf_launch_kv_write(const vf_model *m, const SeqDesc &s, int layer, int t0, i
 int vf_launch_accept(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
                      const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y,
                      hipStream_t st);
+int vf_launch_accept_static(const vf_model *m, const Batch &b, const AcceptBatch &ab, const int32_t *tokens,
+                            const float *logits, int32_t *n_accept, int32_t *out_tokens, int32_t *y,
+                            hipStream_t st);
+int vf_accept_static_init();
 int vf_launch_attention_rows(const vf_model *m, const Batch &b, int layer, hipStream_t st);
 bool vf_fast_path_ok(const vf_model *m, int total_rows);
 int vf_run_fast(vf_model *m, const Batch &b, const int32_t *tokens, float *logits_out, hipStream_t st);
