@@ -113,6 +113,7 @@ struct FusedArgs {
     float inv_d, eps, scale_log2e;
     unsigned root0;   // value of the barrier's root counter when this launch starts
     int ks_qkv, ks_o, ks_gu, ks_down, ks_head;
+    int wave_gu, wave_head;  // gate/up, output head: one weight block per wavefront (K unsplit and the staged rows fit)
     int lds_total;    // dynamic LDS bytes of this launch
 };
 
@@ -126,9 +127,17 @@ struct GridBar {
     unsigned *mem, *fail;
     unsigned target, per;  // per: workgroups per counter
     bool dead;
+#ifdef FUSED_ARRIVALS
+    unsigned long long *stamps;  // [barrier][2][workgroup]: clock at the arrival and at the end of the wait
+    int n_arr, n_wait;
+#endif
     __device__ __forceinline__ void arrive() {
         stores_done();  // this wavefront's write-through stores have reached memory
         __syncthreads();
+#ifdef FUSED_ARRIVALS
+        if (threadIdx.x == 0) stamps[((size_t)n_arr * 2) * gridDim.x + blockIdx.x] = wall_clock64();
+        ++n_arr;
+#endif
         target += per;
         if (threadIdx.x == 0)
             __hip_atomic_fetch_add(mem + (blockIdx.x % BAR_COUNTERS) * 64, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -152,6 +161,10 @@ struct GridBar {
             }
         }
         lds_sync();
+#ifdef FUSED_ARRIVALS
+        if (threadIdx.x == 0) stamps[((size_t)n_wait * 2 + 1) * gridDim.x + blockIdx.x] = wall_clock64();
+        ++n_wait;
+#endif
     }
 };
 
@@ -727,6 +740,248 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
     }
 }
 
+// ---- GEMM phase with whole weight blocks per wavefront ---------------------------------------------------
+// For the matrices with many more 16-row blocks than a K split across workgroups could use (gate/up,
+// output head) and a K that fits LDS whole.  A wavefront streams its share of a block's fragments
+// through a ring of RING registers and keeps the accumulators to itself: no partial sums in LDS
+// per work item, no workgroup barrier inside the streaming loop.  Every wavefront of the chip holds
+// RING fragments in flight, issued before the barrier wait; what limits a compute unit's share of
+// the stream is the bytes it has in flight, so all eight wavefronts of a workgroup carry a ring.
+//   gate/up: a pass covers two units of the workgroup (unit = 16 ffn columns: a block of gate rows
+//            and a block of up rows); its eight tasks (unit, gate | up, lower | upper half of K) go
+//            to the eight wavefronts.  At the end of a pass the four tiles of a unit meet in LDS;
+//            wavefront q of the unit adds the halves of row block q and applies SwiGLU.
+//   head:    blocks w, w + W, ... (W = wavefronts of the grid) per wavefront, full K, one after
+//            the other through the same ring; logits are stored from the accumulators.
+#ifndef FUSED_WRING
+#define FUSED_WRING 24
+#endif
+#ifndef FUSED_ATT_TOP
+#define FUSED_ATT_TOP 1         // attention items go to the workgroups at the top of the grid
+#endif
+#ifndef FUSED_GU_REV
+#define FUSED_GU_REV 1          // gate/up: the units of a partial last range go to the workgroups at the top of the grid
+#endif
+#ifndef FUSED_WXP
+#define FUSED_WXP 8             // activation staging of these phases: loads in flight per thread (the ring is live meanwhile)
+#endif
+#ifndef FUSED_WAVE_PHASES
+#define FUSED_WAVE_PHASES 1     // 1: gate/up and the output head run this way when K is not split across workgroups
+#endif
+constexpr int WAVE_TAIL_BYTES = 24 * 1024;  // LDS kept free behind the staged activations: the gain vector (up to
+                                            // 6144 columns) while staging, then the tiles of a pass (FW * NB KB)
+template <int NB, int EPI>
+__device__ __forceinline__ void wave_phase(const FastGemm &g, GridBar &bar, unsigned char *smem, int lds_total,
+                                           FusedShared &sh TRACE_ARG) {
+    static_assert(EPI == EPI_SWIGLU || EPI == EPI_LOGITS, "gate/up and output head");
+    static_assert(FW * NB * 1024 <= WAVE_TAIL_BYTES && NB <= 4, "a pass's tiles fit the tail; one row block per wavefront of a unit");
+    constexpr int RING = FUSED_WRING, XP = FUSED_WXP;
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int G = gridDim.x, wg = blockIdx.x;
+    const int m = g.m, KB = g.KB, NBt = g.N >> 4;
+    u32x4 *xs = reinterpret_cast<u32x4 *>(smem);
+    floatx4 *exch = reinterpret_cast<floatx4 *>(smem + lds_total - WAVE_TAIL_BYTES);
+    float *gain_s = reinterpret_cast<float *>(smem + lds_total - WAVE_TAIL_BYTES);  // staging only
+
+    // this wavefront's tasks: block of task j = blk0 + j * bstride, all over the K range [kb_lo, kb_hi)
+    // (gate/up: pass j, slot s covers units (2j + s) G .. + G; a range that the units fill only in part is
+    //  handed out from the top workgroup downwards: the workgroups at the bottom of the grid are the ones
+    //  busy in the O projection before, and the last to start here)
+    int blk0, bstride, n_task, kb_lo, kb_hi, passes, blk_last = -1;
+    if (EPI == EPI_SWIGLU) {
+        const int n_units = NBt >> 1, slot = wave >> 2, KBh = (KB + 1) >> 1;
+        const int sub = (wave >> 1) & 1;
+        blk0 = 2 * (wg + slot * G) + sub;
+        bstride = 4 * G;
+        passes = max(1, (n_units + 2 * G - 1) / (2 * G));
+        n_task = 0;
+        for (int j = 0; j < passes; ++j) {
+            const int start = (2 * j + slot) * G, left = n_units - start;
+            if (left >= G) ++n_task;
+            else if (left > 0) {
+                const int idx = FUSED_GU_REV ? G - 1 - wg : wg;
+                if (idx < left) { blk_last = 2 * (start + idx) + sub; ++n_task; }
+            }
+        }
+        kb_lo = (wave & 1) ? KBh : 0;
+        kb_hi = (wave & 1) ? KB : KBh;
+    } else {
+        const int gw = wave * G + wg, W = FW * G;          // neighbouring blocks on different compute units
+        blk0 = gw;
+        bstride = W;
+        n_task = gw < NBt ? (NBt - gw + W - 1) / W : 0;
+        kb_lo = 0;
+        kb_hi = KB;
+        passes = n_task;
+    }
+    const int rpt = max(1, (kb_hi - kb_lo + RING - 1) / RING);  // rounds per task
+    const int rounds = n_task * rpt;
+    global_w_ptr wbase = (global_w_ptr)g.W + lane;
+    u32x4 w[RING];
+#pragma unroll
+    for (int d = 0; d < RING; ++d) w[d] = u32x4{0u, 0u, 0u, 0u};
+    // fragment of flat round r, slot d.  Never predicated: a step past the end of the K range (or of
+    // the wavefront's tasks) reads a valid fragment again and its product is discarded.
+    auto task_block = [&](int j) { return (j == n_task - 1 && blk_last >= 0) ? blk_last : blk0 + j * bstride; };
+    auto frag = [&](int r, int d) {
+        const int j = min(r / rpt, max(n_task - 1, 0));
+        const int kb = min(kb_lo + (r % rpt) * RING + d, kb_hi - 1);
+        const size_t blk = (size_t)min(task_block(j), NBt - 1);
+        return __builtin_nontemporal_load(wbase + (blk * KB + kb) * 64);
+    };
+    if (n_task > 0) {
+#pragma unroll
+        for (int d = 0; d < RING; ++d) w[d] = frag(0, d);
+    }
+    TRACE(1);
+    bar.wait();
+    TRACE(2);
+
+    // ---- stage x = bf16(h * rstd * gain) for the whole K (as in gemm_phase, one slice) ----
+    {
+        const int nk = KB, chunks = nk * 8, pieces = m * chunks;
+        const int qstep = FT / chunks, rstep = FT % chunks;
+        float t[16];
+        const unsigned ss_lane = (unsigned)min(lane, m - 1);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int j = wave + i * FW;
+            t[i] = ssa_load_f1(g.ss_in + min(j, g.n_ss - 1) * 64 + ss_lane) * (j < g.n_ss ? 1.f : 0.f);
+        }
+        floatx4 gn = load_global_f4(g.gain + min(tid, chunks - 1) * 4);
+        for (int base = 0; base < pieces; base += FT * XP) {
+            floatx4 v[XP];
+            int row = (base + tid) / chunks, c = (base + tid) % chunks;
+            const int row0 = row, c0 = c;
+#pragma unroll
+            for (int i = 0; i < XP; ++i) {
+                v[i] = ssa_load_f4(g.Xh + (unsigned)(min(row, m - 1) * KB * 32 + c * 4));
+                row += qstep;
+                c += rstep;
+                if (c >= chunks) { c -= chunks; ++row; }
+            }
+            if (base == 0) {
+                float sum = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum += t[i];
+                if (lane < m)
+                    for (int j = wave + 16 * FW; j < g.n_ss; j += FW) sum += ssa_load_f1(g.ss_in + j * 64 + lane);
+                sh.rs_tmp[wave][lane] = sum;
+                for (int cc = tid; cc < chunks; cc += FT) {
+                    if (cc != tid) gn = load_global_f4(g.gain + cc * 4);
+                    *reinterpret_cast<floatx4 *>(gain_s + cc * 4) = gn;
+                }
+                lds_sync();
+                TRACE(6);
+                if (tid < 64) {
+                    float part[FW], tot = 0.f;
+#pragma unroll
+                    for (int j = 0; j < FW; ++j) part[j] = sh.rs_tmp[j][tid];
+                    asm volatile("" ::: "memory");
+#pragma unroll
+                    for (int j = 0; j < FW; ++j) tot += part[j];
+                    sh.rs_s[tid] = 1.0f / sqrtf(tot * g.inv_d + g.eps);
+                }
+                lds_sync();
+                TRACE(7);
+            }
+            scale_and_stage<XP>(v, sh.rs_s, gain_s, reinterpret_cast<u32x2 *>(xs), row0, c0, qstep, rstep, chunks, m);
+        }
+    }
+    lds_sync();
+    TRACE(3);
+
+    int xoff[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) xoff[c] = min(c * 16 + (lane & 15), m - 1) * 4 + (lane >> 4);
+
+    floatx4 acc[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // one round = RING steps of straight-line code; REFILL: every slot is loaded again after its
+    // use with the fragment of the next round (the same task's next K range or the next task)
+    auto round_body = [&](auto refill_tag, int r) {
+        constexpr bool REFILL = decltype(refill_tag)::value;
+        const int kbase = kb_lo + (r % rpt) * RING;
+        constexpr int BA = FUSED_BB_AHEAD < RING ? FUSED_BB_AHEAD : RING - 1;
+        bf16x8 bb[BA + 1][NB];
+        auto read_bb = [&](int d) {
+            const int kx = min(kbase + d, kb_hi - 1);
+#pragma unroll
+            for (int c = 0; c < NB; ++c) bb[d % (BA + 1)][c] = __builtin_bit_cast(bf16x8, xs[kx * m * 4 + xoff[c]]);
+        };
+#pragma unroll
+        for (int d = 0; d < BA; ++d) read_bb(d);
+#pragma unroll
+        for (int d = 0; d < RING; ++d) {
+            const bool live = kbase + d < kb_hi;
+            const bf16x8 a = __builtin_bit_cast(bf16x8, live ? w[d] : u32x4{0u, 0u, 0u, 0u});
+            if (REFILL) w[d] = frag(r + 1, d);
+            if (d + BA < RING) read_bb(d + BA);
+#pragma unroll
+            for (int c = 0; c < NB; ++c)
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bb[d % (BA + 1)][c], acc[c], 0, 0, 0);
+        }
+        if (FUSED_SGB > 0) {
+            constexpr int SA = FUSED_SGB < RING ? FUSED_SGB : RING;
+            __builtin_amdgcn_sched_group_barrier(0x100, SA * NB, 0);
+#pragma unroll
+            for (int d = 0; d < RING; ++d) {
+                __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
+                if (d + SA < RING) __builtin_amdgcn_sched_group_barrier(0x100, NB, 0);
+            }
+        }
+    };
+
+#pragma unroll 1
+    for (int j = 0; j < passes; ++j) {
+        const bool mine = j < n_task;
+        if (mine) {
+#pragma unroll 1
+            for (int rr = 0; rr < rpt; ++rr) {
+                const int r = j * rpt + rr;
+                if (r + 1 < rounds) round_body(std::true_type{}, r);
+                else round_body(std::false_type{}, r);
+            }
+        }
+        TRACE(4);
+        const int nb = task_block(j);
+        if (EPI == EPI_LOGITS) {
+#pragma unroll
+            for (int c = 0; c < NB; ++c) {
+                const int row = c * 16 + (lane & 15);
+                if (row < m)
+                    __builtin_nontemporal_store(acc[c], reinterpret_cast<floatx4 *>(g.logits + (size_t)row * g.N + nb * 16 + (lane >> 4) * 4));
+                acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+            }
+        } else {
+            // tile (wavefront w, row block c) at exch[(w * NB + c) * 64 + lane]; wavefronts 4u .. 4u + 3 hold
+            // unit u's gate lower, gate upper, up lower, up upper half
+            if (j) lds_sync();   // the previous pass's tiles have been read
+            if (mine) {
+#pragma unroll
+                for (int c = 0; c < NB; ++c) exch[(wave * NB + c) * 64 + lane] = acc[c];
+            }
+            lds_sync();
+            const int q = wave & 3, w0 = wave & ~3;
+            if (mine && q < NB) {
+                floatx4 t4[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t4[i] = exch[((w0 + i) * NB + q) * 64 + lane];
+                asm volatile("" ::: "memory");
+                const int row = q * 16 + (lane & 15);
+                if (row < m) epi_swiglu<true>(g, row, nb & ~1, lane, t4[0] + t4[1], t4[2] + t4[3]);
+            }
+#pragma unroll
+            for (int c = 0; c < NB; ++c) acc[c] = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+        TRACE(5);
+    }
+}
+
 // ---- attention phase -----------------------------------------------------------------------------------
 // Work item = (block of 16 query items, kv head, sequence, part of the keys); a query item is a
 // (row, head of the group) pair.  The eight wavefronts of a workgroup take the 32-key tiles of the
@@ -959,7 +1214,13 @@ template <int NB, int HD>
 __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs a, Batch b) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ FusedShared sh;
+#ifdef FUSED_ARRIVALS
+    // debug build: stamps go behind the first 64 rows of the logits buffer (the model workspace's, when the caller passes none)
+    GridBar bar{a.bar, a.fail, a.root0, gridDim.x / BAR_COUNTERS, false,
+                reinterpret_cast<unsigned long long *>(a.logits + (size_t)64 * a.vocab), 0, 0};
+#else
     GridBar bar{a.bar, a.fail, a.root0, gridDim.x / BAR_COUNTERS, false};
+#endif
     const int d = a.d, F = a.F, hd = a.hd, nq = a.hq * hd, nkv = a.hkv * hd;
     const size_t hstride = (size_t)FROWS * d, sstride = (size_t)(d / 16) * 64;
 
@@ -1036,7 +1297,8 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
             FastGemm g = base;
             g.W = lp.wgu; g.N = 2 * F; g.KB = d / 32; g.Xh = h1; g.gain = lp.ffn_norm; g.ss_in = ss1; g.a_out = act;
             g.ks = a.ks_gu; g.kbps = (g.KB + g.ks - 1) / g.ks;
-            gemm_phase<NB, 2, 6, EPI_SWIGLU>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+            if (a.wave_gu) wave_phase<NB, EPI_SWIGLU>(g, bar, smem, a.lds_total, sh TRACE_PASS);
+            else gemm_phase<NB, 2, 6, EPI_SWIGLU>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
         }
         bar.arrive();
         TRACE(15);
@@ -1055,9 +1317,13 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
         g.Xh = a.hv + (size_t)(2 * a.n_layers) * hstride; g.gain = a.final_norm;
         g.ss_in = a.ssv + (size_t)(2 * a.n_layers) * sstride; g.logits = a.logits;
         g.ks = a.ks_head; g.kbps = (g.KB + g.ks - 1) / g.ks;
-        gemm_phase<NB, 2, 6, EPI_LOGITS>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
+        if (a.wave_head) wave_phase<NB, EPI_LOGITS>(g, bar, smem, a.lds_total, sh TRACE_PASS);
+        else gemm_phase<NB, 2, 6, EPI_LOGITS>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
     }
     TRACE(99);
+#ifdef FUSED_ARRIVALS
+    if (threadIdx.x == 0) bar.stamps[((size_t)bar.n_arr * 2) * gridDim.x + blockIdx.x] = wall_clock64();  // end of the head phase
+#endif
 }
 
 // ---- host side -------------------------------------------------------------------------------------
@@ -1267,8 +1533,11 @@ int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logi
         const int n_work = blocks * parts;
         for (int w = 0; w < FUSED_G; ++w) a.att_first[w] = (short)(w < n_work && n_work > G ? w : -1);
         if (n_work <= G) {
+            // from the top of the grid downwards: the QKV phase before it keeps the lowest workgroups busy
+            // (one item each), and a workgroup that is idle there has worked out its attention item and
+            // requested its first key tile by the time the others arrive
             int next[8], die = 0;
-            for (int x = 0; x < 8; ++x) next[x] = x;
+            for (int x = 0; x < 8; ++x) next[x] = FUSED_ATT_TOP ? G - 8 + x : x;
             int blk0 = 0;
             for (int sq = 0; sq < b.n_seqs; ++sq) {
                 const int nqb = (b.s[sq].nrows * group + 15) / 16;
@@ -1276,9 +1545,9 @@ int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logi
                     for (int p = 0; p < parts; ++p) {
                         for (int qb = 0; qb < nqb; ++qb) {
                             int x = die;
-                            for (int tries = 0; tries < 8 && next[x] >= G; ++tries) x = (x + 1) % 8;  // that die is full
+                            for (int tries = 0; tries < 8 && (next[x] >= G || next[x] < 0); ++tries) x = (x + 1) % 8;  // that die is full
                             a.att_first[next[x]] = (short)(p * blocks + blk0 + kvh * nqb + qb);
-                            next[x] += 8;
+                            next[x] += FUSED_ATT_TOP ? -8 : 8;
                         }
                         die = (die + 1) % 8;
                     }
@@ -1293,6 +1562,12 @@ int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logi
     a.root0 = m->fz_epoch;
     m->fz_epoch += (1u + 5u * (unsigned)c.n_layers) * (unsigned)(G / BAR_COUNTERS);  // barriers per launch x arrivals per counter
     const int rows = b.total_rows;
+    {
+        const bool fits = FUSED_WAVE_PHASES && (size_t)(c.d_model / 32) * rows * 64 + WAVE_TAIL_BYTES <= (size_t)LDS_BYTES &&
+                          (size_t)c.d_model * 4 <= (size_t)WAVE_TAIL_BYTES;
+        a.wave_gu = fits && a.ks_gu == 1;
+        a.wave_head = fits && a.ks_head == 1;
+    }
     ProfScope ps(m, VF_SITE_STEP, st);
     if (c.head_dim == 128) {
         if (rows <= 16) return launch_fused<1, 128>(m, a, b, G, st);
@@ -1318,6 +1593,15 @@ int vf_fused_check(vf_model *m) {
     }
     return VF_OK;
 }
+
+#ifdef FUSED_ARRIVALS
+// Copies the arrival / release stamps of the last launch (logits left in the model workspace): [barrier][2][workgroup].
+extern "C" int vf_debug_arrivals(vf_model *m, unsigned long long *out_host, int n_barriers) {
+    VF_HIP(hipDeviceSynchronize());
+    VF_HIP(hipMemcpy(out_host, m->logits + (size_t)64 * m->cfg.vocab, (size_t)n_barriers * 2 * FUSED_G * 8, hipMemcpyDeviceToHost));
+    return VF_OK;
+}
+#endif
 
 #ifdef FUSED_TRACE
 // Copies the phase timeline of the traced workgroup's last launch: pairs (clock, mark id).
