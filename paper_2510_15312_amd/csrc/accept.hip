@@ -2,14 +2,21 @@
 // the accepted prefix x_1..x_{e-1} followed by y_e), greedy and stochastic, and the commit of the
 // sequence state (length, pending token) without a host round trip.
 //
-//   row_stats : per (row, vocabulary chunk): maximum logit, its lowest index and, for stochastic
-//               rows, sum exp((z - chunk max)/T) in float64.
-//   decide    : one workgroup per sequence merges the chunks in a fixed order (arg-max y of every
-//               row, softmax normaliser), walks the drafts and fixes the accepted count a.  Greedy
-//               sequences are finished here.
-//   draw_sums : stochastic only: per vocabulary chunk the float64 sum of the weights the
-//               replacement (or bonus) token is drawn from at row a.
-//   emit      : inverse CDF in id order: finds the chunk, then the id inside it; commits the state.
+//   row statistics : per (row, vocabulary chunk): maximum logit, its lowest index and, for stochastic
+//                    rows, sum exp((z - chunk max)/T) in float64.
+//   decide         : per sequence the chunks are merged in a fixed order (arg-max y of every row,
+//                    softmax normaliser), the drafts are walked and the accepted count a is fixed.
+//                    Greedy sequences are finished here.
+//   draw sums      : stochastic only: per vocabulary chunk the float64 sum of the weights the
+//                    replacement (or bonus) token is drawn from at row a.
+//   emit           : inverse CDF in id order: finds the chunk, then the id inside it; commits the state.
+// Four short launches in stream order.  Each is a chain of a few dependent trips to memory, so inside
+// a kernel everything a thread needs is requested together and kept in registers (the logits of a
+// chunk for both passes over them, the weights of the chosen chunk, the drafts' logits and draft
+// probabilities ahead of the statistics they are compared with).  Merging them into two launches, the
+// workgroup that completes a sequence running the second half, measured slower (52 against 44 us
+// per step before this was written): the counter that elects that workgroup costs more trips than
+// the kernel boundary it replaces.
 #include "vf_internal.h"
 
 namespace {
@@ -63,6 +70,35 @@ AcceptScratch model_scratch(const vf_model *m) {
     return AcceptScratch{m->stat_max, m->stat_idx, m->stat_sum, m->draw, m->draw_sums};
 }
 
+// exp(x) in float64 for x <= 0 (every use here is exp((z - row maximum) / T)), within one unit in the
+// last place of the library routine (checked on the host over 2e7 arguments): x = k ln 2 + r with
+// |r| <= ln 2 / 2 (ln 2 in two parts, so r is exact to the last bit), exp(r) by its Taylor polynomial of
+// degree 13 (truncation below 4e-18), scaled by 2^k.  About twenty float64 operations; the library
+// routine, which also serves arguments this code never has, takes several times as many, and these
+// kernels spend their time in it.
+__device__ inline double exp_nonpos(double x) {
+    if (!(x > -745.2)) return 0.0;  // below the smallest subnormal
+    const double kf = rint(x * 1.4426950408889634);
+    const double r = fma(kf, -1.90821492927058770002e-10, fma(kf, -6.93147180369123816490e-01, x));
+    double p = 1.0 / 6227020800.0;
+    p = fma(p, r, 1.0 / 479001600.0);
+    p = fma(p, r, 1.0 / 39916800.0);
+    p = fma(p, r, 1.0 / 3628800.0);
+    p = fma(p, r, 1.0 / 362880.0);
+    p = fma(p, r, 1.0 / 40320.0);
+    p = fma(p, r, 1.0 / 5040.0);
+    p = fma(p, r, 1.0 / 720.0);
+    p = fma(p, r, 1.0 / 120.0);
+    p = fma(p, r, 1.0 / 24.0);
+    p = fma(p, r, 1.0 / 6.0);
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(p, (int)kf);
+}
+
+constexpr int ACC_EL = 16;  // logits a thread holds at a time
+
 struct MaxIdx {
     float v;
     int i;
@@ -83,17 +119,35 @@ __device__ inline double wave_sum(double s) {
     return s;
 }
 
-__global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict__ logits, int V, Batch b,
-                                                        AcceptBatch ab, float *__restrict__ smax,
-                                                        int32_t *__restrict__ sidx, double *__restrict__ ssum) {
+// Statistics of one (row, vocabulary chunk) by one workgroup of 256 threads.
+__device__ inline void row_stats_body(const float *__restrict__ logits, int V, const Batch &b, const AcceptBatch &ab,
+                                      int row, int chunk, float *__restrict__ smax, int32_t *__restrict__ sidx,
+                                      double *__restrict__ ssum) {
     __shared__ MaxIdx rm[4];
     __shared__ double rs[4];
-    const int row = blockIdx.y, chunk = blockIdx.x;
     const int per = (V + VF_STAT_CHUNKS - 1) / VF_STAT_CHUNKS;
     const int v0 = min(V, chunk * per), v1 = min(V, v0 + per);
     const float *z = logits + (size_t)row * V;
+    // A thread's logits (ids v0 + thread, + 256, ...) are requested together and kept in registers
+    // for the second pass: one trip to memory instead of one per element.  Chunks too long for that
+    // (vocabularies beyond 64 * 256 * ACC_EL ids) take the plain loops.
+    const bool held = v1 - v0 <= 256 * ACC_EL;
+    float zz[ACC_EL];
     MaxIdx best{-INFINITY, 0x7fffffff};
-    for (int v = v0 + threadIdx.x; v < v1; v += 256) best = better(best, MaxIdx{z[v], v});
+    if (held) {
+#pragma unroll
+        for (int i = 0; i < ACC_EL; ++i) {
+            const int v = v0 + (int)threadIdx.x + i * 256;
+            zz[i] = v < v1 ? z[v] : -INFINITY;
+        }
+#pragma unroll
+        for (int i = 0; i < ACC_EL; ++i) {
+            const int v = v0 + (int)threadIdx.x + i * 256;
+            if (v < v1) best = better(best, MaxIdx{zz[i], v});
+        }
+    } else {
+        for (int v = v0 + threadIdx.x; v < v1; v += 256) best = better(best, MaxIdx{z[v], v});
+    }
     best = wave_best(best);
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) rm[wave] = best;
@@ -103,7 +157,13 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict_
     double sum = 0.0;
     if (a.mode == VF_STOCHASTIC && v0 < v1) {
         const double t = (double)a.temperature, cm = (double)best.v;
-        for (int v = v0 + threadIdx.x; v < v1; v += 256) sum += exp(((double)z[v] - cm) / t);
+        if (held) {
+#pragma unroll
+            for (int i = 0; i < ACC_EL; ++i)
+                if (v0 + (int)threadIdx.x + i * 256 < v1) sum += exp_nonpos(((double)zz[i] - cm) / t);
+        } else {
+            for (int v = v0 + threadIdx.x; v < v1; v += 256) sum += exp_nonpos(((double)z[v] - cm) / t);
+        }
         sum = wave_sum(sum);
         if ((threadIdx.x & 63) == 0) rs[wave] = sum;
         __syncthreads();
@@ -117,51 +177,75 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict_
     }
 }
 
+__global__ __launch_bounds__(256) void row_stats_kernel(const float *__restrict__ logits, int V, Batch b,
+                                                        AcceptBatch ab, float *__restrict__ smax,
+                                                        int32_t *__restrict__ sidx, double *__restrict__ ssum) {
+    row_stats_body(logits, V, b, ab, blockIdx.y, blockIdx.x, smax, sidx, ssum);
+}
+
+// The acceptance decision of sequence `seq` by one workgroup of 256 threads.
 // commit_len == 0: only the pending token is written (first token after prefill).
-__global__ __launch_bounds__(256) void accept_decide_kernel(
-    const float *__restrict__ logits, int V, Batch b, AcceptBatch ab, const int32_t *__restrict__ tokens,
-    const float *__restrict__ smax, const int32_t *__restrict__ sidx, const double *__restrict__ ssum,
+struct DecideInputs {   // thread i < k: draft x_i, its logit in row i, its draft probability (1 for a one-hot drafter), uniform u_i
+    int x;
+    float zx, qx, u;
+};
+__device__ inline void decide_body(
+    const DecideInputs &di, int V, const Batch &b, const AcceptBatch &ab, int seq, const int32_t *__restrict__ tokens,
+    const float *smax, const int32_t *sidx, const double *ssum,
     int32_t *__restrict__ n_accept, int32_t *__restrict__ out_tokens, int32_t *__restrict__ y,
     DrawDesc *__restrict__ draw, int commit_len) {
     __shared__ double row_S[VF_MAX_DRAFTS + 1];
     __shared__ float row_max[VF_MAX_DRAFTS + 1];
     __shared__ int row_arg[VF_MAX_DRAFTS + 1];
     __shared__ int ok[VF_MAX_DRAFTS + 1];
-    const SeqDesc &s = b.s[blockIdx.x];
-    const AcceptDesc &a = ab.a[blockIdx.x];
+    const SeqDesc &s = b.s[seq];
+    const AcceptDesc &a = ab.a[seq];
     const int m = s.nrows, k = m - 1;
     const double t = (double)a.temperature;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int r = wave; r < m; r += 4) {
-        const size_t o = (size_t)(s.row0 + r) * VF_STAT_CHUNKS + lane;  // one chunk per lane
-        const MaxIdx mine{smax[o], sidx[o]};
-        const MaxIdx best = wave_best(mine);
-        double S = 0.0;
-        if (a.mode == VF_STOCHASTIC) {
-            const double sm = ssum[o];
-            S = wave_sum(sm != 0.0 ? sm * exp(((double)mine.v - (double)best.v) / t) : 0.0);
-        }
-        if (lane == 0) {
-            row_S[r] = S;
-            row_max[r] = best.v;
-            row_arg[r] = best.i;
-            y[s.row0 + r] = best.i;
+    // rows wave, wave + 4, ... per wavefront, one chunk per lane; the statistics of all of a
+    // wavefront's rows are requested before the first is used
+    constexpr int RPW = (VF_MAX_DRAFTS + 1 + 3) / 4;
+    float mv[RPW];
+    int mi[RPW];
+    double ms[RPW];
+#pragma unroll
+    for (int j = 0; j < RPW; ++j) {
+        const int r = min(wave + 4 * j, m - 1);
+        const size_t o = (size_t)(s.row0 + r) * VF_STAT_CHUNKS + lane;
+        mv[j] = smax[o];
+        mi[j] = sidx[o];
+        ms[j] = a.mode == VF_STOCHASTIC ? ssum[o] : 0.0;
+    }
+#pragma unroll
+    for (int j = 0; j < RPW; ++j) {
+        const int r = wave + 4 * j;
+        if (r < m) {
+            const MaxIdx mine{mv[j], mi[j]};
+            const MaxIdx best = wave_best(mine);
+            double S = 0.0;
+            if (a.mode == VF_STOCHASTIC)
+                S = wave_sum(ms[j] != 0.0 ? ms[j] * exp_nonpos(((double)mine.v - (double)best.v) / t) : 0.0);
+            if (lane == 0) {
+                row_S[r] = S;
+                row_max[r] = best.v;
+                row_arg[r] = best.i;
+                y[s.row0 + r] = best.i;
+            }
         }
     }
     __syncthreads();
     const int32_t *drafts = tokens + s.row0 + 1;
     if ((int)threadIdx.x < k) {
-        const int i = threadIdx.x, x = drafts[i];
+        const int i = threadIdx.x, x = di.x;
         int good;
         if (a.mode == VF_GREEDY) {
             good = x == row_arg[i];
         } else if (x < 0 || x >= V) {
             good = 0;
         } else {
-            const float *z = logits + (size_t)(s.row0 + i) * V;
-            const double px = exp(((double)z[x] - (double)row_max[i]) / t) / row_S[i];
-            const double qx = a.q ? (double)a.q[(size_t)i * V + x] : 1.0;
-            good = (double)a.u[i] * qx < px;
+            const double px = exp_nonpos(((double)di.zx - (double)row_max[i]) / t) / row_S[i];
+            good = (double)di.u * (double)di.qx < px;
         }
         ok[i] = good;
     }
@@ -175,7 +259,7 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
         out_tokens[s.row0 + threadIdx.x] = v;
     }
     if (threadIdx.x == 0) {
-        n_accept[blockIdx.x] = acc;
+        n_accept[seq] = acc;
         DrawDesc d;
         d.zmax = (double)row_max[acc];
         d.S = row_S[acc];
@@ -187,12 +271,41 @@ __global__ __launch_bounds__(256) void accept_decide_kernel(
         d.n_excl = 0;
         d.u = d.active ? (double)a.u[m + acc] : 0.0;
         d.t = t;
-        draw[blockIdx.x] = d;
+        draw[seq] = d;
         if (a.mode == VF_GREEDY) {
             if (commit_len) s.state[0] += 1 + acc;
             s.state[1] = row_arg[acc];
         }
     }
+}
+
+// One workgroup per sequence.
+__global__ __launch_bounds__(256) void accept_decide_kernel(
+    const float *__restrict__ logits, int V, Batch b, AcceptBatch ab, const int32_t *__restrict__ tokens,
+    const float *__restrict__ smax, const int32_t *__restrict__ sidx, const double *__restrict__ ssum,
+    int32_t *__restrict__ n_accept, int32_t *__restrict__ out_tokens, int32_t *__restrict__ y,
+    DrawDesc *__restrict__ draw, int commit_len) {
+    const int seq = blockIdx.x;
+    // a draft, its logit, its draft probability and its uniform per thread: requested before the statistics
+    DecideInputs di;
+    {
+        const SeqDesc &sq = b.s[seq];
+        const AcceptDesc &aq = ab.a[seq];
+        const int k = sq.nrows - 1, i = threadIdx.x;
+        di.x = -1;
+        di.zx = 0.f;
+        di.qx = 1.f;
+        di.u = 0.f;
+        if (i < k) {
+            di.x = tokens[sq.row0 + 1 + i];
+            if (aq.mode == VF_STOCHASTIC && di.x >= 0 && di.x < V) {
+                di.zx = logits[(size_t)(sq.row0 + i) * V + di.x];
+                if (aq.q) di.qx = aq.q[(size_t)i * V + di.x];
+                di.u = aq.u[i];
+            }
+        }
+    }
+    decide_body(di, V, b, ab, seq, tokens, smax, sidx, ssum, n_accept, out_tokens, y, draw, commit_len);
 }
 
 // Tree-structured drafts: the same row statistics, then one thread walks down from the root.
@@ -225,7 +338,7 @@ __global__ __launch_bounds__(256) void accept_tree_decide_kernel(
         double S = 0.0;
         if (a.mode == VF_STOCHASTIC) {
             const double sm = ssum[o];
-            S = wave_sum(sm != 0.0 ? sm * exp(((double)mine.v - (double)best.v) / t) : 0.0);
+            S = wave_sum(sm != 0.0 ? sm * exp_nonpos(((double)mine.v - (double)best.v) / t) : 0.0);
         }
         if (lane == 0) {
             row_S[r] = S;
@@ -240,7 +353,7 @@ __global__ __launch_bounds__(256) void accept_tree_decide_kernel(
         double v = 0.0;
         const int x = tokens[s.row0 + c], pr = par[c];
         if (a.mode == VF_STOCHASTIC && x >= 0 && x < V)
-            v = exp(((double)logits[(size_t)(s.row0 + pr) * V + x] - (double)row_max[pr]) / t) / row_S[pr];
+            v = exp_nonpos(((double)logits[(size_t)(s.row0 + pr) * V + x] - (double)row_max[pr]) / t) / row_S[pr];
         px[c] = v;
     }
     __syncthreads();
@@ -300,20 +413,46 @@ __global__ __launch_bounds__(256) void accept_tree_decide_kernel(
 //   max(0, p_v - q_v)  (dense draft distribution),  p_v with p_x = 0  (one-hot drafter; for a tree
 //   every refused child's token x),
 //   p_v  (bonus token / first token / every residual weight zero),  p_v = exp((z_v - zmax)/T) / S.
-__device__ inline double draw_weight(const float *__restrict__ z, const DrawDesc &d, int v, bool plain) {
-    const double p = exp(((double)z[v] - d.zmax) / d.t) / d.S;
+struct DrawParams {       // the scalars of a DrawDesc, read once
+    double zmax, S, t;
+    const float *q;
+    const int32_t *excl;  // the descriptor's exclusion list (left in memory: it is indexed at run time)
+    int x_excl, n_excl;
+};
+__device__ inline DrawParams draw_params(const DrawDesc &d) {
+    return DrawParams{d.zmax, d.S, d.t, d.q, d.excl, d.x_excl, d.n_excl};
+}
+// zv: logit of id v; qv: q[v] when there is a dense draft distribution
+__device__ inline double draw_weight(float zv, float qv, const DrawParams &d, int v, bool plain) {
+    const double p = exp_nonpos(((double)zv - d.zmax) / d.t) / d.S;
     if (plain) return p;
-    if (d.q) return fmax(p - (double)d.q[v], 0.0);
+    if (d.q) return fmax(p - (double)qv, 0.0);
     if (v == d.x_excl) return 0.0;
     for (int i = 0; i < d.n_excl; ++i)
         if (v == d.excl[i]) return 0.0;
     return p;
 }
 
-__device__ inline double chunk_weight_sum(const float *__restrict__ z, const DrawDesc &d, int v0, int v1,
+__device__ inline double chunk_weight_sum(const float *__restrict__ z, const DrawParams &d, int v0, int v1,
                                           bool plain, double *rs) {
     double sum = 0.0;
-    for (int v = v0 + threadIdx.x; v < v1; v += 256) sum += draw_weight(z, d, v, plain);
+    const bool use_q = d.q && !plain;
+    if (v1 - v0 <= 256 * ACC_EL) {
+        float zz[ACC_EL], qq[ACC_EL];
+#pragma unroll
+        for (int i = 0; i < ACC_EL; ++i) {
+            const int v = v0 + (int)threadIdx.x + i * 256;
+            zz[i] = v < v1 ? z[v] : 0.f;
+            qq[i] = (use_q && v < v1) ? d.q[v] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < ACC_EL; ++i) {
+            const int v = v0 + (int)threadIdx.x + i * 256;
+            if (v < v1) sum += draw_weight(zz[i], qq[i], d, v, plain);
+        }
+    } else {
+        for (int v = v0 + threadIdx.x; v < v1; v += 256) sum += draw_weight(z[v], use_q ? d.q[v] : 0.f, d, v, plain);
+    }
     sum = wave_sum(sum);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) rs[threadIdx.x >> 6] = sum;
@@ -321,32 +460,21 @@ __device__ inline double chunk_weight_sum(const float *__restrict__ z, const Dra
     return ((rs[0] + rs[1]) + rs[2]) + rs[3];
 }
 
-__global__ __launch_bounds__(256) void draw_sums_kernel(const float *__restrict__ logits, int V,
-                                                        const DrawDesc *__restrict__ draw,
-                                                        double *__restrict__ wsum) {
-    __shared__ double rs[4];
-    const DrawDesc &d = draw[blockIdx.y];
-    if (!d.active) return;
-    const int per = (V + VF_STAT_CHUNKS - 1) / VF_STAT_CHUNKS;
-    const int v0 = min(V, (int)blockIdx.x * per), v1 = min(V, v0 + per);
-    const double sum = chunk_weight_sum(logits + (size_t)d.row * V, d, v0, v1, false, rs);
-    if (threadIdx.x == 0) wsum[blockIdx.y * VF_STAT_CHUNKS + blockIdx.x] = sum;
-}
-
-__global__ __launch_bounds__(256) void accept_emit_kernel(const float *__restrict__ logits, int V, Batch b,
-                                                          const DrawDesc *__restrict__ draw,
-                                                          const double *__restrict__ wsum,
-                                                          int32_t *__restrict__ out_tokens, int commit_len) {
+// The draw of sequence `seq` by one workgroup of 256 threads, from the per-chunk weight sums.
+__device__ inline void emit_body(const float *__restrict__ logits, int V, const Batch &b, int seq,
+                                 const DrawDesc *draw, const double *wsum,
+                                 int32_t *__restrict__ out_tokens, int commit_len) {
     __shared__ double cs[VF_STAT_CHUNKS];
     __shared__ double seg[256];
     __shared__ double rs[4];
     __shared__ int result;
-    const DrawDesc &d = draw[blockIdx.x];
-    if (!d.active) return;
-    const SeqDesc &s = b.s[blockIdx.x];
-    const float *z = logits + (size_t)d.row * V;
+    const DrawParams d = draw_params(draw[seq]);
+    const int d_row = draw[seq].row, d_acc = draw[seq].acc;
+    const double d_u = draw[seq].u;
+    const SeqDesc &s = b.s[seq];
+    const float *z = logits + (size_t)d_row * V;
     const int per = (V + VF_STAT_CHUNKS - 1) / VF_STAT_CHUNKS;
-    if (threadIdx.x < VF_STAT_CHUNKS) cs[threadIdx.x] = wsum[blockIdx.x * VF_STAT_CHUNKS + threadIdx.x];
+    if (threadIdx.x < VF_STAT_CHUNKS) cs[threadIdx.x] = wsum[seq * VF_STAT_CHUNKS + threadIdx.x];
     __syncthreads();
     double total = 0.0;
     for (int c = 0; c < VF_STAT_CHUNKS; ++c) total += cs[c];
@@ -363,7 +491,7 @@ __global__ __launch_bounds__(256) void accept_emit_kernel(const float *__restric
         total = 0.0;
         for (int c = 0; c < VF_STAT_CHUNKS; ++c) total += cs[c];
     }
-    const double target = d.u * total;
+    const double target = d_u * total;
     // first chunk whose inclusive prefix exceeds the target
     int cstar = VF_STAT_CHUNKS - 1;
     double before_chunk = 0.0;
@@ -375,11 +503,29 @@ __global__ __launch_bounds__(256) void accept_emit_kernel(const float *__restric
             if (c == VF_STAT_CHUNKS - 1) before_chunk = run - cs[c];
         }
     }
+    // the chosen chunk, a run of per_t consecutive ids per thread; a thread's weights are worked out
+    // once (values requested together) and kept for the second pass
     const int v0 = min(V, cstar * per), v1 = min(V, v0 + per);
     const int per_t = (v1 - v0 + 255) / 256;
     const int a0 = min(v1, v0 + (int)threadIdx.x * per_t), a1 = min(v1, a0 + per_t);
+    const bool held = per_t <= ACC_EL, use_q = d.q && !plain;
+    double wt[ACC_EL];
     double local = 0.0;
-    for (int v = a0; v < a1; ++v) local += draw_weight(z, d, v, plain);
+    if (held) {
+        float zz[ACC_EL], qq[ACC_EL];
+#pragma unroll
+        for (int i = 0; i < ACC_EL; ++i) {
+            zz[i] = a0 + i < a1 ? z[a0 + i] : 0.f;
+            qq[i] = (use_q && a0 + i < a1) ? d.q[a0 + i] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < ACC_EL; ++i) {
+            wt[i] = a0 + i < a1 ? draw_weight(zz[i], qq[i], d, a0 + i, plain) : 0.0;
+            if (a0 + i < a1) local += wt[i];
+        }
+    } else {
+        for (int v = a0; v < a1; ++v) local += draw_weight(z[v], use_q ? d.q[v] : 0.f, d, v, plain);
+    }
     seg[threadIdx.x] = local;
     if (threadIdx.x == 0) result = 0x7fffffff;
     __syncthreads();
@@ -387,9 +533,20 @@ __global__ __launch_bounds__(256) void accept_emit_kernel(const float *__restric
     for (int j = 0; j < (int)threadIdx.x; ++j) before += seg[j];
     if (before <= target) {
         double run = before;
-        for (int v = a0; v < a1; ++v) {
-            run += draw_weight(z, d, v, plain);
-            if (run > target) { atomicMin(&result, v); break; }
+        if (held) {
+            bool found = false;
+#pragma unroll
+            for (int i = 0; i < ACC_EL; ++i) {
+                if (!found && a0 + i < a1) {
+                    run += wt[i];
+                    if (run > target) { atomicMin(&result, a0 + i); found = true; }
+                }
+            }
+        } else {
+            for (int v = a0; v < a1; ++v) {
+                run += draw_weight(z[v], use_q ? d.q[v] : 0.f, d, v, plain);
+                if (run > target) { atomicMin(&result, v); break; }
+            }
         }
     }
     __syncthreads();
@@ -400,13 +557,34 @@ __global__ __launch_bounds__(256) void accept_emit_kernel(const float *__restric
             // at or before the end of the chosen chunk (never an id the rule gives no weight)
             w = -1;
             for (int v = v1 - 1; v >= 0 && w < 0; --v)
-                if (draw_weight(z, d, v, plain) > 0.0) w = v;
+                if (draw_weight(z[v], use_q ? d.q[v] : 0.f, d, v, plain) > 0.0) w = v;
             if (w < 0) w = max(v0, v1 - 1);
         }
-        out_tokens[s.row0 + d.acc] = w;
-        if (commit_len) s.state[0] += 1 + d.acc;
+        out_tokens[s.row0 + d_acc] = w;
+        if (commit_len) s.state[0] += 1 + d_acc;
         s.state[1] = w;
     }
+}
+
+__global__ __launch_bounds__(256) void draw_sums_kernel(const float *__restrict__ logits, int V,
+                                                        const DrawDesc *__restrict__ draw,
+                                                        double *__restrict__ wsum) {
+    __shared__ double rs[4];
+    const int seq = blockIdx.y;
+    if (!draw[seq].active) return;
+    const DrawParams d = draw_params(draw[seq]);
+    const int per = (V + VF_STAT_CHUNKS - 1) / VF_STAT_CHUNKS;
+    const int v0 = min(V, (int)blockIdx.x * per), v1 = min(V, v0 + per);
+    const double sum = chunk_weight_sum(logits + (size_t)draw[seq].row * V, d, v0, v1, false, rs);
+    if (threadIdx.x == 0) wsum[seq * VF_STAT_CHUNKS + blockIdx.x] = sum;
+}
+
+__global__ __launch_bounds__(256) void accept_emit_kernel(const float *__restrict__ logits, int V, Batch b,
+                                                          const DrawDesc *__restrict__ draw,
+                                                          const double *__restrict__ wsum,
+                                                          int32_t *__restrict__ out_tokens, int commit_len) {
+    if (!draw[blockIdx.x].active) return;
+    emit_body(logits, V, b, blockIdx.x, draw, wsum, out_tokens, commit_len);
 }
 
 int launch_all(const vf_model *m, const AcceptScratch &sc, const Batch &b, const AcceptBatch &ab,
