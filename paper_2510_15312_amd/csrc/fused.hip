@@ -113,6 +113,7 @@ struct FusedArgs {
     float inv_d, eps, scale_log2e;
     unsigned root0;   // value of the barrier's root counter when this launch starts
     int ks_qkv, ks_o, ks_gu, ks_down, ks_head;
+    int gu_light;            // gate/up: the first gu_light workgroups (busy in the O projection) take one unit each (0: even shares)
     int wave_gu, wave_head;  // gate/up, output head: one weight block per wavefront (K unsplit and the staged rows fit)
     int lds_total;    // dynamic LDS bytes of this launch
 };
@@ -759,6 +760,9 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 #ifndef FUSED_ATT_TOP
 #define FUSED_ATT_TOP 1         // attention items go to the workgroups at the top of the grid
 #endif
+#ifndef FUSED_GU_LIGHT
+#define FUSED_GU_LIGHT 1        // gate/up: workgroups busy in the O projection take one unit, the others share the rest
+#endif
 #ifndef FUSED_GU_REV
 #define FUSED_GU_REV 1          // gate/up: the units of a partial last range go to the workgroups at the top of the grid
 #endif
@@ -771,7 +775,7 @@ __device__ __forceinline__ void gemm_phase(const FastGemm &g, const Batch &b, Gr
 constexpr int WAVE_TAIL_BYTES = 24 * 1024;  // LDS kept free behind the staged activations: the gain vector (up to
                                             // 6144 columns) while staging, then the tiles of a pass (FW * NB KB)
 template <int NB, int EPI>
-__device__ __forceinline__ void wave_phase(const FastGemm &g, GridBar &bar, unsigned char *smem, int lds_total,
+__device__ __forceinline__ void wave_phase(const FastGemm &g, int n_light, GridBar &bar, unsigned char *smem, int lds_total,
                                            FusedShared &sh TRACE_ARG) {
     static_assert(EPI == EPI_SWIGLU || EPI == EPI_LOGITS, "gate/up and output head");
     static_assert(FW * NB * 1024 <= WAVE_TAIL_BYTES && NB <= 4, "a pass's tiles fit the tail; one row block per wavefront of a unit");
@@ -789,20 +793,39 @@ __device__ __forceinline__ void wave_phase(const FastGemm &g, GridBar &bar, unsi
     // (gate/up: pass j, slot s covers units (2j + s) G .. + G; a range that the units fill only in part is
     //  handed out from the top workgroup downwards: the workgroups at the bottom of the grid are the ones
     //  busy in the O projection before, and the last to start here)
+    // (With n_light > 0 the first n_light workgroups -- the ones that work in the O projection and so
+    //  start here last, their weight ring requested behind everybody else's -- take one unit each, and
+    //  the others, which have had their rings in flight since the O projection began, share the rest:
+    //  unit n_light + (wg - n_light) + t H for t = 0, 1, 2, ..., H = G - n_light.)
     int blk0, bstride, n_task, kb_lo, kb_hi, passes, blk_last = -1;
     if (EPI == EPI_SWIGLU) {
         const int n_units = NBt >> 1, slot = wave >> 2, KBh = (KB + 1) >> 1;
         const int sub = (wave >> 1) & 1;
-        blk0 = 2 * (wg + slot * G) + sub;
-        bstride = 4 * G;
-        passes = max(1, (n_units + 2 * G - 1) / (2 * G));
-        n_task = 0;
-        for (int j = 0; j < passes; ++j) {
-            const int start = (2 * j + slot) * G, left = n_units - start;
-            if (left >= G) ++n_task;
-            else if (left > 0) {
-                const int idx = FUSED_GU_REV ? G - 1 - wg : wg;
-                if (idx < left) { blk_last = 2 * (start + idx) + sub; ++n_task; }
+        if (n_light > 0) {
+            const int H = G - n_light, T = (max(n_units - n_light, 0) + H - 1) / H;
+            passes = max(1, (T + 1) / 2);
+            if (wg < n_light) {
+                blk0 = 2 * wg + sub;
+                bstride = 0;
+                n_task = (slot == 0 && wg < n_units) ? 1 : 0;
+            } else {
+                const int u0 = n_light + (wg - n_light) + slot * H;
+                blk0 = 2 * u0 + sub;
+                bstride = 4 * H;
+                n_task = u0 < n_units ? (n_units - u0 + 2 * H - 1) / (2 * H) : 0;
+            }
+        } else {
+            blk0 = 2 * (wg + slot * G) + sub;
+            bstride = 4 * G;
+            passes = max(1, (n_units + 2 * G - 1) / (2 * G));
+            n_task = 0;
+            for (int j = 0; j < passes; ++j) {
+                const int start = (2 * j + slot) * G, left = n_units - start;
+                if (left >= G) ++n_task;
+                else if (left > 0) {
+                    const int idx = FUSED_GU_REV ? G - 1 - wg : wg;
+                    if (idx < left) { blk_last = 2 * (start + idx) + sub; ++n_task; }
+                }
             }
         }
         kb_lo = (wave & 1) ? KBh : 0;
@@ -1297,7 +1320,7 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
             FastGemm g = base;
             g.W = lp.wgu; g.N = 2 * F; g.KB = d / 32; g.Xh = h1; g.gain = lp.ffn_norm; g.ss_in = ss1; g.a_out = act;
             g.ks = a.ks_gu; g.kbps = (g.KB + g.ks - 1) / g.ks;
-            if (a.wave_gu) wave_phase<NB, EPI_SWIGLU>(g, bar, smem, a.lds_total, sh TRACE_PASS);
+            if (a.wave_gu) wave_phase<NB, EPI_SWIGLU>(g, a.gu_light, bar, smem, a.lds_total, sh TRACE_PASS);
             else gemm_phase<NB, 2, 6, EPI_SWIGLU>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
         }
         bar.arrive();
@@ -1317,7 +1340,7 @@ __global__ __launch_bounds__(FT, FUSED_MINW) void verify_fused_kernel(FusedArgs 
         g.Xh = a.hv + (size_t)(2 * a.n_layers) * hstride; g.gain = a.final_norm;
         g.ss_in = a.ssv + (size_t)(2 * a.n_layers) * sstride; g.logits = a.logits;
         g.ks = a.ks_head; g.kbps = (g.KB + g.ks - 1) / g.ks;
-        if (a.wave_head) wave_phase<NB, EPI_LOGITS>(g, bar, smem, a.lds_total, sh TRACE_PASS);
+        if (a.wave_head) wave_phase<NB, EPI_LOGITS>(g, 0, bar, smem, a.lds_total, sh TRACE_PASS);
         else gemm_phase<NB, 2, 6, EPI_LOGITS>(g, b, bar, smem, a.lds_total, sh TRACE_PASS);
     }
     TRACE(99);
@@ -1566,6 +1589,12 @@ int vf_run_fused(vf_model *m, const Batch &b, const int32_t *tokens, float *logi
         const bool fits = FUSED_WAVE_PHASES && (size_t)(c.d_model / 32) * rows * 64 + WAVE_TAIL_BYTES <= (size_t)LDS_BYTES &&
                           (size_t)c.d_model * 4 <= (size_t)WAVE_TAIL_BYTES;
         a.wave_gu = fits && a.ks_gu == 1;
+        {
+            // one unit for each workgroup of the O projection, if the others can take the rest in at most
+            // three units each (two passes)
+            const int n_o = (c.d_model / 16) * a.ks_o, units = c.d_ffn / 16, H = G - n_o;
+            a.gu_light = (FUSED_GU_LIGHT && n_o > 0 && H > 0 && n_o < units && units - n_o <= 3 * H && units - n_o > H) ? n_o : 0;
+        }
         a.wave_head = fits && a.ks_head == 1;
     }
     ProfScope ps(m, VF_SITE_STEP, st);
