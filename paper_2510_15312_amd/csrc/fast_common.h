@@ -64,11 +64,21 @@ template <bool COH> __device__ inline void st_u32x2(void *p, u32x2 v) {
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     else *reinterpret_cast<u32x2 *>(p) = v;
 }
+#ifndef VF_STORE16_WT
+#define VF_STORE16_WT 1   // 16-byte write-through stores as one instruction (0: two 8-byte atomic stores)
+#endif
 template <bool COH> __device__ inline void st_f32x4(float *p, floatx4 v) {
     if (COH) {
+#if VF_STORE16_WT
+        // one 16-byte store with the agent-scope (write-through) cache policy: what the 8-byte atomic
+        // stores compile to, at twice the width.  Readers never depend on the 16 bytes arriving together.
+        typedef float __attribute__((address_space(1))) *global_f32_ptr;
+        asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"((global_f32_ptr)p), "v"(v) : "memory");
+#else
         const u32x4 r = __builtin_bit_cast(u32x4, v);
         st_u32x2<true>(p, u32x2{r[0], r[1]});
         st_u32x2<true>(p + 2, u32x2{r[2], r[3]});
+#endif
     } else {
         *reinterpret_cast<floatx4 *>(p) = v;
     }
