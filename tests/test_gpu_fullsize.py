@@ -5,10 +5,12 @@ For the 28-layer 1.5B model the oracle accumulates in float32, the precision the
 fixes ("bf16 weights/activations with fp32 accumulate"): at that depth, with random weights, the
 logit metric is dominated by chaotic amplification of bfloat16 rounding flips -- the oracle run in
 float32 and in float64 on these very inputs differs from itself by 1.4e-2 (last prefill row) and
-1.6e-2 to 1.8e-2 (the 17 verify rows), so the stated 2e-2 bar sits at the noise floor.  The 3B shape, whose
-oracle would take minutes, is checked through properties that hold at any size: a multi-row
-verify equals successive single-row decodes, and greedy acceptance of the target's own
-continuation accepts every draft.
+1.6e-2 to 1.8e-2 (the 17 verify rows), so the stated 2e-2 bar sits at the noise floor; a 6-layer
+model of the same widths measures the GPU's error against both oracle precisions where that noise
+does not dominate.  The 3B shape is checked element by element against the oracle at its full
+widths, vocabulary, context and row count with two layers, and at its full depth, where the oracle
+would take minutes, through properties that hold at any size: a multi-row verify equals successive
+single-row decodes, and greedy acceptance of the target's own continuation accepts every draft.
 """
 import numpy as np
 import pytest
