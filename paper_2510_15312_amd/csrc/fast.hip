@@ -382,11 +382,20 @@ __global__ __launch_bounds__(ROWS_WAVES * 64) void attn_rows_kernel(Batch b, int
     const int tiles = blk_last[ROWS_QB - 1] / ATT_TILE + 1;  // the last block sees the most keys
     const int tpp = (tiles + n_parts - 1) / n_parts;
     const int t_begin = kpart * tpp, t_end = min(tiles, t_begin + tpp);
+    // The pages of this part's tiles, one per lane, read once: a look-up in the block table per tile
+    // would be a second memory round trip in front of every tile's loads.
+    const int page0 = t_begin * ATT_TILE / VF_TILE;
+    int page_v = 0;
+    if (s.block_table) page_v = s.block_table[min(page0 + lane, (tiles * ATT_TILE - 1) / VF_TILE)];
     AttTile<HD> tile;
 #pragma unroll 1
     for (int t = t_begin + wave; t < t_end; t += ROWS_WAVES) {
         const int t0 = t * ATT_TILE;
-        tile.load(s, layer, hkv, kvh, t, false, lane);
+        const int pi = t0 / VF_TILE - page0;  // the same for the whole wavefront
+        const int page = !s.block_table ? t0 / VF_TILE
+                         : pi < 64      ? __builtin_amdgcn_readlane(page_v, pi)
+                                        : __builtin_amdgcn_readfirstlane(kv_page(s, t0));
+        tile.template load_page<false>(s, layer, hkv, kvh, t, page, lane);
         tile.mask_values(t0, kmax, lane);
 #pragma unroll
         for (int c = 0; c < ROWS_QB; ++c)

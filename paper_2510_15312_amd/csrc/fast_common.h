@@ -72,8 +72,11 @@ template <bool COH> __device__ inline void st_f32x4(float *p, floatx4 v) {
 #if VF_STORE16_WT
         // one 16-byte store with the agent-scope (write-through) cache policy: what the 8-byte atomic
         // stores compile to, at twice the width.  Readers never depend on the 16 bytes arriving together.
+        // A store of more than 8 bytes reads its data registers for some cycles after it has issued, and
+        // the compiler, which keeps the next instruction from overwriting them after its own stores, does
+        // not look inside this statement: the two idle cycles the hardware asks for are part of it.
         typedef float __attribute__((address_space(1))) *global_f32_ptr;
-        asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"((global_f32_ptr)p), "v"(v) : "memory");
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"((global_f32_ptr)p), "v"(v) : "memory");
 #else
         const u32x4 r = __builtin_bit_cast(u32x4, v);
         st_u32x2<true>(p, u32x2{r[0], r[1]});
@@ -390,10 +393,15 @@ template <int HD> struct AttTile {
     }
     template <bool coh>
     __device__ __forceinline__ void load_as(const SeqDesc &s, int layer, int hkv, int kvh, int t, int lane) {
+        load_page<coh>(s, layer, hkv, kvh, t, kv_page(s, t * ATT_TILE), lane);
+    }
+    // page: the cache page of tile t, for a caller that has looked it up already
+    template <bool coh>
+    __device__ __forceinline__ void load_page(const SeqDesc &s, int layer, int hkv, int kvh, int t, int page, int lane) {
         const int g4 = lane >> 4, l15 = lane & 15;
         const int krow = 8 * (l15 >> 2) + (l15 & 3);
         const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);
-        const int t0 = t * ATT_TILE, page = kv_page(s, t0), tin = t0 % VF_TILE;
+        const int t0 = t * ATT_TILE, tin = t0 % VF_TILE;
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
