@@ -338,8 +338,14 @@ __global__ __launch_bounds__(256) VF_MFMA_KERNEL void attn_fast_kernel(Batch b, 
 #endif
 constexpr int ROWS_QB = ROWS_QB_N, ROWS_WAVES = 8;
 
+#ifndef ROWS_WPE
+#define ROWS_WPE 2
+#endif
+#ifndef ROWS_PREFETCH
+#define ROWS_PREFETCH 0
+#endif
 template <int HD>
-__global__ __launch_bounds__(ROWS_WAVES * 64) void attn_rows_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
+__global__ __launch_bounds__(ROWS_WAVES * 64) __attribute__((amdgpu_waves_per_eu(ROWS_WPE, 4))) void attn_rows_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
                                                                    bf16_t *__restrict__ o, int hq, int hkv, int ncb,
                                                                    float scale_log2e, int n_parts,
                                                                    float *__restrict__ part) {
@@ -387,20 +393,47 @@ __global__ __launch_bounds__(ROWS_WAVES * 64) void attn_rows_kernel(Batch b, int
     const int page0 = t_begin * ATT_TILE / VF_TILE;
     int page_v = 0;
     if (s.block_table) page_v = s.block_table[min(page0 + lane, (tiles * ATT_TILE - 1) / VF_TILE)];
-    AttTile<HD> tile;
-#pragma unroll 1
-    for (int t = t_begin + wave; t < t_end; t += ROWS_WAVES) {
-        const int t0 = t * ATT_TILE;
-        const int pi = t0 / VF_TILE - page0;  // the same for the whole wavefront
+    auto request = [&](AttTile<HD> &tile, int t) {
+        const int t0 = min(t, t_end - 1) * ATT_TILE;  // past the end: the part's last tile again, not used
+        const int pi = t0 / VF_TILE - page0;          // the same for the whole wavefront
         const int page = !s.block_table ? t0 / VF_TILE
                          : pi < 64      ? __builtin_amdgcn_readlane(page_v, pi)
                                         : __builtin_amdgcn_readfirstlane(kv_page(s, t0));
-        tile.template load_page<false>(s, layer, hkv, kvh, t, page, lane);
+        tile.template load_page<false>(s, layer, hkv, kvh, t0 / ATT_TILE, page, lane);
+    };
+    auto work = [&](AttTile<HD> &tile, int t) {
+        const int t0 = t * ATT_TILE;
         tile.mask_values(t0, kmax, lane);
 #pragma unroll
         for (int c = 0; c < ROWS_QB; ++c)
             if (t0 <= blk_last[c]) att_tile_update<HD>(st[c], qf[c], tile, t0, last_key[c], ATT_NO_TREE, 0, scale_log2e, lane);
+    };
+#if ROWS_PREFETCH
+    // a wavefront's next tile is requested before it works on the current one
+    AttTile<HD> ta, tb;
+    int t = t_begin + wave;
+    if (t < t_end) {
+        request(ta, t);
+#pragma unroll 1
+        for (;;) {
+            request(tb, t + ROWS_WAVES);
+            work(ta, t);
+            t += ROWS_WAVES;
+            if (t >= t_end) break;
+            request(ta, t + ROWS_WAVES);
+            work(tb, t);
+            t += ROWS_WAVES;
+            if (t >= t_end) break;
+        }
     }
+#else
+    AttTile<HD> tile;
+#pragma unroll 1
+    for (int t = t_begin + wave; t < t_end; t += ROWS_WAVES) {
+        request(tile, t);
+        work(tile, t);
+    }
+#endif
     // merge of the eight wavefronts, one item block at a time: thread (db = wave, lane) owns
     // O^T[d = 16*db + 4*g4 + j][item l15]; HD = 64 leaves wavefronts 4..7 idle here
 #pragma unroll

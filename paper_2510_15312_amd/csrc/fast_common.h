@@ -156,15 +156,18 @@ __device__ inline void epi_qkv(const FastGemm &g, const Batch &b, int row, int n
         const float c1 = g.cosv[(size_t)pos * half + i0 + 1], s1 = g.sinv[(size_t)pos * half + i0 + 1];
         const float a0 = v[0] * c0 - v[1] * s0, b0 = v[1] * c0 + v[0] * s0;
         const float a1 = v[2] * c1 - v[3] * s1, b1 = v[3] * c1 + v[2] * s1;
-        bf16_t *dst;
+        // i0 is even: elements i0, i0 + 1 are neighbours in either layout, 4-byte aligned
+        bf16_t *d0, *d1;
         if (head < g.hq) {
-            dst = g.q + ((size_t)row * g.hq + head) * hd;
+            d0 = g.q + ((size_t)row * g.hq + head) * hd + i0;
+            d1 = d0 + half;
         } else {
             const int page = kv_page(s, slot), tin = slot % VF_TILE;
-            dst = kv + kv_k_index(g.layer, s.n_pages, page, g.hkv, head - g.hq, tin, 0, hd);
+            d0 = kv + kv_k_index(g.layer, s.n_pages, page, g.hkv, head - g.hq, tin, i0, hd);
+            d1 = kv + kv_k_index(g.layer, s.n_pages, page, g.hkv, head - g.hq, tin, i0 + half, hd);
         }
-        st_u32<COH>(dst + i0, pack2_bf16(a0, a1));          // i0 is even: 4-byte aligned
-        st_u32<COH>(dst + i0 + half, pack2_bf16(b0, b1));
+        st_u32<COH>(d0, pack2_bf16(a0, a1));
+        st_u32<COH>(d1, pack2_bf16(b0, b1));
     } else {
         const int vh = head - g.hq - g.hkv;
         const int page = kv_page(s, slot), tin = slot % VF_TILE;
@@ -398,20 +401,22 @@ template <int HD> struct AttTile {
     // page: the cache page of tile t, for a caller that has looked it up already
     template <bool coh>
     __device__ __forceinline__ void load_page(const SeqDesc &s, int layer, int hkv, int kvh, int t, int page, int lane) {
-        const int g4 = lane >> 4, l15 = lane & 15;
-        const int krow = 8 * (l15 >> 2) + (l15 & 3);
+        // the cache keeps a tile's fragments in operand order: fragment f of the tile is the kilobyte at
+        // 512 * f elements, a lane's share the 16 bytes at 8 * lane
         const bf16_t *kv = reinterpret_cast<const bf16_t *>(s.kv);
         const int t0 = t * ATT_TILE, tin = t0 % VF_TILE;
+        const bf16_t *kb = kv + kv_k_index(layer, s.n_pages, page, hkv, kvh, tin, 0, HD) + lane * 8;
+        const bf16_t *vb = kv + kv_v_index(layer, s.n_pages, page, hkv, kvh, tin, 0, HD) + lane * 8;
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int kd = 0; kd < HD / 32; ++kd) {
-                const bf16_t *kp = kv + kv_k_index(layer, s.n_pages, page, hkv, kvh, tin + krow + 4 * h, kd * 32 + g4 * 8, HD);
+                const bf16_t *kp = kb + (h * (HD / 32) + kd) * 512;
                 kf[h][kd] = coh ? __builtin_bit_cast(bf16x8, load_coherent16(kp)) : *reinterpret_cast<const bf16x8 *>(kp);
             }
 #pragma unroll
         for (int db = 0; db < HD / 16; ++db) {
-            const bf16_t *vp = kv + kv_v_index(layer, s.n_pages, page, hkv, kvh, tin + g4 * 8, db * 16 + l15, HD);
+            const bf16_t *vp = vb + db * 512;
             vf[db] = coh ? __builtin_bit_cast(bf16x8, load_coherent16(vp)) : *reinterpret_cast<const bf16x8 *>(vp);
         }
     }

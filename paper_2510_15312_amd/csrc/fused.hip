@@ -300,10 +300,17 @@ __device__ __forceinline__ void epi_qkv_pre(const FastGemm &g, const FusedShared
         const float c0 = pre.v[0], s0 = pre.v[1], c1 = pre.v[2], s1 = pre.v[3];
         const float a0 = v[0] * c0 - v[1] * s0, b0 = v[1] * c0 + v[0] * s0;
         const float a1 = v[2] * c1 - v[3] * s1, b1 = v[3] * c1 + v[2] * s1;
-        bf16_t *dst = head < g.hq ? g.q + ((size_t)row * g.hq + head) * hd
-                                  : rm.kv + kv_k_index(g.layer, rm.n_pages, rm.page, g.hkv, head - g.hq, rm.tin, 0, hd);
-        st_u32<true>(dst + i0, pack2_bf16(a0, a1));          // i0 is even: 4-byte aligned
-        st_u32<true>(dst + i0 + half, pack2_bf16(b0, b1));
+        // i0 is even: elements i0, i0 + 1 are neighbours in either layout, 4-byte aligned
+        bf16_t *d0, *d1;
+        if (head < g.hq) {
+            d0 = g.q + ((size_t)row * g.hq + head) * hd + i0;
+            d1 = d0 + half;
+        } else {
+            d0 = rm.kv + kv_k_index(g.layer, rm.n_pages, rm.page, g.hkv, head - g.hq, rm.tin, i0, hd);
+            d1 = rm.kv + kv_k_index(g.layer, rm.n_pages, rm.page, g.hkv, head - g.hq, rm.tin, i0 + half, hd);
+        }
+        st_u32<true>(d0, pack2_bf16(a0, a1));
+        st_u32<true>(d1, pack2_bf16(b0, b1));
     } else {
         const int vh = head - g.hq - g.hkv;
         for (int i = 0; i < 4; ++i) {

@@ -180,14 +180,26 @@ template <typename T> __device__ inline size_t w_index(int n, int k, int K);
 template <> __device__ inline size_t w_index<float>(int n, int k, int K) { return (size_t)n * K + k; }
 template <> __device__ inline size_t w_index<bf16_t>(int n, int k, int K) { return wfrag_index(n, k, K); }
 
-// KV pool: per layer and page, K as [Hkv][64][hd] then V transposed as [Hkv][hd][64].
+// KV pool: per layer and 64-token page, the K blocks of the kv heads, then their V blocks, 64 * hd
+// elements each, stored in the order the attention MFMAs read them, so that a wavefront's load of one
+// operand fragment is one contiguous kilobyte (lane l reads 16 bytes at 16 * l):
+//   K: [32-key tile][16-key half h][32-wide depth block kd][g4][l15][8]   key  = 8 * (l15 >> 2) + (l15 & 3) + 4 * h
+//                                                                         d    = 32 * kd + 8 * g4 + j
+//   V: [32-key tile][16-wide depth block db][g4][l15][8]                  key  = 8 * g4 + j,  d = 16 * db + l15
+// (lane = 16 * g4 + l15; a K row's eight-element groups and a V row's eight-key groups stay contiguous).
 __host__ __device__ inline size_t kv_k_index(int layer, int n_pages, int page, int hkv, int head, int tin,
                                               int d, int hd) {
-    return ((((size_t)layer * n_pages + page) * 2 * hkv + head) * VF_TILE + tin) * hd + d;
+    const int key = tin % 32, h = (key % 8) / 4, l15 = (key / 8) * 4 + key % 4;
+    const int frag = ((tin / 32) * 2 + h) * (hd / 32) + d / 32;
+    return (((size_t)layer * n_pages + page) * 2 * hkv + head) * VF_TILE * hd +
+           (size_t)((frag * 4 + (d % 32) / 8) * 16 + l15) * 8 + d % 8;
 }
 __host__ __device__ inline size_t kv_v_index(int layer, int n_pages, int page, int hkv, int head, int tin,
                                               int d, int hd) {
-    return ((((size_t)layer * n_pages + page) * 2 * hkv + hkv + head) * hd + d) * VF_TILE + tin;
+    const int key = tin % 32;
+    const int frag = (tin / 32) * (hd / 16) + d / 16;
+    return (((size_t)layer * n_pages + page) * 2 * hkv + hkv + head) * VF_TILE * hd +
+           (size_t)((frag * 4 + key / 8) * 16 + d % 16) * 8 + key % 8;
 }
 __device__ inline int kv_page(const SeqDesc &s, int t) {
     int tile = t / VF_TILE;
