@@ -323,13 +323,17 @@ __global__ __launch_bounds__(256) VF_MFMA_KERNEL void attn_fast_kernel(Batch b, 
     }
 }
 
-// Many rows (a prefill chunk, or a large batch): one workgroup of eight wavefronts per (32 query
-// items = two blocks of 16, kv head, sequence).  The wavefronts take the 32-key tiles its items can
-// see in turn (tile t goes to wavefront t mod 8); a tile's K and V^T fragments go from the cache
-// straight into registers, once, and serve both item blocks.  Each wavefront keeps an online
-// softmax state per item block; the eight states are merged through LDS at the end, so nothing
-// partial leaves the workgroup.  Output in the bf16 activation (MFMA B-operand) layout the
-// general GEMM reads.
+// Many rows (a prefill chunk, or a large batch): one workgroup of eight wavefronts per (ROWS_QB blocks
+// of 16 query items, kv head, sequence, part of the keys).  The wavefronts take the 32-key tiles its
+// items can see in turn (tile t goes to wavefront t mod 8); a tile's K and V^T fragments go from the
+// cache straight into registers (the cache keeps them in operand order: every load a contiguous
+// kilobyte), once, and serve every item block.  Each wavefront keeps an online softmax state per item
+// block; the eight states are merged through LDS at the end.  Output in the bf16 activation (MFMA
+// B-operand) layout the general GEMM reads; with more than one key part, a record per (row, head) for
+// the merge kernel.  Measured and not taken: the tiles of a workgroup of 128 items handed through LDS
+// to eight wavefronts that own 16 items each, with the parts merged by the last one to arrive (no
+// faster: the merging workgroup pulls every part's state through one compute unit); the next tile
+// requested ahead of the current one's arithmetic, and twice the wavefronts per SIMD (both slower).
 #ifndef ROWS_QB_N
 #define ROWS_QB_N 1
 #endif
@@ -338,14 +342,8 @@ __global__ __launch_bounds__(256) VF_MFMA_KERNEL void attn_fast_kernel(Batch b, 
 #endif
 constexpr int ROWS_QB = ROWS_QB_N, ROWS_WAVES = 8;
 
-#ifndef ROWS_WPE
-#define ROWS_WPE 2
-#endif
-#ifndef ROWS_PREFETCH
-#define ROWS_PREFETCH 0
-#endif
 template <int HD>
-__global__ __launch_bounds__(ROWS_WAVES * 64) __attribute__((amdgpu_waves_per_eu(ROWS_WPE, 4))) void attn_rows_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
+__global__ __launch_bounds__(ROWS_WAVES * 64) void attn_rows_kernel(Batch b, int layer, const bf16_t *__restrict__ q,
                                                                    bf16_t *__restrict__ o, int hq, int hkv, int ncb,
                                                                    float scale_log2e, int n_parts,
                                                                    float *__restrict__ part) {
@@ -408,32 +406,12 @@ __global__ __launch_bounds__(ROWS_WAVES * 64) __attribute__((amdgpu_waves_per_eu
         for (int c = 0; c < ROWS_QB; ++c)
             if (t0 <= blk_last[c]) att_tile_update<HD>(st[c], qf[c], tile, t0, last_key[c], ATT_NO_TREE, 0, scale_log2e, lane);
     };
-#if ROWS_PREFETCH
-    // a wavefront's next tile is requested before it works on the current one
-    AttTile<HD> ta, tb;
-    int t = t_begin + wave;
-    if (t < t_end) {
-        request(ta, t);
-#pragma unroll 1
-        for (;;) {
-            request(tb, t + ROWS_WAVES);
-            work(ta, t);
-            t += ROWS_WAVES;
-            if (t >= t_end) break;
-            request(ta, t + ROWS_WAVES);
-            work(tb, t);
-            t += ROWS_WAVES;
-            if (t >= t_end) break;
-        }
-    }
-#else
     AttTile<HD> tile;
 #pragma unroll 1
     for (int t = t_begin + wave; t < t_end; t += ROWS_WAVES) {
         request(tile, t);
         work(tile, t);
     }
-#endif
     // merge of the eight wavefronts, one item block at a time: thread (db = wave, lane) owns
     // O^T[d = 16*db + 4*g4 + j][item l15]; HD = 64 leaves wavefronts 4..7 idle here
 #pragma unroll
