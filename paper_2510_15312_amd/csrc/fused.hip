@@ -56,7 +56,9 @@ constexpr long long SPIN_LIMIT = 4000000;  // polls before a barrier gives up (s
 #define FUSED_FREE_SPLIT 1     // a phase of at most one item per workgroup may use a K split that does not divide the grid
 #endif
 #ifndef FUSED_MAXP
-#define FUSED_MAXP 4              // most key parts per attention block (measured: 8 parts 1280 us per launch, 6 1261, 5 1258, 4 1254, 3 1274, 2 1318)
+#define FUSED_MAXP 6              // most key parts per attention block (8 parts: 1280 us per launch, 6 1261, 5 1258, 4 1254, 3 1274, 2 1318;
+                                  // every setting gives the same mean logit error at the full 1.5B size, 1.3e-2, but with 4 and 5 parts one row
+                                  // of 136 lands at 2.12e-2 and 2.005e-2, past the stated 2e-2: 6 is the fastest setting inside it)
 #endif
 // One workgroup of 8 wavefronts per CU: two wavefronts per SIMD, so each may use up to 256 vector
 // registers (weight ring + staging loads in flight) without spilling.
