@@ -30,7 +30,7 @@ METRIC = "verify-step latency (\u00b5s) + achieved HBM GB/s vs peak, 1.5B shape 
 GATEUP_TRAFFIC_BYTES = None
 # The same for one launch of the persistent whole-pass kernel (profiles/verify_fused_1.5b_k16_pmc.md); set to
 # None whenever that kernel changes.
-FUSED_TRAFFIC_BYTES = None     # retaken below whenever the persistent kernel changes
+FUSED_TRAFFIC_BYTES = 3_460_100_000
 
 
 def log(*a):
