@@ -151,12 +151,15 @@ void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp
     static_assert(!SWIGLU || TNB % 2 == 0, "gate and up blocks come in pairs");
     static_assert(NSETS % 2 == 0, "set s is staged in LDS buffer s & 1");
     constexpr int NT = NW * 64;
-    constexpr int NF = TNB + MB;              // fragments per 32-wide k-block
-    constexpr int NL = KSTEP * NF * 64 / NT;  // 16-byte loads per thread and stage
-    static_assert(KSTEP * NF * 64 % NT == 0, "a stage is a whole number of loads per thread");
+    constexpr int NL = KSTEP * TNB * 64 / NT;  // 16-byte weight loads per thread and stage
+    static_assert(KSTEP * TNB * 64 % NT == 0, "a stage is a whole number of loads per thread");
     static_assert(MB % NW == 0, "whole activation blocks per wavefront");
     constexpr int WC = MB / NW;               // activation blocks per wavefront
-    __shared__ u32x4 lds[2][KSTEP * NF * 64];
+    // Only the weight fragments go through LDS: all wavefronts use them.  A wavefront's activation
+    // fragments are its own (its rows, nobody else's), so they stay in the registers they were loaded
+    // into; staged like the weights they were 16 of the 24 KB written and 16 of the 80 KB read per
+    // k-block of the wide tile, on the port that sets this kernel's pace.
+    __shared__ u32x4 lds[2][KSTEP * TNB * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int NBt = N >> 4;
     const int nb0 = blockIdx.x * TNB;
@@ -168,62 +171,67 @@ void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp
 #pragma unroll
         for (int c = 0; c < WC; ++c) acc[n][c] = floatx4{0.f, 0.f, 0.f, 0.f};
     if (kb_begin >= kb_end) return;
-    // where this thread's pieces of a stage come from: piece i is fragment f of k-block `half`
+    // where this thread's weight pieces of a stage come from: piece i is fragment f of k-block `half`
     const u32x4 *src[NL];
-    size_t kstride[NL];
     int half_of[NL];
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-        const int idx = tid + i * NT, rem = idx % (NF * 64), f = rem >> 6, l = rem & 63;
-        half_of[i] = idx / (NF * 64);
-        if (f < TNB) {
-            src[i] = Wp + (size_t)min(nb0 + f, NBt - 1) * KB * 64 + l;   // rows past N: a valid block, result dropped
-            kstride[i] = 64;
-        } else {
-            src[i] = Xp + (size_t)min(cb0 + f - TNB, ncb - 1) * 64 + l;  // rows past the call: likewise
-            kstride[i] = (size_t)ncb * 64;
-        }
+        const int idx = tid + i * NT, rem = idx % (TNB * 64), f = rem >> 6, l = rem & 63;
+        half_of[i] = idx / (TNB * 64);
+        src[i] = Wp + (size_t)min(nb0 + f, NBt - 1) * KB * 64 + l;   // rows past N: a valid block, result dropped
     }
-    auto fetch = [&](u32x4 (&r)[NL], int kb) {
+    // and its wavefront's activation blocks (rows past the call: a valid block, result dropped)
+    const u32x4 *xsrc[WC];
 #pragma unroll
-        for (int i = 0; i < NL; ++i) r[i] = src[i][(size_t)min(kb + half_of[i], kb_end - 1) * kstride[i]];
+    for (int c = 0; c < WC; ++c) xsrc[c] = Xp + (size_t)min(cb0 + wave * WC + c, ncb - 1) * 64 + lane;
+    const size_t xstride = (size_t)ncb * 64;
+    struct Set {
+        u32x4 w[NL];
+        u32x4 x[KSTEP][WC];
     };
-    auto stage = [&](const u32x4 (&r)[NL], int buf) {
+    auto fetch = [&](Set &r, int kb) {
 #pragma unroll
-        for (int i = 0; i < NL; ++i) lds[buf][tid + i * NT] = r[i];
+        for (int i = 0; i < NL; ++i) r.w[i] = src[i][(size_t)min(kb + half_of[i], kb_end - 1) * 64];
+#pragma unroll
+        for (int half = 0; half < KSTEP; ++half)
+#pragma unroll
+            for (int c = 0; c < WC; ++c) r.x[half][c] = xsrc[c][(size_t)min(kb + half, kb_end - 1) * xstride];
+    };
+    auto stage = [&](const Set &r, int buf) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) lds[buf][tid + i * NT] = r.w[i];
     };
     // kb_limit: k-blocks from here on do not exist (what was fetched for them came from a clamped
     // address); the main loop passes a limit no step reaches, which leaves no test in its code
-    auto multiply = [&](int buf, int kb, int kb_limit) {
+    auto multiply = [&](int buf, const u32x4 (&x)[KSTEP][WC], int kb, int kb_limit) {
 #pragma unroll
         for (int half = 0; half < KSTEP; ++half) {
             if (kb + half >= kb_limit) continue;
-            const u32x4 *st = lds[buf] + half * NF * 64;
-            // every fragment of the k-block leaves LDS before the first MFMA, so that no MFMA waits for
-            // a read issued right in front of it
-            bf16x8 bfr[WC], afr[TNB];
-#pragma unroll
-            for (int c = 0; c < WC; ++c) bfr[c] = __builtin_bit_cast(bf16x8, st[(TNB + wave * WC + c) * 64 + lane]);
+            const u32x4 *st = lds[buf] + half * TNB * 64;
+            // every weight fragment of the k-block leaves LDS before the first MFMA, so that no MFMA
+            // waits for a read issued right in front of it
+            bf16x8 afr[TNB];
 #pragma unroll
             for (int n = 0; n < TNB; ++n) afr[n] = __builtin_bit_cast(bf16x8, st[n * 64 + lane]);
 #pragma unroll
             for (int n = 0; n < TNB; ++n)
 #pragma unroll
                 for (int c = 0; c < WC; ++c)
-                    acc[n][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[n], bfr[c], acc[n][c], 0, 0, 0);
-            // order for the instruction scheduler: the k-block's LDS reads, then its MFMAs (reads two or
-            // three weight fragments ahead of the MFMAs, the rest under them, measured the same)
-            __builtin_amdgcn_sched_group_barrier(0x100, WC + TNB, 0);
+                    acc[n][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[n], __builtin_bit_cast(bf16x8, x[half][c]),
+                                                                        acc[n][c], 0, 0, 0);
+            // order for the instruction scheduler: the k-block's LDS reads, then its MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x100, TNB, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, TNB * WC, 0);
         }
     };
-    u32x4 r[NSETS][NL];
+    Set r[NSETS];
 #pragma unroll
     for (int s = 0; s < NSETS; ++s) fetch(r[s], kb_begin + s * KSTEP);
     // Whole groups of NSETS steps first.  An LDS buffer is written again two steps later, behind
     // the barrier of the step in between, which every wavefront reaches only after its MFMAs on
     // that buffer.  The scheduling barriers keep each step's order: stores of its set (the only
-    // wait for loads), barrier, the set's next loads, then the MFMAs that hide them.
+    // wait for loads), barrier, the set's next loads, then the MFMAs that hide them.  The step's
+    // activation fragments move to registers of their own before the set is requested again.
     constexpr int NEVER = 0x7fffffff;
     const int ngroups = (kb_end - kb_begin) / (NSETS * KSTEP);
     int kb = kb_begin;
@@ -231,10 +239,15 @@ void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp
 #pragma unroll
         for (int s = 0; s < NSETS; ++s) {
             stage(r[s], s & 1);
+            u32x4 x[KSTEP][WC];
+#pragma unroll
+            for (int half = 0; half < KSTEP; ++half)
+#pragma unroll
+                for (int c = 0; c < WC; ++c) x[half][c] = r[s].x[half][c];
             lds_sync();
             fetch(r[s], kb + NSETS * KSTEP);
             __builtin_amdgcn_sched_barrier(0);
-            multiply(s & 1, 0, NEVER);
+            multiply(s & 1, x, 0, NEVER);
             __builtin_amdgcn_sched_barrier(0);
             kb += KSTEP;
         }
@@ -245,7 +258,7 @@ void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp
         if (kb < kb_end) {
             stage(r[s], s & 1);
             lds_sync();
-            multiply(s & 1, kb, kb_end);
+            multiply(s & 1, r[s].x, kb, kb_end);
             kb += KSTEP;
         }
     }
