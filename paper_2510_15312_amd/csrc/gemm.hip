@@ -132,8 +132,11 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) VF_MFMA_KERNEL void gemm_bf16_kern
 #ifndef ROWS_NW_WIDE
 #define ROWS_NW_WIDE 8
 #endif
+#ifndef ROWS_KSTEP_WIDE
+#define ROWS_KSTEP_WIDE 2
+#endif
 #ifndef ROWS_SETS_WIDE
-#define ROWS_SETS_WIDE 4
+#define ROWS_SETS_WIDE 2
 #endif
 #ifndef ROWS_NW_NARROW
 #define ROWS_NW_NARROW 4
@@ -204,24 +207,37 @@ void gemm_rows_kernel(const u32x4 *__restrict__ Wp, const u32x4 *__restrict__ Xp
     // kb_limit: k-blocks from here on do not exist (what was fetched for them came from a clamped
     // address); the main loop passes a limit no step reaches, which leaves no test in its code
     auto multiply = [&](int buf, const u32x4 (&x)[KSTEP][WC], int kb, int kb_limit) {
+        // The weight fragments of the step's first k-block leave LDS before its first MFMA; those of
+        // every further k-block are read under the MFMAs of the one before (one read, then the MFMAs
+        // of one weight block), so that only the first k-block of a step waits for LDS.
+        bf16x8 afr[2][TNB];
+        auto read = [&](int half) {
+            const u32x4 *st = lds[buf] + half * TNB * 64;
+#pragma unroll
+            for (int n = 0; n < TNB; ++n) afr[half & 1][n] = __builtin_bit_cast(bf16x8, st[n * 64 + lane]);
+        };
+        read(0);
+        __builtin_amdgcn_sched_group_barrier(0x100, TNB, 0);
 #pragma unroll
         for (int half = 0; half < KSTEP; ++half) {
-            if (kb + half >= kb_limit) continue;
-            const u32x4 *st = lds[buf] + half * TNB * 64;
-            // every weight fragment of the k-block leaves LDS before the first MFMA, so that no MFMA
-            // waits for a read issued right in front of it
-            bf16x8 afr[TNB];
+            if (half + 1 < KSTEP) read(half + 1);
+            if (kb + half < kb_limit) {
 #pragma unroll
-            for (int n = 0; n < TNB; ++n) afr[n] = __builtin_bit_cast(bf16x8, st[n * 64 + lane]);
+                for (int n = 0; n < TNB; ++n)
 #pragma unroll
-            for (int n = 0; n < TNB; ++n)
+                    for (int c = 0; c < WC; ++c)
+                        acc[n][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[half & 1][n], __builtin_bit_cast(bf16x8, x[half][c]),
+                                                                            acc[n][c], 0, 0, 0);
+            }
+            if (half + 1 < KSTEP) {
 #pragma unroll
-                for (int c = 0; c < WC; ++c)
-                    acc[n][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[n], __builtin_bit_cast(bf16x8, x[half][c]),
-                                                                        acc[n][c], 0, 0, 0);
-            // order for the instruction scheduler: the k-block's LDS reads, then its MFMAs
-            __builtin_amdgcn_sched_group_barrier(0x100, TNB, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, TNB * WC, 0);
+                for (int n = 0; n < TNB; ++n) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, WC, 0);
+                }
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x008, TNB * WC, 0);
+            }
         }
     };
     Set r[NSETS];
@@ -438,13 +454,13 @@ int vf_launch_gemm(const vf_model *m, const void *W, const void *X, float *part,
             return vf_fail(VF_ERR_ARG, "the fused epilogues take no K split");
         if (plan.topk) {
             if (plan.topk > VF_TOPK_MAX || !plan.topk_ids) return vf_fail(VF_ERR_ARG, "top-k epilogue: k %d", plan.topk);
-            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, 1, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_TOPK>, ROWS_NW_WIDE);
+            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, ROWS_KSTEP_WIDE, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_TOPK>, ROWS_NW_WIDE);
             else go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, ROWS_EPI_TOPK>, ROWS_NW_NARROW);
         } else if (plan.swiglu) {
-            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, 1, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_SWIGLU>, ROWS_NW_WIDE);
+            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, ROWS_KSTEP_WIDE, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_SWIGLU>, ROWS_NW_WIDE);
             else go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, ROWS_EPI_SWIGLU>, ROWS_NW_NARROW);
         } else if (plan.tnb == 8) {
-            go(gemm_rows_kernel<8, 16, 1, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_PARTIAL>, ROWS_NW_WIDE);
+            go(gemm_rows_kernel<8, 16, ROWS_KSTEP_WIDE, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_PARTIAL>, ROWS_NW_WIDE);
         } else {
             go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, ROWS_EPI_PARTIAL>, ROWS_NW_NARROW);
         }
