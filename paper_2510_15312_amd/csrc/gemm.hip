@@ -118,6 +118,11 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) VF_MFMA_KERNEL void gemm_bf16_kern
 // through NSETS register sets; they are never predicated (addresses past the end are clamped and
 // what they fetch is not used), so the wait before a set's LDS stores leaves the other sets' loads
 // in flight, and the barrier orders LDS traffic only.
+// Measured on the gate/up GEMM of the 1.5B shape (256 x 17920 x 1536, 28 us): with the MFMAs taken out
+// it takes 20 us, with the loop's global loads 23 us, with the LDS reads 21 us: three costs of 5 to 8 us
+// that two lock-stepped wavefronts per SIMD overlap poorly, over 7 us of launch, first loads and
+// epilogue.  128-row tiles (twice the workgroups), deeper register sets and streaming loads all left
+// the time where it was.
 //
 // EPI = ROWS_EPI_TOPK (output head, no K split): instead of the logits the kernel writes, per row and
 // column tile, the `topk` largest of the tile's TNB * 16 values with their column ids, in falling
@@ -129,6 +134,9 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) VF_MFMA_KERNEL void gemm_bf16_kern
 // a = bf16(silu(gate) * up) in activation layout.  Weight block 2j holds gate columns 16j.. and
 // block 2j+1 the matching up columns, so a pair of accumulators of one lane holds both factors.
 // wavefronts per workgroup and register sets of the two tile shapes
+#ifndef ROWS_MB_WIDE
+#define ROWS_MB_WIDE 16          // 16-row blocks of the wide tile
+#endif
 #ifndef ROWS_NW_WIDE
 #define ROWS_NW_WIDE 8
 #endif
@@ -416,7 +424,7 @@ GemmPlan vf_gemm_plan(const vf_model *m, int N, int K, int rows, int force_singl
     if (rows > 64 && m->fast_path) {
         // many-row kernel: 256 rows x 8 weight blocks per workgroup for wide matrices, 128 x 4 for narrow ones
         p.tnb = NBt >= 1024 ? 8 : 4;
-        const int groups = (NBt + p.tnb - 1) / p.tnb * (p.tnb == 8 ? (rows + 255) / 256 : (rows + 127) / 128);
+        const int groups = (NBt + p.tnb - 1) / p.tnb * (p.tnb == 8 ? (rows + 16 * ROWS_MB_WIDE - 1) / (16 * ROWS_MB_WIDE) : (rows + 127) / 128);
         int ks = 1;
         if (!force_single)
             while (groups * ks < 384 && KB / (ks * 2) >= 8 &&
@@ -444,7 +452,7 @@ int vf_launch_gemm(const vf_model *m, const void *W, const void *X, float *part,
         const int KB = K >> 5, NBt = N >> 4, ncb = (rows_total + 15) >> 4;
         const int kbps = (KB + plan.ks - 1) / plan.ks;
         const int cbs = ((row_hi + 15) >> 4) - (row_lo >> 4);
-        const int mb = plan.tnb == 8 ? 16 : 8;
+        const int mb = plan.tnb == 8 ? ROWS_MB_WIDE : 8;
         dim3 grid((NBt + plan.tnb - 1) / plan.tnb, plan.ks, (cbs + mb - 1) / mb);
         auto go = [&](auto kern, int nw) {
             hipLaunchKernelGGL(kern, grid, dim3(nw * 64), 0, st, (const u32x4 *)W, (const u32x4 *)X, part, N, KB, ncb,
@@ -454,13 +462,13 @@ int vf_launch_gemm(const vf_model *m, const void *W, const void *X, float *part,
             return vf_fail(VF_ERR_ARG, "the fused epilogues take no K split");
         if (plan.topk) {
             if (plan.topk > VF_TOPK_MAX || !plan.topk_ids) return vf_fail(VF_ERR_ARG, "top-k epilogue: k %d", plan.topk);
-            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, ROWS_KSTEP_WIDE, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_TOPK>, ROWS_NW_WIDE);
+            if (plan.tnb == 8) go(gemm_rows_kernel<8, ROWS_MB_WIDE, ROWS_KSTEP_WIDE, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_TOPK>, ROWS_NW_WIDE);
             else go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, ROWS_EPI_TOPK>, ROWS_NW_NARROW);
         } else if (plan.swiglu) {
-            if (plan.tnb == 8) go(gemm_rows_kernel<8, 16, ROWS_KSTEP_WIDE, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_SWIGLU>, ROWS_NW_WIDE);
+            if (plan.tnb == 8) go(gemm_rows_kernel<8, ROWS_MB_WIDE, ROWS_KSTEP_WIDE, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_SWIGLU>, ROWS_NW_WIDE);
             else go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, ROWS_EPI_SWIGLU>, ROWS_NW_NARROW);
         } else if (plan.tnb == 8) {
-            go(gemm_rows_kernel<8, 16, ROWS_KSTEP_WIDE, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_PARTIAL>, ROWS_NW_WIDE);
+            go(gemm_rows_kernel<8, ROWS_MB_WIDE, ROWS_KSTEP_WIDE, ROWS_NW_WIDE, ROWS_SETS_WIDE, ROWS_EPI_PARTIAL>, ROWS_NW_WIDE);
         } else {
             go(gemm_rows_kernel<4, 8, 2, ROWS_NW_NARROW, ROWS_SETS_NARROW, ROWS_EPI_PARTIAL>, ROWS_NW_NARROW);
         }
