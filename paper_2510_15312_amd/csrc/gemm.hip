@@ -121,8 +121,10 @@ __global__ __launch_bounds__(GEMM_WAVES * 64) VF_MFMA_KERNEL void gemm_bf16_kern
 // Measured on the gate/up GEMM of the 1.5B shape (256 x 17920 x 1536, 28 us): with the MFMAs taken out
 // it takes 20 us, with the loop's global loads 23 us, with the LDS reads 21 us: three costs of 5 to 8 us
 // that two lock-stepped wavefronts per SIMD overlap poorly, over 7 us of launch, first loads and
-// epilogue.  128-row tiles (twice the workgroups), deeper register sets and streaming loads all left
-// the time where it was.
+// epilogue.  128-row tiles (twice the workgroups), deeper register sets, streaming loads, and a loop
+// with three LDS buffers in which a step's LDS reads, LDS writes and memory requests are all issued
+// ahead of its MFMAs (27 us) left the time where it was: the three costs add up whatever the order of
+// issue, which points at the register file's ports rather than at the pipes.
 //
 // EPI = ROWS_EPI_TOPK (output head, no K split): instead of the logits the kernel writes, per row and
 // column tile, the `topk` largest of the tile's TNB * 16 values with their column ids, in falling
