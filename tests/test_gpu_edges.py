@@ -164,3 +164,35 @@ def test_qkv_bias_and_sampled_first_token(dtype):
     err = rel_inf(out.cpu().numpy(), z).max()
     print(f"qkv bias, {dtype}: verify error {err:.3e}", flush=True)
     assert err < tol
+
+
+@pytest.mark.parametrize("name", ["0.5b_k8", "1.5b_k16"])
+def test_kv_cache_layout_round_trip(name):
+    """Every (position, kv head, feature) of a cache has a place of its own: K and V rows written at
+    arbitrary offsets of a paged cache (head_dim 64 and 128) come back exactly, and rows written
+    later leave the earlier ones alone.  The cache keeps its pages in the order the attention MFMAs
+    consume them, so this is a test of that index map, not of a copy."""
+    cfg = wl.scaled(C[name], n_layers=2, vocab=512)
+    s = wl.streams(cfg)
+    wd = wl.make_weights(cfg, s.weights)
+    model = vf.vf_model_create(vf.config_from(cfg, 64, 512), vf.upload_weights(wd, cfg.dtype, DEV), DEV)
+    n_pages = 5
+    pool = torch.zeros(vf.vf_kv_bytes(model, 64, n_pages), dtype=torch.uint8, device=DEV)
+    seq = vf.vf_seq_create(model, 4 * 64, pool, i32([3, 0, 4, 1]), DEV)
+    rng = np.random.default_rng(7)
+    shape = (4 * 64, cfg.n_kv_heads, cfg.head_dim)
+    want = {}
+    for layer in range(cfg.n_layers):
+        k = rng.standard_normal(shape).astype(np.float32)
+        v = rng.standard_normal(shape).astype(np.float32)
+        k, v = (torch.tensor(a).to(torch.bfloat16).float().numpy() for a in (k, v))   # values the cache can hold
+        want[layer] = (k, v)
+        for t0, n in ((0, 37), (37, 1), (38, 90), (128, 128)):                       # ragged pieces, page borders inside
+            vf.vf_kv_write(model, seq, layer, t0, f32(k[t0:t0 + n]), f32(v[t0:t0 + n]))
+    torch.cuda.synchronize()
+    for layer in range(cfg.n_layers):
+        for t0, n in ((0, 256), (63, 2), (100, 57)):
+            kg, vg = vf.vf_kv_read(model, seq, layer, t0, n)
+            torch.cuda.synchronize()
+            assert np.array_equal(kg.cpu().numpy(), want[layer][0][t0:t0 + n])
+            assert np.array_equal(vg.cpu().numpy(), want[layer][1][t0:t0 + n])
