@@ -61,12 +61,15 @@ def _run_mix(cfg, mix, expect_fast, persistent=True, check_kv=False):
     dense_done = False
     for b in range(B):
         k = int(mix.k[b])
-        cont = plain_greedy(pair.spec, pair.ow, caches[b].clone(), pendings[b], k)
-        drafts = wl.inject_mismatch(cont, int(s.drafts.integers(1, k + 2)), cfg.vocab, s.drafts)
+        if k:
+            cont = plain_greedy(pair.spec, pair.ow, caches[b].clone(), pendings[b], k)
+            drafts = wl.inject_mismatch(cont, int(s.drafts.integers(1, k + 2)), cfg.vocab, s.drafts)
+        else:
+            drafts = np.zeros(0, dtype=np.int64)          # no drafts: the step is one plain decoding step
         q = u = None
         if mix.stochastic[b]:
             u = wl.make_uniforms(k + 1, s.uniforms)
-            if not dense_done:
+            if not dense_done and k:
                 qs = s.gumbel.dirichlet(np.full(cfg.vocab, 0.05), size=k).astype(np.float32)
                 qs[np.arange(k), drafts] += 0.5
                 q = (qs / qs.sum(-1, keepdims=True, dtype=np.float64)).astype(np.float32)
@@ -182,6 +185,20 @@ def test_small_paged_batch_through_the_persistent_kernel():
     mix = wl.rag_mix(cfg, wl.streams(cfg).mix, ctx_min=100, ctx_max=500)
     assert int(np.sum(mix.k + 1)) <= 32
     _run_mix(cfg, mix, expect_fast=True, persistent=True)
+
+
+@pytest.mark.parametrize("rows", [48, 49])
+def test_full_batch_at_the_row_limit_of_the_few_row_kernels(rows):
+    """As many sequences as a call may hold (VF_MAX_BATCH), half of them without any draft, with 48 rows
+    in all (the most the persistent kernel takes) and with 49 (the first call that goes to the kernels
+    for any row count): both against the oracle, sequence by sequence."""
+    B = vf.VF_MAX_BATCH
+    cfg = wl.scaled(C["1.5b_rag_mix"], n_layers=2, vocab=4096, ctx=120, batch=B, k=3)
+    mix = wl.rag_mix(cfg, wl.streams(cfg).mix, ctx_min=40, ctx_max=300)
+    with_draft = rows - B                                  # sequences with one draft; the others have none
+    mix.k = np.array([1] * with_draft + [0] * (B - with_draft))   # never more than the drafts the pages were sized for
+    assert int(np.sum(mix.k + 1)) == rows and len(mix.k) == B
+    _run_mix(cfg, mix, expect_fast=rows <= 48, persistent=True)
 
 
 def test_multi_row_verify_equals_single_row_decodes_on_the_gpu():
